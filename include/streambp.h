@@ -1,0 +1,221 @@
+/*
+ * libstreambp - StreamBP hot path for AMD MI355X (gfx950): the sequence-chunked,
+ * layer-wise exact backward pass of a decoder-only transformer.
+ *
+ * For every chunk of the sequence the library recomputes that chunk's forward
+ * and runs its backward; weight gradients, the prefix dK/dV and the input
+ * gradient accumulate across chunks, so full-sequence activations and logits are
+ * never stored (paper Sec. 3.1, Eq. 1: the full chain-rule product is the sum of
+ * the per-chunk products over any partition of the module's output).
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ *  - All tensor pointers are DEVICE pointers owned by the caller; config and
+ *    weight-table structs are HOST memory, read before the call returns.
+ *  - The library never allocates, frees or synchronises.  Work is enqueued on
+ *    `hip_stream` (a hipStream_t passed as void*; NULL = the default stream) and is
+ *    complete when that stream is.  Scratch memory comes from the caller through
+ *    `workspace`; the matching *_workspace_bytes() call gives the size needed.
+ *    Workspace must be 256-byte aligned.  Two calls may not share a workspace
+ *    unless they are ordered on one stream.
+ *  - Tensors are dense row-major.  Matrices are stored [out, in] (y = x W^T).
+ *  - `dtype` selects the storage type of activations and weights (fp32 or bf16);
+ *    arithmetic accumulates in fp32.  Weight-gradient accumulators, dK/dV and
+ *    the loss are always fp32.
+ *  - "+=" arguments are accumulated into (the caller zeroes them before the
+ *    first call - "initialised from zero", Sec. 3.2.1); "out" arguments are
+ *    overwritten.  Inputs are never modified.
+ *  - Return value: 0 on success; negative on error, in which case nothing has
+ *    been enqueued (except SBP_ERR_HIP, which can surface mid-sequence).
+ *    streambp_last_error() returns a thread-local message for the last failure.
+ *  - chunk need not divide seq_len (the last chunk is shorter); chunk >= seq_len
+ *    means a single chunk (Sec. 4.4, partition-size ablation).
+ */
+#ifndef STREAMBP_H
+#define STREAMBP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SBP_F32 = 0, SBP_BF16 = 1 };
+
+enum {
+  SBP_OK = 0,
+  SBP_ERR_NULL = -1,       /* a required pointer is NULL                        */
+  SBP_ERR_SHAPE = -2,      /* bad shape / config value                          */
+  SBP_ERR_UNSUPPORTED = -3,/* dtype / objective / alignment not supported       */
+  SBP_ERR_WORKSPACE = -4,  /* workspace too small or misaligned                 */
+  SBP_ERR_HIP = -5         /* HIP runtime error (see streambp_last_error)       */
+};
+
+enum { SBP_OBJ_SFT = 0, SBP_OBJ_GRPO = 1, SBP_OBJ_DPO = 2 };
+
+/* ---------------------------------------------------------------- layer -- */
+
+/* One pre-norm decoder layer (Sec. 3.2.2; the paper's display leaves out the
+ * norms, heads, residuals and W_o, which are present here):
+ *   a = RMSNorm(x; g1); q,k,v = a Wq^T, a Wk^T, a Wv^T; RoPE(q), RoPE(k)
+ *   o = causal softmax(q k^T / sqrt(head_dim)) v   (query head h uses KV head
+ *       h / (n_q_heads / n_kv_heads))
+ *   h1 = x + o Wo^T;  m = RMSNorm(h1; g2)
+ *   y = h1 + (silu(m Wgate^T) * (m Wup^T)) Wdown^T
+ * RoPE pairs element j with j + head_dim/2, angle (t + pos_offset) * rope_theta^(-2j/head_dim). */
+typedef struct {
+  int32_t dtype;        /* SBP_F32 or SBP_BF16: x, dy, dx, y and the weights  */
+  int32_t batch;        /* B independent sequences of equal length            */
+  int32_t seq_len;      /* T                                                  */
+  int32_t chunk;        /* c: rows of the output processed per partition      */
+  int32_t hidden;       /* d                                                  */
+  int32_t n_q_heads, n_kv_heads, head_dim;  /* head_dim even                  */
+  int32_t mlp_width;    /* F                                                  */
+  float rms_eps;        /* e.g. 1e-6                                          */
+  float rope_theta;     /* e.g. 1e4                                           */
+  int32_t pos_offset;   /* RoPE position of row 0                             */
+} sbp_layer_cfg;
+
+/* wq [Hq*dh, d]; wk, wv [Hkv*dh, d]; wo [d, Hq*dh]; wgate, wup [F, d];
+ * wdown [d, F]; g1, g2 [d].  Element type = cfg.dtype. */
+typedef struct {
+  const void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown, *g1, *g2;
+} sbp_layer_weights;
+
+/* Same shapes, fp32, accumulated into. */
+typedef struct {
+  float *wq, *wk, *wv, *wo, *wgate, *wup, *wdown, *g1, *g2;
+} sbp_layer_grads;
+
+/* Bytes of workspace streambp_layer_backward / streambp_layer_forward need for
+ * this config (0 if the config is invalid).  The figure is
+ *   alpha * min(chunk, T) + beta * T * n_kv_heads * head_dim + const:
+ * it has no term in T * mlp_width, T * hidden or T^2 (Sec. 3.2.2, memory
+ * efficiency: K and V are cached for the whole sequence, everything else is
+ * per chunk). */
+size_t streambp_layer_workspace_bytes(const sbp_layer_cfg *cfg);
+
+/* StreamBP of one layer (Sec. 3.2.2): K and V are computed once for the whole
+ * sequence and cached in the workspace; then for every chunk of rows the
+ * chunk's forward is recomputed against the prefix K/V only and its backward
+ * is run, with dW += per-chunk term (Eq. 1), dK/dV of the prefix accumulated in
+ * fp32 in the workspace and dx rows written as soon as they are final.
+ *   x  [B, T, d] in  : layer input (the gradient checkpoint)
+ *   dy [B, T, d] in  : gradient of the loss wrt the layer output
+ *   dx [B, T, d] out : gradient wrt the layer input (may not alias x or dy)
+ *   dw          +=   : weight gradients, summed over chunks and sequences */
+int32_t streambp_layer_backward(const sbp_layer_cfg *cfg, const sbp_layer_weights *w,
+                                const void *x, const void *dy, void *dx,
+                                const sbp_layer_grads *dw,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Chunked forward of the same layer with the same kernels (used to produce the
+ * per-layer checkpoints of a stack): y [B, T, d] out. */
+int32_t streambp_layer_forward(const sbp_layer_cfg *cfg, const sbp_layer_weights *w,
+                               const void *x, void *y,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* --------------------------------------------------------------- LM head -- */
+
+/* logits = h W^T (Sec. 3.2.1); the objective is a sum of independent
+ * per-position terms, so logits exist only for one chunk of rows at a time. */
+typedef struct {
+  int32_t dtype;        /* SBP_F32 or SBP_BF16: h, w, dh                       */
+  int32_t batch, seq_len;
+  int32_t chunk;        /* rows of logits alive at once                        */
+  int32_t hidden, vocab;
+  int32_t objective;    /* SBP_OBJ_SFT, SBP_OBJ_GRPO or SBP_OBJ_DPO            */
+  float loss_scale;     /* SFT: L = -loss_scale * sum_active log p(target).
+                           1 = the paper's un-normalised sum; 1/n_active = mean */
+  float clip_eps;       /* GRPO: ratio clip                                    */
+  float kl_beta;        /* GRPO: weight of the KL term; DPO: beta              */
+  int32_t kl_mode;      /* GRPO: 0 = log(pi/pi_ref) (the paper's compact form),
+                           1 = exp(ref-logp) - (ref-logp) - 1                  */
+} sbp_head_cfg;
+
+size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg *cfg);
+
+/* StreamBP of the LM head + objective (Sec. 3.2.1).  Per chunk of rows:
+ * logits chunk -> row log-sum-exp and log p(target) -> dz = coef * (onehot -
+ * softmax) -> dh rows = dz W, dw += dz^T h.
+ *   w [V, d] in; h [B, T, d] in
+ *   targets [B, T] int32 in: id the row must predict (labels already shifted
+ *       by the caller); negative = ignored row (its dh row is exactly zero)
+ *   old_logp [B, T] fp32 or NULL (GRPO; NULL = on-policy, ratio 1)
+ *   ref_logp [B, T] fp32 (GRPO, DPO; NULL for SFT)
+ *   advantages [B] fp32 (GRPO; NULL otherwise)
+ *   dh [B, T, d] out (cfg.dtype);  dw [V, d] fp32 +=
+ *   loss: device fp32 scalar, +=.   n_active: device int64 scalar, out.
+ * GRPO: L = -(1/B) sum_j (1/T_o,j) sum_{t active in j} f(j,t) with T_o,j the
+ * number of active rows of sequence j.
+ * DPO (batch must be 2: row 0 chosen, row 1 rejected): gradients are first
+ * accumulated with coefficient +-beta, then scaled in place by
+ * sigmoid(beta*ell) - 1 once ell is complete, as the paper prescribes; dw must
+ * therefore hold only this call's contribution (zero on entry). */
+int32_t streambp_lmhead_ce_backward(const sbp_head_cfg *cfg, const void *w, const void *h,
+                                    const int32_t *targets, const float *old_logp,
+                                    const float *ref_logp, const float *advantages,
+                                    void *dh, float *dw, float *loss, int64_t *n_active,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ------------------------------------------------------- chunk attention -- */
+
+/* Causal attention of one chunk of queries against the cached prefix
+ * (Sec. 3.2.2, partitioned attention; Property 3.1).  Query row t sits at global
+ * position q_start + t and sees keys 0 .. q_start + t. */
+typedef struct {
+  int32_t dtype;                 /* q, k, v, o, d_o, dq                       */
+  int32_t n_q_heads, n_kv_heads, head_dim;
+  int32_t q_start;               /* s: global position of the chunk's row 0   */
+  int32_t q_len;                 /* c                                         */
+  float scale;                   /* usually 1/sqrt(head_dim)                  */
+} sbp_attn_cfg;
+
+size_t streambp_attn_workspace_bytes(const sbp_attn_cfg *cfg);
+
+/* q [c, Hq, dh] (rotated); k, v [>= s + c, Hkv, dh]; o [c, Hq, dh] out;
+ * lse [Hq, c] fp32 out (natural log-sum-exp of the scaled masked scores). */
+int32_t streambp_attn_chunk_forward(const sbp_attn_cfg *cfg, const void *q, const void *k,
+                                    const void *v, void *o, float *lse, void *hip_stream);
+
+/* d_o [c, Hq, dh] in; dq [c, Hq, dh] out; dk, dv [>= s + c, Hkv, dh] fp32 +=
+ * (rows 0 .. s + c - 1 are touched; contributions of the query heads that
+ * share a KV head are summed). */
+int32_t streambp_attn_chunk_backward(const sbp_attn_cfg *cfg, const void *q, const void *k,
+                                     const void *v, const void *o, const float *lse,
+                                     const void *d_o, void *dq, float *dk, float *dv,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ------------------------------------------------ stack glue (Sec. 2, 3.1) -- */
+
+/* Final RMSNorm between the layer stack and the LM head, and the embedding
+ * lookup in front of the stack: rows x [n, d] (dtype), gain g [d].
+ * forward:  y = RMSNorm(x; g).   backward: dx out (dtype), dg fp32 +=; needs
+ * streambp_rmsnorm_workspace_bytes(n_rows, hidden) bytes of workspace. */
+size_t streambp_rmsnorm_workspace_bytes(int64_t n_rows, int32_t hidden);
+int32_t streambp_rmsnorm_forward(int32_t dtype, int64_t n_rows, int32_t hidden, float eps,
+                                 const void *x, const void *g, void *y, void *hip_stream);
+int32_t streambp_rmsnorm_backward(int32_t dtype, int64_t n_rows, int32_t hidden, float eps,
+                                  const void *x, const void *g, const void *dy, void *dx,
+                                  float *dg, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+/* x[t] = emb[ids[t]] ; demb[ids[t]] += dx[t] (fp32 accumulators, atomic adds). */
+int32_t streambp_embedding_forward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab,
+                                   const int32_t *ids, const void *emb, void *x, void *hip_stream);
+int32_t streambp_embedding_backward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab,
+                                    const int32_t *ids, const void *dx, float *demb, void *hip_stream);
+
+/* ------------------------------------------------------------------ misc -- */
+
+const char *streambp_version(void);
+const char *streambp_last_error(void);
+/* Number of (query tile, key tile) pairs the attention kernels visit for a
+ * chunk, and the tile sizes; host arithmetic only, for the causal-skip check
+ * (Sec. 3.2.2, computational efficiency: about (1+D)/(2D) of the full square). */
+int64_t streambp_attn_tile_pairs(int32_t q_start, int32_t q_len, int32_t *tile_q, int32_t *tile_k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STREAMBP_H */

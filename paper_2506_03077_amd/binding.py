@@ -1,0 +1,307 @@
+"""Thin ctypes binding over libstreambp.so: argument marshalling only.
+
+Function names mirror the C ABI in include/streambp.h.  torch is used for
+device memory and the current HIP stream, nothing else: every step of the
+path runs in the library's kernels.  If the library is missing the import of
+any entry point raises - there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libstreambp.so")
+
+SBP_F32, SBP_BF16 = 0, 1
+SBP_OBJ_SFT, SBP_OBJ_GRPO, SBP_OBJ_DPO = 0, 1, 2
+WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "g1", "g2")
+
+
+class StreamBPError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libstreambp error {code}: {msg}")
+        self.code = code
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
+                ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("mlp_width", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("pos_offset", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
+
+
+class LayerGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
+
+
+class HeadCfg(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
+                ("hidden", C.c_int32), ("vocab", C.c_int32), ("objective", C.c_int32), ("loss_scale", C.c_float),
+                ("clip_eps", C.c_float), ("kl_beta", C.c_float), ("kl_mode", C.c_int32)]
+
+
+class AttnCfg(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("q_start", C.c_int32), ("q_len", C.c_int32), ("scale", C.c_float)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the C-ABI library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2506_03077_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i32, i64, f32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_int64, C.c_float
+        L.streambp_version.restype = C.c_char_p
+        L.streambp_last_error.restype = C.c_char_p
+        L.streambp_layer_workspace_bytes.restype = sz
+        L.streambp_layer_workspace_bytes.argtypes = [C.POINTER(LayerCfg)]
+        L.streambp_layer_backward.restype = i32
+        L.streambp_layer_backward.argtypes = [C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp,
+                                              C.POINTER(LayerGrads), vp, sz, vp]
+        L.streambp_layer_forward.restype = i32
+        L.streambp_layer_forward.argtypes = [C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp, sz, vp]
+        L.streambp_lmhead_workspace_bytes.restype = sz
+        L.streambp_lmhead_workspace_bytes.argtypes = [C.POINTER(HeadCfg)]
+        L.streambp_lmhead_ce_backward.restype = i32
+        L.streambp_lmhead_ce_backward.argtypes = [C.POINTER(HeadCfg), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.streambp_attn_workspace_bytes.restype = sz
+        L.streambp_attn_workspace_bytes.argtypes = [C.POINTER(AttnCfg)]
+        L.streambp_attn_chunk_forward.restype = i32
+        L.streambp_attn_chunk_forward.argtypes = [C.POINTER(AttnCfg), vp, vp, vp, vp, vp, vp]
+        L.streambp_attn_chunk_backward.restype = i32
+        L.streambp_attn_chunk_backward.argtypes = [C.POINTER(AttnCfg), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.streambp_rmsnorm_workspace_bytes.restype = sz
+        L.streambp_rmsnorm_workspace_bytes.argtypes = [i64, i32]
+        L.streambp_rmsnorm_forward.restype = i32
+        L.streambp_rmsnorm_forward.argtypes = [i32, i64, i32, f32, vp, vp, vp, vp]
+        L.streambp_rmsnorm_backward.restype = i32
+        L.streambp_rmsnorm_backward.argtypes = [i32, i64, i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.streambp_embedding_forward.restype = i32
+        L.streambp_embedding_forward.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp]
+        L.streambp_embedding_backward.restype = i32
+        L.streambp_embedding_backward.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp]
+        L.streambp_attn_tile_pairs.restype = i64
+        L.streambp_attn_tile_pairs.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.streambp_debug_force_generic.restype = None
+        L.streambp_debug_force_generic.argtypes = [C.c_int, C.c_int]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise StreamBPError(rc, lib().streambp_last_error().decode())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dt_code(t):
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return SBP_F32
+    if t.dtype == torch.bfloat16:
+        return SBP_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "tensors must be contiguous device tensors"
+    return t.data_ptr()
+
+
+def _stream(stream):
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def _workspace(nbytes, device):
+    torch = _torch()
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def streambp_version():
+    return lib().streambp_version().decode()
+
+
+def layer_cfg(dtype, batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
+              rms_eps=1e-6, rope_theta=1e4, pos_offset=0):
+    return LayerCfg(int(dtype), batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
+                    rms_eps, rope_theta, pos_offset)
+
+
+def streambp_layer_workspace_bytes(cfg: LayerCfg) -> int:
+    return int(lib().streambp_layer_workspace_bytes(C.byref(cfg)))
+
+
+def _weights_struct(w):
+    return LayerWeights(*[_ptr(w[n]) for n in WEIGHT_NAMES])
+
+
+def new_layer_grads(w):
+    """Zero fp32 accumulators shaped like the weights."""
+    torch = _torch()
+    return {n: torch.zeros(w[n].shape, dtype=torch.float32, device=w[n].device) for n in WEIGHT_NAMES}
+
+
+def streambp_layer_backward(cfg: LayerCfg, w, x, dy, dx=None, dw=None, workspace=None, stream=None):
+    """x, dy [B,T,d]; returns (dx, dw).  dw (dict of fp32 tensors) is accumulated into."""
+    torch = _torch()
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dw is None:
+        dw = new_layer_grads(w)
+    if workspace is None:
+        workspace = _workspace(streambp_layer_workspace_bytes(cfg), x.device)
+    ws, gs = _weights_struct(w), LayerGrads(*[_ptr(dw[n]) for n in WEIGHT_NAMES])
+    _check(lib().streambp_layer_backward(C.byref(cfg), C.byref(ws), _ptr(x), _ptr(dy), _ptr(dx), C.byref(gs),
+                                         _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dx, dw
+
+
+def streambp_layer_forward(cfg: LayerCfg, w, x, y=None, workspace=None, stream=None):
+    torch = _torch()
+    if y is None:
+        y = torch.empty_like(x)
+    if workspace is None:
+        workspace = _workspace(streambp_layer_workspace_bytes(cfg), x.device)
+    ws = _weights_struct(w)
+    _check(lib().streambp_layer_forward(C.byref(cfg), C.byref(ws), _ptr(x), _ptr(y), _ptr(workspace),
+                                        workspace.numel(), _stream(stream)))
+    return y
+
+
+def head_cfg(dtype, batch, seq_len, chunk, hidden, vocab, objective=SBP_OBJ_SFT, loss_scale=1.0,
+             clip_eps=0.2, kl_beta=0.04, kl_mode=0):
+    return HeadCfg(int(dtype), batch, seq_len, chunk, hidden, vocab, objective, loss_scale, clip_eps, kl_beta, kl_mode)
+
+
+def streambp_lmhead_workspace_bytes(cfg: HeadCfg) -> int:
+    return int(lib().streambp_lmhead_workspace_bytes(C.byref(cfg)))
+
+
+def streambp_lmhead_ce_backward(cfg: HeadCfg, w, h, targets, old_logp=None, ref_logp=None, advantages=None,
+                                dh=None, dw=None, loss=None, n_active=None, workspace=None, stream=None):
+    """Returns (dh, dw, loss, n_active) - loss and n_active are 1-element device tensors."""
+    torch = _torch()
+    dev = h.device
+    if dh is None:
+        dh = torch.empty_like(h)
+    if dw is None:
+        dw = torch.zeros(w.shape, dtype=torch.float32, device=dev)
+    if loss is None:
+        loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    if n_active is None:
+        n_active = torch.zeros(1, dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = _workspace(streambp_lmhead_workspace_bytes(cfg), dev)
+    assert targets.dtype == torch.int32
+    _check(lib().streambp_lmhead_ce_backward(C.byref(cfg), _ptr(w), _ptr(h), _ptr(targets), _ptr(old_logp),
+                                             _ptr(ref_logp), _ptr(advantages), _ptr(dh), _ptr(dw), _ptr(loss),
+                                             _ptr(n_active), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dh, dw, loss, n_active
+
+
+def attn_cfg(dtype, n_q_heads, n_kv_heads, head_dim, q_start, q_len, scale):
+    return AttnCfg(int(dtype), n_q_heads, n_kv_heads, head_dim, q_start, q_len, scale)
+
+
+def streambp_attn_workspace_bytes(cfg: AttnCfg) -> int:
+    return int(lib().streambp_attn_workspace_bytes(C.byref(cfg)))
+
+
+def streambp_attn_chunk_forward(cfg: AttnCfg, q, k, v, o=None, lse=None, stream=None):
+    torch = _torch()
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((cfg.n_q_heads, cfg.q_len), dtype=torch.float32, device=q.device)
+    _check(lib().streambp_attn_chunk_forward(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _stream(stream)))
+    return o, lse
+
+
+def streambp_attn_chunk_backward(cfg: AttnCfg, q, k, v, o, lse, d_o, dq=None, dk=None, dv=None, workspace=None,
+                                 stream=None):
+    """dk, dv [>= s+c, Hkv, dh] fp32 are accumulated into (zero tensors are made if not given)."""
+    torch = _torch()
+    if dq is None:
+        dq = torch.empty_like(q)
+    if dk is None:
+        dk = torch.zeros(k.shape, dtype=torch.float32, device=q.device)
+    if dv is None:
+        dv = torch.zeros(v.shape, dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = _workspace(streambp_attn_workspace_bytes(cfg), q.device)
+    _check(lib().streambp_attn_chunk_backward(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(),
+                                              _stream(stream)))
+    return dq, dk, dv
+
+
+def streambp_rmsnorm_forward(x, g, eps=1e-6, y=None, stream=None):
+    torch = _torch()
+    if y is None:
+        y = torch.empty_like(x)
+    d = x.shape[-1]
+    _check(lib().streambp_rmsnorm_forward(_dt_code(x), x.numel() // d, d, eps, _ptr(x), _ptr(g), _ptr(y), _stream(stream)))
+    return y
+
+
+def streambp_rmsnorm_backward(x, g, dy, eps=1e-6, dx=None, dg=None, workspace=None, stream=None):
+    torch = _torch()
+    d = x.shape[-1]
+    n = x.numel() // d
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dg is None:
+        dg = torch.zeros(d, dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = _workspace(lib().streambp_rmsnorm_workspace_bytes(n, d), x.device)
+    _check(lib().streambp_rmsnorm_backward(_dt_code(x), n, d, eps, _ptr(x), _ptr(g), _ptr(dy), _ptr(dx), _ptr(dg),
+                                           _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dx, dg
+
+
+def streambp_embedding_forward(ids, emb, x=None, stream=None):
+    torch = _torch()
+    V, d = emb.shape
+    if x is None:
+        x = torch.empty((ids.numel(), d), dtype=emb.dtype, device=emb.device)
+    _check(lib().streambp_embedding_forward(_dt_code(emb), ids.numel(), d, V, _ptr(ids), _ptr(emb), _ptr(x), _stream(stream)))
+    return x
+
+
+def streambp_embedding_backward(ids, dx, vocab, demb=None, stream=None):
+    torch = _torch()
+    d = dx.shape[-1]
+    if demb is None:
+        demb = torch.zeros((vocab, d), dtype=torch.float32, device=dx.device)
+    _check(lib().streambp_embedding_backward(_dt_code(dx), ids.numel(), d, vocab, _ptr(ids), _ptr(dx), _ptr(demb), _stream(stream)))
+    return demb
+
+
+def streambp_attn_tile_pairs(q_start, q_len):
+    tq, tk = C.c_int32(0), C.c_int32(0)
+    n = lib().streambp_attn_tile_pairs(q_start, q_len, C.byref(tq), C.byref(tk))
+    return int(n), tq.value, tk.value
+
+
+def debug_force_generic(gemm=False, attn=False):
+    """Route GEMMs / attention through the shape-agnostic kernels (A/B testing of the MFMA kernels)."""
+    lib().streambp_debug_force_generic(int(gemm), int(attn))

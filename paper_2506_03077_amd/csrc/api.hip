@@ -1,0 +1,473 @@
+// C ABI of libstreambp and the host-side chunk loops (paper Sec. 3.2.1, 3.2.2).
+// Host code only validates, carves the caller's workspace and enqueues kernels
+// on the caller's stream; it never allocates or synchronises.
+#include "../../include/streambp.h"
+#include "launch.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+using namespace sbp;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIPCHK(expr)                                                                       \
+  do {                                                                                     \
+    hipError_t e__ = (expr);                                                               \
+    if (e__ != hipSuccess)                                                                 \
+      return fail(SBP_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+  } while (0)
+
+// Bump allocator over the caller's workspace (256-byte granularity).
+struct Carver {
+  char* base; size_t off = 0;
+  explicit Carver(void* p) : base((char*)p) {}
+  template <typename T> T* take(size_t n_elems) { return (T*)take_bytes(n_elems * sizeof(T)); }
+  void* take_bytes(size_t bytes) {
+    void* p = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  }
+};
+
+bool valid_dtype(int32_t dt) { return dt == SBP_F32 || dt == SBP_BF16; }
+
+// ------------------------------------------------------------- layer ------
+struct LayerWs {
+  void *K, *V;                 // [T, Hkv*dh] dt   cached for the whole sequence
+  float *dK, *dV;              // [T, Hkv*dh] fp32 prefix accumulators
+  float2* rope;                // [T, dh/2] cos/sin
+  void *a, *q, *o, *m, *gate, *up, *act, *dh1_t, *d_o, *dq, *dkc, *dvc;   // per chunk, dt
+  float *h1, *dm, *dh1, *da, *proj;                                       // per chunk, fp32 [c, d]
+  float *rstd1, *rstd2, *lse, *delta, *partial;
+  size_t bytes;
+};
+
+int32_t check_layer_cfg(const sbp_layer_cfg* c) {
+  if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
+  if (!valid_dtype(c->dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", c->dtype);
+  if (c->batch < 1 || c->seq_len < 1 || c->chunk < 1) return fail(SBP_ERR_SHAPE, "batch, seq_len and chunk must be >= 1");
+  if (c->hidden < 1 || c->mlp_width < 1) return fail(SBP_ERR_SHAPE, "hidden and mlp_width must be >= 1");
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads != 0)
+    return fail(SBP_ERR_SHAPE, "n_q_heads (%d) must be a positive multiple of n_kv_heads (%d)", c->n_q_heads, c->n_kv_heads);
+  if (c->head_dim < 2 || (c->head_dim & 1) || c->head_dim > 256)
+    return fail(SBP_ERR_SHAPE, "head_dim must be even and in [2, 256]");
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(SBP_ERR_SHAPE, "rms_eps must be >= 0 and rope_theta > 0");
+  return SBP_OK;
+}
+
+LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
+  const size_t es = dtype_size(c->dtype);
+  const size_t T = c->seq_len, cm = (size_t)std::min(c->chunk, c->seq_len);
+  const size_t d = c->hidden, F = c->mlp_width, qd = (size_t)c->n_q_heads * c->head_dim, kd = (size_t)c->n_kv_heads * c->head_dim;
+  Carver cv(ws);
+  LayerWs w;
+  w.K = cv.take_bytes(T * kd * es);
+  w.V = cv.take_bytes(T * kd * es);
+  w.dK = cv.take<float>(T * kd);
+  w.dV = cv.take<float>(T * kd);
+  w.rope = cv.take<float2>(T * (c->head_dim / 2));
+  w.a = cv.take_bytes(cm * d * es);
+  w.q = cv.take_bytes(cm * qd * es);
+  w.o = cv.take_bytes(cm * qd * es);
+  w.m = cv.take_bytes(cm * d * es);
+  w.gate = cv.take_bytes(cm * F * es);
+  w.up = cv.take_bytes(cm * F * es);
+  w.act = cv.take_bytes(cm * F * es);
+  w.dh1_t = cv.take_bytes(cm * d * es);
+  w.d_o = cv.take_bytes(cm * qd * es);
+  w.dq = cv.take_bytes(cm * qd * es);
+  w.dkc = cv.take_bytes(cm * kd * es);
+  w.dvc = cv.take_bytes(cm * kd * es);
+  w.h1 = cv.take<float>(cm * d);
+  w.dm = cv.take<float>(cm * d);
+  w.dh1 = cv.take<float>(cm * d);
+  w.da = cv.take<float>(cm * d);
+  w.proj = cv.take<float>(cm * d);
+  w.rstd1 = cv.take<float>(cm);
+  w.rstd2 = cv.take<float>(cm);
+  w.lse = cv.take<float>(cm * c->n_q_heads);
+  w.delta = cv.take<float>(cm * c->n_q_heads);
+  w.partial = cv.take<float>(rmsnorm_bwd_partial_floats((int)cm, (int)d));
+  w.bytes = cv.off;
+  return w;
+}
+
+GemmArgs mk(const void* A, const void* B, void* C, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
+            bool ta, bool tb, int in_dt, int out_dt, bool acc) {
+  GemmArgs g{A, B, C, M, N, K, lda, ldb, ldc, ta, tb, in_dt, out_dt, acc};
+  return g;
+}
+// Y[M,N] = X[M,K] W[N,K]^T
+GemmArgs fwd_gemm(const void* X, const void* W, void* Y, int M, int N, int K, int dt, int out_dt) {
+  return mk(X, W, Y, M, N, K, K, K, N, false, true, dt, out_dt, false);
+}
+// dX[M,K] (=|+=) dY[M,N] W[N,K]
+GemmArgs dx_gemm(const void* dY, const void* W, void* dX, int M, int N, int K, int dt, int out_dt, bool acc) {
+  return mk(dY, W, dX, M, K, N, N, K, K, false, false, dt, out_dt, acc);
+}
+// dW[N,K] += dY[M,N]^T X[M,K]
+GemmArgs dw_gemm(const void* dY, const void* X, float* dW, int M, int N, int K, int dt) {
+  return mk(dY, X, dW, N, K, M, N, K, K, true, false, dt, DT_F32, true);
+}
+
+const char* at(const void* p, size_t row, size_t width, size_t es) { return (const char*)p + row * width * es; }
+char* at(void* p, size_t row, size_t width, size_t es) { return (char*)p + row * width * es; }
+
+int32_t check_layer_ptrs(const sbp_layer_weights* w) {
+  if (!w) return fail(SBP_ERR_NULL, "weights table is NULL");
+  const void* ps[] = {w->wq, w->wk, w->wv, w->wo, w->wgate, w->wup, w->wdown, w->g1, w->g2};
+  for (const void* p : ps) if (!p) return fail(SBP_ERR_NULL, "a weight pointer is NULL");
+  return SBP_OK;
+}
+
+// K and V of the whole sequence, once (cached for all chunks of the layer).
+int32_t kv_prepass(const sbp_layer_cfg* c, const sbp_layer_weights* w, const LayerWs& s, const char* xb, hipStream_t st) {
+  const int dt = c->dtype;
+  const size_t es = dtype_size(dt);
+  const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden;
+  const int kd = c->n_kv_heads * c->head_dim;
+  for (int r0 = 0; r0 < T; r0 += cm) {
+    const int n = std::min(cm, T - r0);
+    HIPCHK(rmsnorm_fwd(dt, at(xb, r0, d, es), nullptr, w->g1, s.a, nullptr, s.rstd1, n, d, c->rms_eps, st));
+    HIPCHK(gemm(fwd_gemm(s.a, w->wk, at(s.K, r0, kd, es), n, kd, d, dt, dt), st));
+    HIPCHK(gemm(fwd_gemm(s.a, w->wv, at(s.V, r0, kd, es), n, kd, d, dt, dt), st));
+    HIPCHK(rope_apply(dt, at(s.K, r0, kd, es), s.rope + (size_t)r0 * (c->head_dim / 2), n, c->n_kv_heads, c->head_dim, false, st));
+  }
+  return SBP_OK;
+}
+
+// Partitioned reforward of rows [r0, r0+n): fills a, q, o, lse, h1, m, gate, up, act.
+int32_t chunk_reforward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const LayerWs& s, const char* xb,
+                        int r0, int n, hipStream_t st) {
+  const int dt = c->dtype;
+  const size_t es = dtype_size(dt);
+  const int d = c->hidden, F = c->mlp_width, qd = c->n_q_heads * c->head_dim;
+  const char* xc = at(xb, r0, d, es);
+  HIPCHK(rmsnorm_fwd(dt, xc, nullptr, w->g1, s.a, nullptr, s.rstd1, n, d, c->rms_eps, st));
+  HIPCHK(gemm(fwd_gemm(s.a, w->wq, s.q, n, qd, d, dt, dt), st));
+  HIPCHK(rope_apply(dt, s.q, s.rope + (size_t)r0 * (c->head_dim / 2), n, c->n_q_heads, c->head_dim, false, st));
+  AttnArgs aa{};
+  aa.dt = dt; aa.Hq = c->n_q_heads; aa.Hkv = c->n_kv_heads; aa.dh = c->head_dim;
+  aa.q_start = r0; aa.q_len = n; aa.scale = 1.0f / std::sqrt((float)c->head_dim);
+  aa.q = s.q; aa.k = s.K; aa.v = s.V; aa.o = s.o; aa.lse = s.lse;
+  HIPCHK(attn_forward(aa, st));
+  HIPCHK(gemm(fwd_gemm(s.o, w->wo, s.proj, n, d, qd, dt, DT_F32), st));
+  HIPCHK(rmsnorm_fwd(dt, xc, s.proj, w->g2, s.m, s.h1, s.rstd2, n, d, c->rms_eps, st));
+  HIPCHK(gemm(fwd_gemm(s.m, w->wgate, s.gate, n, F, d, dt, dt), st));
+  HIPCHK(gemm(fwd_gemm(s.m, w->wup, s.up, n, F, d, dt, dt), st));
+  HIPCHK(swiglu_fwd(dt, s.gate, s.up, s.act, (int64_t)n * F, st));
+  return SBP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* streambp_version(void) { return "streambp-mi355x 0.1 (gfx950)"; }
+const char* streambp_last_error(void) { return g_err; }
+
+size_t streambp_layer_workspace_bytes(const sbp_layer_cfg* cfg) {
+  if (check_layer_cfg(cfg) != SBP_OK) return 0;
+  return carve_layer(cfg, nullptr).bytes;
+}
+
+int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const void* x, const void* dy,
+                                void* dx, const sbp_layer_grads* g, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  int32_t rc = check_layer_cfg(c);
+  if (rc) return rc;
+  if ((rc = check_layer_ptrs(w))) return rc;
+  if (!x || !dy || !dx || !g || !workspace) return fail(SBP_ERR_NULL, "x, dy, dx, dw and workspace must be non-NULL");
+  {
+    const float* ps[] = {g->wq, g->wk, g->wv, g->wo, g->wgate, g->wup, g->wdown, g->g1, g->g2};
+    for (const float* p : ps) if (!p) return fail(SBP_ERR_NULL, "a gradient pointer is NULL");
+  }
+  if (dx == x || dx == dy) return fail(SBP_ERR_SHAPE, "dx may not alias x or dy");
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const LayerWs s = carve_layer(c, workspace);
+  if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int dt = c->dtype;
+  const size_t es = dtype_size(dt);
+  const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden, F = c->mlp_width;
+  const int qd = c->n_q_heads * c->head_dim, kd = c->n_kv_heads * c->head_dim, half = c->head_dim / 2;
+
+  HIPCHK(rope_table(s.rope, T, c->head_dim, c->rope_theta, c->pos_offset, st));
+  for (int b = 0; b < c->batch; ++b) {
+    const char* xb = at(x, (size_t)b * T, d, es);
+    const char* dyb = at(dy, (size_t)b * T, d, es);
+    char* dxb = at(dx, (size_t)b * T, d, es);
+    if ((rc = kv_prepass(c, w, s, xb, st))) return rc;
+    HIPCHK(fill_zero(s.dK, (size_t)T * kd * sizeof(float), st));
+    HIPCHK(fill_zero(s.dV, (size_t)T * kd * sizeof(float), st));
+    // Chunks run last to first: rows of dK/dV belonging to chunk i are final once
+    // chunks >= i are done (later queries are the only other readers of those
+    // keys), so the K/V-side gradient and dx of the chunk can be finished at once.
+    const int n_chunks = (int)cdiv(T, cm);
+    for (int ci = n_chunks - 1; ci >= 0; --ci) {
+      const int r0 = ci * cm, n = std::min(cm, T - r0);
+      if ((rc = chunk_reforward(c, w, s, xb, r0, n, st))) return rc;
+      const char* dyc = at(dyb, r0, d, es);
+      // ---- MLP backward
+      HIPCHK(gemm(dw_gemm(dyc, s.act, g->wdown, n, d, F, dt), st));
+      HIPCHK(gemm(dx_gemm(dyc, w->wdown, s.act, n, d, F, dt, dt, false), st));      // dact overwrites act
+      HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.act, (int64_t)n * F, st));               // gate <- dgate, up <- dup
+      HIPCHK(gemm(dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt), st));
+      HIPCHK(gemm(dw_gemm(s.up, s.m, g->wup, n, F, d, dt), st));
+      HIPCHK(gemm(dx_gemm(s.gate, w->wgate, s.dm, n, F, d, dt, DT_F32, false), st));
+      HIPCHK(gemm(dx_gemm(s.up, w->wup, s.dm, n, F, d, dt, DT_F32, true), st));
+      HIPCHK(rmsnorm_bwd(dt, s.dm, s.h1, true, w->g2, s.rstd2, dyc, false, s.dh1, s.dh1_t, g->g2, s.partial, n, d, st));
+      // ---- attention-side backward
+      HIPCHK(gemm(dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt), st));
+      HIPCHK(gemm(dx_gemm(s.dh1_t, w->wo, s.d_o, n, d, qd, dt, dt, false), st));
+      AttnArgs aa{};
+      aa.dt = dt; aa.Hq = c->n_q_heads; aa.Hkv = c->n_kv_heads; aa.dh = c->head_dim;
+      aa.q_start = r0; aa.q_len = n; aa.scale = 1.0f / std::sqrt((float)c->head_dim);
+      aa.q = s.q; aa.k = s.K; aa.v = s.V; aa.o = s.o; aa.lse = s.lse;
+      aa.d_o = s.d_o; aa.dq = s.dq; aa.dk = s.dK; aa.dv = s.dV; aa.delta = s.delta;
+      HIPCHK(attn_backward(aa, st));
+      HIPCHK(rope_apply(dt, s.dq, s.rope + (size_t)r0 * half, n, c->n_q_heads, c->head_dim, true, st));
+      HIPCHK(gemm(dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt), st));
+      HIPCHK(gemm(dx_gemm(s.dq, w->wq, s.da, n, qd, d, dt, DT_F32, false), st));
+      // ---- K/V side of rows [r0, r0+n): final now
+      HIPCHK(kv_grad_finish(dt, s.dK + (size_t)r0 * kd, s.dV + (size_t)r0 * kd, s.rope + (size_t)r0 * half, s.dkc, s.dvc,
+                            n, c->n_kv_heads, c->head_dim, st));
+      HIPCHK(gemm(dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt), st));
+      HIPCHK(gemm(dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt), st));
+      HIPCHK(gemm(dx_gemm(s.dkc, w->wk, s.da, n, kd, d, dt, DT_F32, true), st));
+      HIPCHK(gemm(dx_gemm(s.dvc, w->wv, s.da, n, kd, d, dt, DT_F32, true), st));
+      HIPCHK(rmsnorm_bwd(dt, s.da, at(xb, r0, d, es), false, w->g1, s.rstd1, s.dh1, true, nullptr, at(dxb, r0, d, es),
+                         g->g1, s.partial, n, d, st));
+    }
+  }
+  return SBP_OK;
+}
+
+int32_t streambp_layer_forward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const void* x, void* y,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int32_t rc = check_layer_cfg(c);
+  if (rc) return rc;
+  if ((rc = check_layer_ptrs(w))) return rc;
+  if (!x || !y || !workspace) return fail(SBP_ERR_NULL, "x, y and workspace must be non-NULL");
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const LayerWs s = carve_layer(c, workspace);
+  if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int dt = c->dtype;
+  const size_t es = dtype_size(dt);
+  const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden, F = c->mlp_width;
+  HIPCHK(rope_table(s.rope, T, c->head_dim, c->rope_theta, c->pos_offset, st));
+  for (int b = 0; b < c->batch; ++b) {
+    const char* xb = at(x, (size_t)b * T, d, es);
+    char* yb = at(y, (size_t)b * T, d, es);
+    if ((rc = kv_prepass(c, w, s, xb, st))) return rc;
+    for (int r0 = 0; r0 < T; r0 += cm) {
+      const int n = std::min(cm, T - r0);
+      if ((rc = chunk_reforward(c, w, s, xb, r0, n, st))) return rc;
+      HIPCHK(gemm(fwd_gemm(s.act, w->wdown, s.proj, n, d, F, dt, DT_F32), st));
+      HIPCHK(add_store(dt, s.h1, s.proj, at(yb, r0, d, es), (int64_t)n * d, st));
+    }
+  }
+  return SBP_OK;
+}
+
+// --------------------------------------------------------------- LM head --
+static int32_t check_head_cfg(const sbp_head_cfg* c) {
+  if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
+  if (!valid_dtype(c->dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", c->dtype);
+  if (c->batch < 1 || c->seq_len < 1 || c->chunk < 1 || c->hidden < 1 || c->vocab < 1)
+    return fail(SBP_ERR_SHAPE, "batch, seq_len, chunk, hidden and vocab must be >= 1");
+  if (c->objective < SBP_OBJ_SFT || c->objective > SBP_OBJ_DPO) return fail(SBP_ERR_UNSUPPORTED, "objective %d not supported", c->objective);
+  if (c->objective == SBP_OBJ_DPO && c->batch != 2) return fail(SBP_ERR_SHAPE, "DPO needs batch == 2 (chosen, rejected)");
+  return SBP_OK;
+}
+
+struct HeadWs { float* z; void* dz; float *row_loss, *seq_weight, *ell; size_t bytes; };
+static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
+  const int64_t rows = (int64_t)c->batch * c->seq_len;
+  const size_t cm = (size_t)std::min<int64_t>(c->chunk, rows);
+  Carver cv(ws);
+  HeadWs h;
+  h.z = cv.take<float>(cm * c->vocab);
+  h.dz = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
+  h.row_loss = cv.take<float>(cm);
+  h.seq_weight = cv.take<float>(c->batch);
+  h.ell = cv.take<float>(1);
+  h.bytes = cv.off;
+  return h;
+}
+
+size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg* cfg) {
+  if (check_head_cfg(cfg) != SBP_OK) return 0;
+  return carve_head(cfg, nullptr).bytes;
+}
+
+int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const void* h, const int32_t* targets,
+                                    const float* old_logp, const float* ref_logp, const float* advantages, void* dh,
+                                    float* dw, float* loss, int64_t* n_active, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream) {
+  int32_t rc = check_head_cfg(c);
+  if (rc) return rc;
+  if (!w || !h || !targets || !dh || !dw || !loss || !n_active || !workspace)
+    return fail(SBP_ERR_NULL, "w, h, targets, dh, dw, loss, n_active and workspace must be non-NULL");
+  if (c->objective == SBP_OBJ_GRPO && (!ref_logp || !advantages)) return fail(SBP_ERR_NULL, "GRPO needs ref_logp and advantages");
+  if (c->objective == SBP_OBJ_DPO && !ref_logp) return fail(SBP_ERR_NULL, "DPO needs ref_logp");
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const HeadWs s = carve_head(c, workspace);
+  if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int dt = c->dtype;
+  const size_t es = dtype_size(dt);
+  const int64_t rows = (int64_t)c->batch * c->seq_len;
+  const int cm = (int)std::min<int64_t>(c->chunk, rows);
+  const int d = c->hidden, V = c->vocab;
+
+  HIPCHK(count_active(targets, c->batch, c->seq_len, s.seq_weight, n_active, st));
+  if (c->objective == SBP_OBJ_DPO) HIPCHK(fill_zero(s.ell, sizeof(float), st));
+  // Positions are independent (Sec. 3.2.1), so the B*T rows are chunked as one flat list.
+  for (int64_t r0 = 0; r0 < rows; r0 += cm) {
+    const int n = (int)std::min<int64_t>(cm, rows - r0);
+    const char* hc = at(h, (size_t)r0, d, es);
+    HIPCHK(gemm(fwd_gemm(hc, w, s.z, n, V, d, dt, DT_F32), st));
+    HeadRowArgs a{};
+    a.dt = dt; a.objective = c->objective; a.z = s.z; a.dz = s.dz; a.targets = targets + r0;
+    a.old_logp = old_logp ? old_logp + r0 : nullptr;
+    a.ref_logp = ref_logp ? ref_logp + r0 : nullptr;
+    a.advantages = advantages; a.seq_weight = s.seq_weight; a.row0 = r0; a.rows = n; a.V = V; a.T = c->seq_len;
+    a.loss_scale = c->loss_scale; a.clip_eps = c->clip_eps; a.kl_beta = c->kl_beta; a.kl_mode = c->kl_mode;
+    a.row_loss = s.row_loss;
+    HIPCHK(head_rows(a, st));
+    HIPCHK(reduce_add(s.row_loss, n, c->objective == SBP_OBJ_DPO ? s.ell : loss, st));
+    HIPCHK(gemm(dx_gemm(s.dz, w, at(dh, (size_t)r0, d, es), n, V, d, dt, dt, false), st));
+    HIPCHK(gemm(dw_gemm(s.dz, hc, dw, n, V, d, dt), st));
+  }
+  if (c->objective == SBP_OBJ_DPO)
+    HIPCHK(dpo_finish(dt, s.ell, c->kl_beta, dh, rows * d, dw, (int64_t)V * d, loss, st));
+  return SBP_OK;
+}
+
+// -------------------------------------------------------- chunk attention --
+static int32_t check_attn_cfg(const sbp_attn_cfg* c) {
+  if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
+  if (!valid_dtype(c->dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", c->dtype);
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads != 0)
+    return fail(SBP_ERR_SHAPE, "n_q_heads must be a positive multiple of n_kv_heads");
+  if (c->head_dim < 1 || c->head_dim > 256) return fail(SBP_ERR_SHAPE, "head_dim must be in [1, 256]");
+  if (c->q_start < 0 || c->q_len < 0) return fail(SBP_ERR_SHAPE, "q_start and q_len must be >= 0");
+  if ((int64_t)c->q_start + c->q_len > INT32_MAX) return fail(SBP_ERR_SHAPE, "q_start + q_len overflows");
+  return SBP_OK;
+}
+
+size_t streambp_attn_workspace_bytes(const sbp_attn_cfg* cfg) {
+  if (check_attn_cfg(cfg) != SBP_OK) return 0;
+  return align_up((size_t)std::max(cfg->q_len, 1) * cfg->n_q_heads * sizeof(float), 256);
+}
+
+int32_t streambp_attn_chunk_forward(const sbp_attn_cfg* c, const void* q, const void* k, const void* v, void* o,
+                                    float* lse, void* hip_stream) {
+  int32_t rc = check_attn_cfg(c);
+  if (rc) return rc;
+  if (c->q_len == 0) return SBP_OK;   // empty chunk: nothing to do
+  if (!q || !k || !v || !o || !lse) return fail(SBP_ERR_NULL, "q, k, v, o and lse must be non-NULL");
+  AttnArgs a{};
+  a.dt = c->dtype; a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads; a.dh = c->head_dim;
+  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  HIPCHK(attn_forward(a, (hipStream_t)hip_stream));
+  return SBP_OK;
+}
+
+int32_t streambp_attn_chunk_backward(const sbp_attn_cfg* c, const void* q, const void* k, const void* v, const void* o,
+                                     const float* lse, const void* d_o, void* dq, float* dk, float* dv,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int32_t rc = check_attn_cfg(c);
+  if (rc) return rc;
+  if (c->q_len == 0) return SBP_OK;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !workspace)
+    return fail(SBP_ERR_NULL, "all tensor pointers and workspace must be non-NULL");
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < streambp_attn_workspace_bytes(c)) return fail(SBP_ERR_WORKSPACE, "workspace too small");
+  AttnArgs a{};
+  a.dt = c->dtype; a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads; a.dh = c->head_dim;
+  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale;
+  a.q = q; a.k = k; a.v = v; a.o = (void*)o; a.lse = (float*)lse;
+  a.d_o = d_o; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
+  HIPCHK(attn_backward(a, (hipStream_t)hip_stream));
+  return SBP_OK;
+}
+
+int64_t streambp_attn_tile_pairs(int32_t q_start, int32_t q_len, int32_t* tile_q, int32_t* tile_k) {
+  if (tile_q) *tile_q = ATTN_TILE_Q;
+  if (tile_k) *tile_k = ATTN_TILE_K;
+  if (q_start < 0 || q_len <= 0) return 0;
+  int64_t pairs = 0;
+  for (int64_t t0 = 0; t0 < q_len; t0 += ATTN_TILE_Q) {
+    const int64_t last_q = q_start + std::min<int64_t>(t0 + ATTN_TILE_Q, q_len) - 1;   // last query position of the tile
+    pairs += last_q / ATTN_TILE_K + 1;                                                 // key tiles that start at or before it
+  }
+  return pairs;
+}
+
+// ------------------------------------------------------------ stack glue --
+size_t streambp_rmsnorm_workspace_bytes(int64_t n_rows, int32_t hidden) {
+  if (n_rows < 0 || n_rows > INT32_MAX || hidden < 1) return 0;
+  return align_up((size_t)std::max<int64_t>(n_rows, 1) * sizeof(float), 256) +
+         align_up(rmsnorm_bwd_partial_floats((int)n_rows, hidden) * sizeof(float) + 256, 256);
+}
+int32_t streambp_rmsnorm_forward(int32_t dtype, int64_t n_rows, int32_t hidden, float eps, const void* x, const void* g,
+                                 void* y, void* hip_stream) {
+  if (!valid_dtype(dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", dtype);
+  if (n_rows < 0 || n_rows > INT32_MAX || hidden < 1 || !(eps >= 0.f)) return fail(SBP_ERR_SHAPE, "bad shape");
+  if (!x || !g || !y) return fail(SBP_ERR_NULL, "x, g and y must be non-NULL");
+  HIPCHK(rmsnorm_fwd(dtype, x, nullptr, g, y, nullptr, nullptr, (int)n_rows, hidden, eps, (hipStream_t)hip_stream));
+  return SBP_OK;
+}
+int32_t streambp_rmsnorm_backward(int32_t dtype, int64_t n_rows, int32_t hidden, float eps, const void* x, const void* g,
+                                  const void* dy, void* dx, float* dg, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+  if (!valid_dtype(dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", dtype);
+  if (n_rows < 0 || n_rows > INT32_MAX || hidden < 1 || !(eps >= 0.f)) return fail(SBP_ERR_SHAPE, "bad shape");
+  if (!x || !g || !dy || !dx || !dg || !workspace) return fail(SBP_ERR_NULL, "x, g, dy, dx, dg and workspace must be non-NULL");
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < streambp_rmsnorm_workspace_bytes(n_rows, hidden)) return fail(SBP_ERR_WORKSPACE, "workspace too small");
+  Carver cv(workspace);
+  float* rstd = cv.take<float>((size_t)std::max<int64_t>(n_rows, 1));
+  float* partial = cv.take<float>(rmsnorm_bwd_partial_floats((int)n_rows, hidden) + 64);
+  hipStream_t st = (hipStream_t)hip_stream;
+  HIPCHK(rmsnorm_fwd(dtype, x, nullptr, g, nullptr, nullptr, rstd, (int)n_rows, hidden, eps, st));
+  HIPCHK(rmsnorm_bwd_plain(dtype, dy, x, g, rstd, dx, dg, partial, (int)n_rows, hidden, st));
+  return SBP_OK;
+}
+int32_t streambp_embedding_forward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab, const int32_t* ids,
+                                   const void* emb, void* x, void* hip_stream) {
+  if (!valid_dtype(dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype");
+  if (n_rows < 0 || hidden < 1 || vocab < 1 || n_rows > INT32_MAX) return fail(SBP_ERR_SHAPE, "bad shape");
+  if (!ids || !emb || !x) return fail(SBP_ERR_NULL, "NULL pointer");
+  HIPCHK(embedding_fwd(dtype, ids, emb, x, n_rows, hidden, (hipStream_t)hip_stream));
+  return SBP_OK;
+}
+int32_t streambp_embedding_backward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab, const int32_t* ids,
+                                    const void* dx, float* demb, void* hip_stream) {
+  if (!valid_dtype(dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype");
+  if (n_rows < 0 || hidden < 1 || vocab < 1 || n_rows > INT32_MAX) return fail(SBP_ERR_SHAPE, "bad shape");
+  if (!ids || !dx || !demb) return fail(SBP_ERR_NULL, "NULL pointer");
+  HIPCHK(embedding_bwd(dtype, ids, dx, demb, n_rows, hidden, (hipStream_t)hip_stream));
+  return SBP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,335 @@
+// Row-statistic and elementwise kernels: RMSNorm (forward / adjoint), RoPE,
+// SwiGLU, residual adds, dK/dV finishing, embedding gather / scatter-add.
+// All are HBM-bound: one pass over their operands, 128-bit accesses where the
+// row width allows, fp32 arithmetic with wavefront (64-lane) reductions.
+#include "launch.h"
+#include <algorithm>
+
+namespace sbp {
+
+#define DISPATCH_DT(dt, T, ...)                      \
+  do {                                               \
+    if ((dt) == DT_BF16) { using T = bf16_t; __VA_ARGS__; } \
+    else { using T = float; __VA_ARGS__; }           \
+  } while (0)
+
+// ------------------------------------------------------------------ RoPE --
+// Rotate-half pairing (j, j + dh/2), angle (t + pos_offset) * theta^(-2j/dh).
+// Angles go through fp64: an fp32 product pos*inv_freq has an absolute error of
+// ~2e-3 rad at position 32768, which the fp32 path's tolerance cannot absorb.
+__global__ void rope_table_k(float2* tab, int n_pos, int half, double theta, int pos_offset) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)n_pos * half) return;
+  int t = (int)(i / half), j = (int)(i % half);
+  double inv_freq = pow(theta, -(double)j / (double)half);   // theta^(-2j/dh)
+  double ang = ((double)t + (double)pos_offset) * inv_freq;
+  double s, c;
+  sincos(ang, &s, &c);
+  tab[i] = make_float2((float)c, (float)s);
+}
+
+hipError_t rope_table(float2* tab, int n_pos, int dh, float theta, int pos_offset, hipStream_t st) {
+  int half = dh / 2;
+  int64_t n = (int64_t)n_pos * half;
+  if (n == 0) return hipSuccess;
+  rope_table_k<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(tab, n_pos, half, (double)theta, pos_offset);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void rope_apply_k(T* x, const float2* tab, int64_t n_pairs, int H, int half, int inverse) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_pairs) return;
+  int j = (int)(i % half);
+  int64_t rh = i / half;              // row * H + head
+  int64_t row = rh / H;
+  float2 cs = tab[row * half + j];
+  float sn = inverse ? -cs.y : cs.y;
+  T* p = x + rh * (2 * half);
+  float a = ldf(p + j), b = ldf(p + j + half);
+  stf(p + j, a * cs.x - b * sn);
+  stf(p + j + half, b * cs.x + a * sn);
+}
+
+hipError_t rope_apply(int dt, void* x, const float2* tab, int rows, int H, int dh, bool inverse, hipStream_t st) {
+  int64_t n = (int64_t)rows * H * (dh / 2);
+  if (n == 0) return hipSuccess;
+  DISPATCH_DT(dt, T, (rope_apply_k<T><<<(unsigned)cdiv(n, 256), 256, 0, st>>>((T*)x, tab, n, H, dh / 2, inverse ? 1 : 0)));
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------- RMSNorm --
+// One workgroup per row.  r = 1/sqrt(mean(v^2) + eps) with v = x (+ add).
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_k(const T* __restrict__ x, const float* __restrict__ add,
+                                                     const T* __restrict__ g, T* __restrict__ out,
+                                                     float* __restrict__ sum_out, float* __restrict__ rstd,
+                                                     int d, float eps) {
+  __shared__ float red[16];
+  const int64_t row = blockIdx.x;
+  const T* xr = x + row * d;
+  const float* ar = add ? add + row * d : nullptr;
+  float ss = 0.f;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    float v = ldf(xr + j) + (ar ? ar[j] : 0.f);
+    ss += v * v;
+  }
+  ss = block_sum(ss, red);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  if (threadIdx.x == 0 && rstd) rstd[row] = r;
+  if (!out) return;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    float v = ldf(xr + j) + (ar ? ar[j] : 0.f);
+    if (sum_out) sum_out[row * d + j] = v;
+    stf(out + row * d + j, ldf(g + j) * v * r);
+  }
+}
+
+hipError_t rmsnorm_fwd(int dt, const void* x, const float* add, const void* g, void* out, float* sum_out,
+                       float* rstd, int rows, int d, float eps, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  DISPATCH_DT(dt, T, (rmsnorm_fwd_k<T><<<rows, 256, 0, st>>>((const T*)x, add, (const T*)g, (T*)out, sum_out, rstd, d, eps)));
+  return hipGetLastError();
+}
+
+// Adjoint.  With u = dnorm * g and dot = <u, x>:  dx = u*r - x * r^3 * dot / d.
+// A workgroup owns RB consecutive rows so that it can emit one partial row of
+// dg = sum_rows dnorm * x * r; a second kernel adds the partial rows in a fixed
+// order (no atomics: the result is reproducible run to run).
+constexpr int RB = 8;
+template <typename T, typename XT, typename RT, typename DN = float>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_k(const DN* __restrict__ dnorm, const XT* __restrict__ xin,
+                                                     const T* __restrict__ g, const float* __restrict__ rstd,
+                                                     const RT* __restrict__ res, float* __restrict__ out_f32,
+                                                     T* __restrict__ out_t, float* __restrict__ partial,
+                                                     int rows, int d) {
+  __shared__ float red[16];
+  __shared__ float dots[RB];
+  const int64_t row0 = (int64_t)blockIdx.x * RB;
+  const int nr = (int)min((int64_t)RB, (int64_t)rows - row0);
+  for (int r = 0; r < nr; ++r) {
+    const int64_t row = row0 + r;
+    float acc = 0.f;
+    for (int j = threadIdx.x; j < d; j += blockDim.x)
+      acc += ldf(dnorm + row * d + j) * ldf(g + j) * ldf(xin + row * d + j);
+    acc = block_sum(acc, red);
+    if (threadIdx.x == 0) dots[r] = acc;
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < d; j += blockDim.x) {
+    const float gj = ldf(g + j);
+    float dgj = 0.f;
+    for (int r = 0; r < nr; ++r) {
+      const int64_t row = row0 + r;
+      const float rs = rstd[row];
+      const float xv = ldf(xin + row * d + j);
+      const float dn = ldf(dnorm + row * d + j);
+      dgj += dn * xv * rs;
+      const float v = (res ? ldf(res + row * d + j) : 0.f) + dn * gj * rs - xv * rs * rs * rs * dots[r] / (float)d;
+      if (out_f32) out_f32[row * d + j] = v;
+      if (out_t) stf(out_t + row * d + j, v);
+    }
+    partial[(int64_t)blockIdx.x * d + j] = dgj;
+  }
+}
+
+__global__ void colsum_accum_k(const float* __restrict__ partial, float* __restrict__ dg, int nblk, int d) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  float s = 0.f;
+  for (int b = 0; b < nblk; ++b) s += partial[(int64_t)b * d + j];
+  dg[j] += s;
+}
+
+size_t rmsnorm_bwd_partial_floats(int rows, int d) { return (size_t)cdiv(rows, RB) * (size_t)d; }
+
+hipError_t rmsnorm_bwd(int dt, const float* dnorm, const void* xin, bool x_is_f32, const void* g,
+                       const float* rstd, const void* res, bool res_is_f32, float* out_f32, void* out_t,
+                       float* dg, float* partial, int rows, int d, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  const int nblk = (int)cdiv(rows, RB);
+#define RB_LAUNCH(T, XT, RT)                                                                             \
+  rmsnorm_bwd_k<T, XT, RT><<<nblk, 256, 0, st>>>(dnorm, (const XT*)xin, (const T*)g, rstd, (const RT*)res, \
+                                                 out_f32, (T*)out_t, partial, rows, d)
+  DISPATCH_DT(dt, T, {
+    if (x_is_f32 && res_is_f32) RB_LAUNCH(T, float, float);
+    else if (x_is_f32) RB_LAUNCH(T, float, T);
+    else if (res_is_f32) RB_LAUNCH(T, T, float);
+    else RB_LAUNCH(T, T, T);
+  });
+#undef RB_LAUNCH
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  colsum_accum_k<<<(unsigned)cdiv(d, 256), 256, 0, st>>>(partial, dg, nblk, d);
+  return hipGetLastError();
+}
+
+// Stand-alone norm adjoint with the incoming gradient in the storage type and no
+// residual branch (the final norm between the layer stack and the LM head).
+hipError_t rmsnorm_bwd_plain(int dt, const void* dy, const void* x, const void* g, const float* rstd, void* dx,
+                             float* dg, float* partial, int rows, int d, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  const int nblk = (int)cdiv(rows, RB);
+  DISPATCH_DT(dt, T, (rmsnorm_bwd_k<T, T, T, T><<<nblk, 256, 0, st>>>((const T*)dy, (const T*)x, (const T*)g, rstd,
+                                                                     (const T*)nullptr, nullptr, (T*)dx, partial, rows, d)));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  colsum_accum_k<<<(unsigned)cdiv(d, 256), 256, 0, st>>>(partial, dg, nblk, d);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- SwiGLU --
+__device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+template <typename T>
+__global__ void swiglu_fwd_k(const T* __restrict__ gate, const T* __restrict__ up, T* __restrict__ act, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    float z = ldf(gate + i);
+    stf(act + i, z * sigmoidf_(z) * ldf(up + i));
+  }
+}
+template <typename T>
+__global__ void swiglu_bwd_k(T* __restrict__ gate, T* __restrict__ up, const T* __restrict__ dact, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    float z = ldf(gate + i), u = ldf(up + i), da = ldf(dact + i);
+    float sg = sigmoidf_(z);
+    stf(gate + i, da * u * sg * (1.0f + z * (1.0f - sg)));
+    stf(up + i, da * z * sg);
+  }
+}
+// 8 bf16 per lane (128-bit) variants for the wide MLP tensors
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+__global__ void swiglu_fwd_bf16x8_k(const bf16x8* __restrict__ gate, const bf16x8* __restrict__ up,
+                                    bf16x8* __restrict__ act, int64_t n8) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n8; i += stride) {
+    bf16x8 g = gate[i], u = up[i], a;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { float z = (float)g[j]; a[j] = (bf16_t)(z * sigmoidf_(z) * (float)u[j]); }
+    act[i] = a;
+  }
+}
+__global__ void swiglu_bwd_bf16x8_k(bf16x8* __restrict__ gate, bf16x8* __restrict__ up,
+                                    const bf16x8* __restrict__ dact, int64_t n8) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n8; i += stride) {
+    bf16x8 g = gate[i], u = up[i], da = dact[i], dg, du;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float z = (float)g[j], uu = (float)u[j], d = (float)da[j];
+      float sg = sigmoidf_(z);
+      dg[j] = (bf16_t)(d * uu * sg * (1.0f + z * (1.0f - sg)));
+      du[j] = (bf16_t)(d * z * sg);
+    }
+    gate[i] = dg; up[i] = du;
+  }
+}
+
+static inline unsigned ew_grid(int64_t n) { return (unsigned)std::min<int64_t>(cdiv(n, 256), 256 * 16); }
+
+hipError_t swiglu_fwd(int dt, const void* gate, const void* up, void* act, int64_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (dt == DT_BF16 && n % 8 == 0) {
+    swiglu_fwd_bf16x8_k<<<ew_grid(n / 8), 256, 0, st>>>((const bf16x8*)gate, (const bf16x8*)up, (bf16x8*)act, n / 8);
+  } else {
+    DISPATCH_DT(dt, T, (swiglu_fwd_k<T><<<ew_grid(n), 256, 0, st>>>((const T*)gate, (const T*)up, (T*)act, n)));
+  }
+  return hipGetLastError();
+}
+hipError_t swiglu_bwd(int dt, void* gate, void* up, const void* dact, int64_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (dt == DT_BF16 && n % 8 == 0) {
+    swiglu_bwd_bf16x8_k<<<ew_grid(n / 8), 256, 0, st>>>((bf16x8*)gate, (bf16x8*)up, (const bf16x8*)dact, n / 8);
+  } else {
+    DISPATCH_DT(dt, T, (swiglu_bwd_k<T><<<ew_grid(n), 256, 0, st>>>((T*)gate, (T*)up, (const T*)dact, n)));
+  }
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------ small glue --
+template <typename T>
+__global__ void add_store_k(const float* __restrict__ a, const float* __restrict__ b, T* __restrict__ y, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) stf(y + i, a[i] + b[i]);
+}
+hipError_t add_store(int dt, const float* a, const float* b, void* y, int64_t n, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  DISPATCH_DT(dt, T, (add_store_k<T><<<ew_grid(n), 256, 0, st>>>(a, b, (T*)y, n)));
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void kv_grad_finish_k(const float* __restrict__ dK, const float* __restrict__ dV,
+                                 const float2* __restrict__ tab, T* __restrict__ dkc, T* __restrict__ dvc,
+                                 int64_t n_pairs, int H, int half) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_pairs) return;
+  int j = (int)(i % half);
+  int64_t rh = i / half;
+  int64_t row = rh / H;
+  float2 cs = tab[row * half + j];
+  int64_t base = rh * (2 * half);
+  float a = dK[base + j], b = dK[base + j + half];
+  stf(dkc + base + j, a * cs.x + b * cs.y);            // rotation by the negative angle
+  stf(dkc + base + j + half, b * cs.x - a * cs.y);
+  stf(dvc + base + j, dV[base + j]);
+  stf(dvc + base + j + half, dV[base + j + half]);
+}
+hipError_t kv_grad_finish(int dt, const float* dK, const float* dV, const float2* tab, void* dkc, void* dvc,
+                          int rows, int H, int dh, hipStream_t st) {
+  int64_t n = (int64_t)rows * H * (dh / 2);
+  if (n == 0) return hipSuccess;
+  DISPATCH_DT(dt, T, (kv_grad_finish_k<T><<<(unsigned)cdiv(n, 256), 256, 0, st>>>(dK, dV, tab, (T*)dkc, (T*)dvc, n, H, dh / 2)));
+  return hipGetLastError();
+}
+
+__global__ void fill_zero_k(uint4* p, int64_t n16) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+__global__ void fill_zero_bytes_k(unsigned char* p, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+// A fill kernel rather than a memset node, so that callers may capture the stream into a graph.
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  size_t n16 = bytes / 16, tail = bytes - n16 * 16;
+  if (((uintptr_t)p & 15) != 0) { n16 = 0; tail = bytes; }
+  if (n16) fill_zero_k<<<ew_grid((int64_t)n16), 256, 0, st>>>((uint4*)p, (int64_t)n16);
+  if (tail) fill_zero_bytes_k<<<(unsigned)cdiv((int64_t)tail, 256), 256, 0, st>>>((unsigned char*)p + n16 * 16, (int64_t)tail);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void embedding_fwd_k(const int32_t* __restrict__ ids, const T* __restrict__ emb, T* __restrict__ x, int d) {
+  const int64_t row = blockIdx.x;
+  const int64_t id = ids[row];
+  for (int j = threadIdx.x; j < d; j += blockDim.x) x[row * d + j] = emb[id * d + j];
+}
+template <typename T>
+__global__ void embedding_bwd_k(const int32_t* __restrict__ ids, const T* __restrict__ dx, float* __restrict__ demb, int d) {
+  const int64_t row = blockIdx.x;
+  const int64_t id = ids[row];
+  for (int j = threadIdx.x; j < d; j += blockDim.x) atomicAdd(demb + id * d + j, ldf(dx + row * d + j));
+}
+hipError_t embedding_fwd(int dt, const int32_t* ids, const void* emb, void* x, int64_t rows, int d, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  DISPATCH_DT(dt, T, (embedding_fwd_k<T><<<(unsigned)rows, 256, 0, st>>>(ids, (const T*)emb, (T*)x, d)));
+  return hipGetLastError();
+}
+hipError_t embedding_bwd(int dt, const int32_t* ids, const void* dx, float* demb, int64_t rows, int d, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  DISPATCH_DT(dt, T, (embedding_bwd_k<T><<<(unsigned)rows, 256, 0, st>>>(ids, (const T*)dx, demb, d)));
+  return hipGetLastError();
+}
+
+}  // namespace sbp

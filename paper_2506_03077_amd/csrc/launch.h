@@ -1,0 +1,102 @@
+// Host-side launchers of the HIP kernels.  Every function only enqueues work on
+// `st`; none allocates or synchronises.  Shapes are validated by the callers in
+// api.hip before anything is launched.
+#pragma once
+#include "common.h"
+
+namespace sbp {
+
+// C[M,N] (=|+=) sum_k A(m,k) * B(k,n), fp32 accumulation.
+//   A(m,k) = ta ? A[k*lda + m] : A[m*lda + k]
+//   B(k,n) = tb ? B[n*ldb + k] : B[k*ldb + n]
+// in_dt: element type of A and B; out_dt: element type of C; acc: C += (fp32 C only).
+struct GemmArgs {
+  const void* A; const void* B; void* C;
+  int M, N, K;
+  int64_t lda, ldb, ldc;
+  bool ta, tb;
+  int in_dt, out_dt;
+  bool acc;
+};
+hipError_t gemm(const GemmArgs& g, hipStream_t st);
+// true when the bf16 MFMA kernel can take this problem (used by tests / tile accounting)
+bool gemm_uses_mfma(const GemmArgs& g);
+// force the generic kernel (debug / A-B tests)
+void gemm_set_force_generic(bool on);
+
+// ---- elementwise / row kernels (dt = storage type of the T-typed tensors) ----
+// cos/sin table [n_pos, dh/2] (float2), angles evaluated in fp64.
+hipError_t rope_table(float2* tab, int n_pos, int dh, float theta, int pos_offset, hipStream_t st);
+// in-place rotation of x [rows, H, dh]; tab points at the row of position 0 of these rows.
+hipError_t rope_apply(int dt, void* x, const float2* tab, int rows, int H, int dh, bool inverse, hipStream_t st);
+// out = g * (x + add) * rstd ; sum_out = x + add (fp32, optional) ; rstd per row
+hipError_t rmsnorm_fwd(int dt, const void* x, const float* add, const void* g, void* out, float* sum_out,
+                       float* rstd, int rows, int d, float eps, hipStream_t st);
+// adjoint: dnorm [rows,d] fp32 is the gradient wrt the normalised output.
+//   xin: the tensor that was normalised (x_is_f32 ? fp32 : dt);  res: gradient flowing around the norm
+//   (res_is_f32 ? fp32 : dt);  out_f32 / out_t (either may be NULL) = res + dx_norm;
+//   dg += column sums of dnorm * xin * rstd (two-stage, deterministic; `partial` >= cdiv(rows,8)*d floats)
+hipError_t rmsnorm_bwd(int dt, const float* dnorm, const void* xin, bool x_is_f32, const void* g,
+                       const float* rstd, const void* res, bool res_is_f32, float* out_f32, void* out_t,
+                       float* dg, float* partial, int rows, int d, hipStream_t st);
+size_t rmsnorm_bwd_partial_floats(int rows, int d);
+// dy, x, dx in dt; no residual branch
+hipError_t rmsnorm_bwd_plain(int dt, const void* dy, const void* x, const void* g, const float* rstd, void* dx,
+                             float* dg, float* partial, int rows, int d, hipStream_t st);
+// recompute rstd only (used when the statistic was not kept): not needed by the layer path
+hipError_t swiglu_fwd(int dt, const void* gate, const void* up, void* act, int64_t n, hipStream_t st);
+// in place: gate <- dgate, up <- dup, given dact
+hipError_t swiglu_bwd(int dt, void* gate, void* up, const void* dact, int64_t n, hipStream_t st);
+// y = T(a + b) with a, b fp32
+hipError_t add_store(int dt, const float* a, const float* b, void* y, int64_t n, hipStream_t st);
+// dkc = T(RoPE^T(dK rows)), dvc = T(dV rows);  dK, dV fp32 [rows, H, dh]
+hipError_t kv_grad_finish(int dt, const float* dK, const float* dV, const float2* tab, void* dkc, void* dvc,
+                          int rows, int H, int dh, hipStream_t st);
+hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t embedding_fwd(int dt, const int32_t* ids, const void* emb, void* x, int64_t rows, int d, hipStream_t st);
+hipError_t embedding_bwd(int dt, const int32_t* ids, const void* dx, float* demb, int64_t rows, int d, hipStream_t st);
+
+// ---- chunk attention ----
+struct AttnArgs {
+  int dt;
+  int Hq, Hkv, dh;
+  int q_start, q_len;
+  float scale;
+  const void *q, *k, *v;   // q [c,Hq,dh]; k,v [>=s+c,Hkv,dh]
+  void* o; float* lse;     // o [c,Hq,dh]; lse [Hq,c]
+  const void* d_o; void* dq; float *dk, *dv;
+  float* delta;            // [Hq,c] scratch (backward)
+};
+hipError_t attn_forward(const AttnArgs& a, hipStream_t st);
+hipError_t attn_backward(const AttnArgs& a, hipStream_t st);
+bool attn_uses_mfma(int dt, int dh, int Hq, int Hkv);
+void attn_set_force_generic(bool on);
+constexpr int ATTN_TILE_Q = 128;   // rows of queries per workgroup in the MFMA kernels
+constexpr int ATTN_TILE_K = 64;    // keys per inner step
+
+// ---- LM head rows ----
+struct HeadRowArgs {
+  int dt;                   // type of dz
+  int objective;            // 0 SFT, 1 GRPO, 2 DPO
+  const float* z;           // [rows, V] fp32 logits of the chunk
+  void* dz;                 // [rows, V] dt
+  const int32_t* targets;   // [rows] (already offset to the chunk)
+  const float* old_logp;    // [rows] or NULL
+  const float* ref_logp;    // [rows] or NULL
+  const float* advantages;  // [B] or NULL
+  const float* seq_weight;  // [B] GRPO: 1/(B*T_o,j); NULL otherwise
+  int64_t row0;             // global row index of the chunk's first row (row / T = sequence)
+  int rows, V, T;
+  float loss_scale, clip_eps, kl_beta; int kl_mode;
+  float* row_loss;          // [rows] scratch: per-row loss term (DPO: per-row signed log-ratio)
+};
+hipError_t head_rows(const HeadRowArgs& a, hipStream_t st);
+// loss += sum(row_loss[0..rows)) in a fixed order
+hipError_t reduce_add(const float* v, int n, float* out, hipStream_t st);
+// per-sequence active counts -> seq_weight[j] = 1/(B*T_o,j) (0 if empty), n_active total
+hipError_t count_active(const int32_t* targets, int B, int T, float* seq_weight, int64_t* n_active, hipStream_t st);
+// DPO fix-up: factor = sigmoid(beta*ell)-1 ; scales dh (dt) and dw (fp32) in place, loss += -log sigmoid(beta*ell)
+hipError_t dpo_finish(int dt, const float* ell, float beta, void* dh, int64_t n_dh, float* dw, int64_t n_dw,
+                      float* loss, hipStream_t st);
+
+}  // namespace sbp

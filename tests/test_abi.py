@@ -1,0 +1,116 @@
+"""The C-ABI library loads and exports every symbol include/streambp.h declares;
+host-side validation returns the documented error codes (no GPU needed: every
+check happens before the first HIP call)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2506_03077_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "streambp.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(streambp_\w+)\s*\(", src)))
+
+
+def test_header_declares_the_three_named_entry_points():
+    names = declared_functions()
+    for n in ("streambp_layer_backward", "streambp_lmhead_ce_backward", "streambp_attn_chunk_backward"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    L = sb.lib()
+    for n in declared_functions():
+        assert hasattr(L, n), n
+    assert b"gfx950" in L.streambp_version()
+
+
+def good_layer_cfg(**kw):
+    base = dict(dtype=sb.SBP_F32, batch=1, seq_len=256, chunk=64, hidden=64, n_q_heads=4, n_kv_heads=4,
+                head_dim=16, mlp_width=172)
+    base.update(kw)
+    return sb.layer_cfg(**base)
+
+
+def test_layer_workspace_has_no_full_sequence_activation_term():
+    # bytes = alpha*min(c,T) + beta*T*Hkv*dh + const: linear in T through K/V-side terms only
+    big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048)
+    w8, w16, w32 = (sb.streambp_layer_workspace_bytes(good_layer_cfg(seq_len=T, **big)) for T in (8192, 16384, 32768))
+    assert w8 > 0 and (w32 - w16) == 2 * (w16 - w8) // 1 and (w16 - w8) > 0
+    per_row = (w16 - w8) / 8192
+    kv_row = 4 * 128 * (2 + 2 + 4 + 4) + 64 * 8      # K, V (bf16), dK, dV (fp32), RoPE table
+    assert per_row == kv_row
+    # chunk >= T: nothing grows past T
+    assert sb.streambp_layer_workspace_bytes(good_layer_cfg(seq_len=100, chunk=10 ** 6)) == \
+        sb.streambp_layer_workspace_bytes(good_layer_cfg(seq_len=100, chunk=100))
+
+
+def test_head_workspace_is_per_chunk():
+    a = sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 152064))
+    b = sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_BF16, 1, 65536, 2048, 3584, 152064))
+    assert a == b and a < 2048 * 152064 * 6 + (1 << 20)          # chunk logits fp32 + dz bf16; no T*V term
+    assert a < 32768 * 152064 * 4 / 8
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_q_heads=4, n_kv_heads=3), -2), (dict(head_dim=15), -2), (dict(chunk=0), -2), (dict(seq_len=0), -2),
+    (dict(dtype=7), -3), (dict(head_dim=512), -2),
+])
+def test_layer_bad_config_codes(kw, code):
+    cfg = good_layer_cfg(**kw)
+    assert sb.streambp_layer_workspace_bytes(cfg) == 0
+    w = sb.LayerWeights(*[1] * 9)
+    g = sb.LayerGrads(*[1] * 9)
+    rc = sb.lib().streambp_layer_backward(C.byref(cfg), C.byref(w), 256, 512, 768, C.byref(g), 1024, 1 << 40, None)
+    assert rc == code
+    assert len(sb.lib().streambp_last_error()) > 0
+
+
+def test_layer_null_alias_and_workspace_codes():
+    cfg = good_layer_cfg()
+    L = sb.lib()
+    w = sb.LayerWeights(*[256] * 9)
+    g = sb.LayerGrads(*[256] * 9)
+    need = sb.streambp_layer_workspace_bytes(cfg)
+    assert L.streambp_layer_backward(C.byref(cfg), C.byref(w), None, 512, 768, C.byref(g), 1024, need, None) == -1
+    assert L.streambp_layer_backward(C.byref(cfg), C.byref(w), 256, 512, 256, C.byref(g), 1024, need, None) == -2
+    assert L.streambp_layer_backward(C.byref(cfg), C.byref(w), 256, 512, 768, C.byref(g), 1024, need - 1, None) == -4
+    assert L.streambp_layer_backward(C.byref(cfg), C.byref(w), 256, 512, 768, C.byref(g), 1025, need, None) == -4
+    w0 = sb.LayerWeights(*([256] * 8 + [None]))
+    assert L.streambp_layer_backward(C.byref(cfg), C.byref(w0), 256, 512, 768, C.byref(g), 1024, need, None) == -1
+
+
+def test_head_and_attn_codes():
+    L = sb.lib()
+    hc = sb.head_cfg(sb.SBP_F32, 1, 8, 4, 8, 16, objective=5)
+    assert sb.streambp_lmhead_workspace_bytes(hc) == 0
+    hc = sb.head_cfg(sb.SBP_F32, 1, 8, 4, 8, 16, objective=sb.SBP_OBJ_GRPO)
+    need = sb.streambp_lmhead_workspace_bytes(hc)
+    args = [256] * 4
+    assert L.streambp_lmhead_ce_backward(C.byref(hc), 256, 256, 256, None, None, None, 256, 256, 256, 256, 1024, need, None) == -1
+    hc = sb.head_cfg(sb.SBP_F32, 3, 8, 4, 8, 16, objective=sb.SBP_OBJ_DPO)
+    assert sb.streambp_lmhead_workspace_bytes(hc) == 0
+    ac = sb.attn_cfg(sb.SBP_BF16, 8, 3, 128, 0, 64, 0.1)
+    assert sb.streambp_attn_workspace_bytes(ac) == 0
+    ac = sb.attn_cfg(sb.SBP_BF16, 8, 2, 128, -1, 64, 0.1)
+    assert L.streambp_attn_chunk_forward(C.byref(ac), 256, 256, 256, 256, 256, None) == -2
+
+
+def test_attn_tile_pairs_follow_the_causal_count():
+    # Sec. 3.2.2: chunked causal attention touches about (1+D)/(2D) of the T x T square.
+    T, c = 32768, 2048
+    D = T // c
+    total = 0
+    for i in range(D):
+        n, tq, tk = sb.streambp_attn_tile_pairs(i * c, c)
+        total += n * tq * tk
+    exact = T * (T + 1) // 2
+    chunk_dense = (1 + D) * T * T // (2 * D)
+    assert exact <= total <= chunk_dense
+    assert total <= exact * 1.01                                  # tile skipping is nearly exact

@@ -1,0 +1,251 @@
+"""GPU parity: HIP path (through the C ABI) vs the fp64 CPU oracle, element by
+element on the same seeded inputs, at sizes the oracle finishes in seconds.
+Tolerances: norm-wise relative error per tensor <= 1e-4 (fp32 path), <= 2e-2
+(bf16 path); integer / mask behaviour bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attn as o_attn
+from oracle import head as o_head
+from oracle import layer as o_layer
+from paper_2506_03077_amd import binding as sb
+from paper_2506_03077_amd import synth
+
+from gpu_util import TOL, assert_close, code, dev, host, lib_layer_cfg, oracle_cfg, tdtype
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.CONFIGS["tiny"]
+# bf16 case spanning several MFMA tiles with ragged row counts (T = 2.5 chunks) and GQA
+MID16 = dict(dtype="bf16", hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=128, mlp_width=512, vocab=1024)
+# same shapes through the fp32 path
+MID32 = dict(MID16, dtype="f32")
+# shapes no MFMA tile divides, in bf16 storage (exercises the shape-agnostic kernels in bf16)
+ODD16 = dict(dtype="bf16", hidden=72, n_q_heads=6, n_kv_heads=2, head_dim=24, mlp_width=172, vocab=333)
+
+
+def run_layer_case(cfg, T, chunk, batch=1, seed=0, pos_offset=0):
+    cfg = dict(cfg, pos_offset=pos_offset)
+    inp = synth.layer_inputs(cfg, seed=seed, seq_len=T, batch=batch)
+    _, dx_ref, g_ref = o_layer.layer_forward_backward(inp["x"], inp["w"], oracle_cfg(cfg), inp["dy"])
+    dt = cfg["dtype"]
+    w = {k: dev(v, dt) for k, v in inp["w"].items()}
+    x, dy = dev(inp["x"], dt), dev(inp["dy"], dt)
+    dx, dw = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, chunk, batch), w, x, dy)
+    torch.cuda.synchronize()
+    tol = TOL[dt]
+    errs = {"dx": assert_close(host(dx), dx_ref, tol, f"dx (chunk {chunk})")}
+    for n in sb.WEIGHT_NAMES:
+        errs[n] = assert_close(host(dw[n]), g_ref[n], tol, f"d{n} (chunk {chunk})")
+    return errs
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 64, 100, 256, 1000])
+def test_layer_backward_tiny_fp32_every_chunk_size(chunk):
+    run_layer_case(TINY, 256, chunk)
+
+
+def test_layer_backward_tiny_fp32_batch_and_offset():
+    run_layer_case(TINY, 96, 40, batch=3, seed=3, pos_offset=11)
+
+
+@pytest.mark.parametrize("chunk", [128, 256, 640])
+def test_layer_backward_mid_bf16(chunk):
+    run_layer_case(MID16, 640, chunk)
+
+
+def test_layer_backward_mid_bf16_ragged_rows():
+    run_layer_case(MID16, 333, 100, batch=2, seed=1)
+
+
+def test_layer_backward_mid_fp32():
+    run_layer_case(MID32, 320, 128)
+
+
+def test_layer_backward_odd_shapes_bf16():
+    run_layer_case(ODD16, 150, 64, batch=2)
+
+
+def test_layer_forward_matches_oracle():
+    for cfg, T, chunk in ((TINY, 256, 64), (MID16, 333, 128)):
+        inp = synth.layer_inputs(cfg, seed=2, seq_len=T)
+        y_ref, _ = o_layer.layer_forward(inp["x"][0], inp["w"], oracle_cfg(cfg))
+        dt = cfg["dtype"]
+        w = {k: dev(v, dt) for k, v in inp["w"].items()}
+        y = sb.streambp_layer_forward(lib_layer_cfg(cfg, T, chunk), w, dev(inp["x"], dt))
+        assert_close(host(y)[0], y_ref, TOL[dt] if dt == "f32" else 1e-2, "y")
+
+
+def test_layer_backward_is_reproducible_and_chunk_invariant():
+    cfg, T = MID16, 640
+    inp = synth.layer_inputs(cfg, seed=4, seq_len=T)
+    w = {k: dev(v, "bf16") for k, v in inp["w"].items()}
+    x, dy = dev(inp["x"], "bf16"), dev(inp["dy"], "bf16")
+    a = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, 256), w, x, dy)
+    b = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, 256), w, x, dy)
+    assert torch.equal(a[0], b[0]) and all(torch.equal(a[1][n], b[1][n]) for n in sb.WEIGHT_NAMES)
+    c = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, 128), w, x, dy)
+    for n in sb.WEIGHT_NAMES:       # chunk size changes only the rounding order
+        assert_close(host(c[1][n]), host(a[1][n]), 1e-2, n)
+
+
+def test_gradients_accumulate_into_dw():
+    cfg, T = TINY, 64
+    inp = synth.layer_inputs(cfg, seed=5, seq_len=T)
+    w = {k: dev(v, "f32") for k, v in inp["w"].items()}
+    x, dy = dev(inp["x"], "f32"), dev(inp["dy"], "f32")
+    lc = lib_layer_cfg(cfg, T, 32)
+    _, g1 = sb.streambp_layer_backward(lc, w, x, dy)
+    g2 = {n: t.clone() for n, t in g1.items()}
+    sb.streambp_layer_backward(lc, w, x, dy, dw=g2)
+    for n in sb.WEIGHT_NAMES:
+        assert_close(host(g2[n]), 2 * host(g1[n]), 1e-6, n)
+
+
+# ------------------------------------------------------------------- head ---
+def head_case(cfg, B, T, chunk, objective, seed=0, **kw):
+    inp = synth.head_inputs(cfg, seed=seed, seq_len=T, batch=B, vocab=cfg["vocab"])
+    dt = cfg["dtype"]
+    h, w, tg = dev(inp["h"], dt), dev(inp["w"], dt), torch.from_numpy(inp["targets"]).cuda()
+    extras = synth.grpo_extras(B, T, seed)
+    if objective == "sft":
+        ref = o_head.sft(inp["h"], inp["w"], inp["targets"], kw.get("loss_scale", 1.0))
+        hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, kw.get("loss_scale", 1.0))
+        out = sb.streambp_lmhead_ce_backward(hc, w, h, tg)
+    elif objective == "grpo":
+        old = kw.get("old")
+        ref = o_head.grpo(inp["h"], inp["w"], inp["targets"], extras["advantages"], extras["ref_logp"], old,
+                          0.2, 0.04, kw.get("kl_mode", 0))
+        hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_GRPO, 1.0, 0.2, 0.04,
+                         kw.get("kl_mode", 0))
+        out = sb.streambp_lmhead_ce_backward(
+            hc, w, h, tg, None if old is None else torch.from_numpy(old.astype(np.float32)).cuda(),
+            torch.from_numpy(extras["ref_logp"]).cuda(), torch.from_numpy(extras["advantages"]).cuda())
+    else:
+        ref = o_head.dpo(inp["h"], inp["w"], inp["targets"], extras["ref_logp"], beta=0.3)
+        hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_DPO, 1.0, 0.2, 0.3, 0)
+        out = sb.streambp_lmhead_ce_backward(hc, w, h, tg, None, torch.from_numpy(extras["ref_logp"]).cuda(), None)
+    torch.cuda.synchronize()
+    dh, dw, loss, n_active = out
+    tol = TOL[dt]
+    assert int(n_active.item()) == ref["n_active"]                       # integer: exact
+    assert_close(host(dh), ref["dh"], tol, "dh")
+    assert_close(host(dw), ref["dw"], tol, "dw")
+    assert abs(float(loss.item()) - ref["loss"]) <= tol * max(1.0, abs(ref["loss"])), (float(loss.item()), ref["loss"])
+    masked = torch.from_numpy(inp["targets"] < 0).cuda()
+    assert torch.all(dh[masked] == 0)                                    # ignored rows: exact zeros
+    return inp, ref
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 64, 100, 256, 1000])
+def test_head_sft_tiny_fp32_every_chunk_size(chunk):
+    head_case(TINY, 1, 256, chunk, "sft", loss_scale=1.0 / 192)
+
+
+def test_head_sft_unnormalised_and_batch():
+    head_case(TINY, 3, 50, 64, "sft", loss_scale=1.0, seed=2)
+
+
+@pytest.mark.parametrize("cfg", [MID16, ODD16])
+def test_head_sft_bf16(cfg):
+    head_case(cfg, 2, 300, 128, "sft", loss_scale=1.0 / 450)
+
+
+@pytest.mark.parametrize("kl_mode", [0, 1])
+def test_head_grpo_on_policy(kl_mode):
+    head_case(TINY, 4, 64, 48, "grpo", kl_mode=kl_mode)
+    head_case(MID16, 2, 300, 128, "grpo", kl_mode=kl_mode)
+
+
+def test_head_grpo_off_policy_with_clipping():
+    inp = synth.head_inputs(TINY, seed=0, seq_len=64, batch=4, vocab=TINY["vocab"])
+    base = o_head.sft(inp["h"], inp["w"], inp["targets"])
+    old = base["logp"] + np.random.default_rng(3).normal(0, 0.3, base["logp"].shape)   # ratios on both sides of the clip
+    head_case(TINY, 4, 64, 48, "grpo", old=old, kl_mode=1)
+
+
+def test_head_dpo():
+    head_case(TINY, 2, 64, 24, "dpo")
+
+
+# -------------------------------------------------------------- attention ---
+def attn_case(dtype, Hq, Hkv, dh, s, c, seed=0, extra_rows=0):
+    inp = synth.attn_inputs(Hq, Hkv, dh, s, c, dtype, seed)
+    scale = 1.0 / np.sqrt(dh)
+    o_ref, lse_ref = o_attn.chunk_forward(inp["q"], inp["k"], inp["v"], s, scale)
+    dq_ref, dk_ref, dv_ref = o_attn.chunk_backward(inp["q"], inp["k"], inp["v"], inp["d_o"], s, scale)
+    q, k, v, d_o = (dev(inp[n], dtype) for n in ("q", "k", "v", "d_o"))
+    if extra_rows:      # rows past the chunk end must never be read (Property 3.1): poison them
+        pad = torch.full((extra_rows, Hkv, dh), float("nan"), dtype=k.dtype, device="cuda")
+        k, v = torch.cat([k, pad]), torch.cat([v, pad])
+    ac = sb.attn_cfg(code(dtype), Hq, Hkv, dh, s, c, scale)
+    o, lse = sb.streambp_attn_chunk_forward(ac, q, k, v)
+    dq, dk, dv = sb.streambp_attn_chunk_backward(ac, q, k, v, o, lse, d_o)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert_close(host(o), o_ref, tol, "o")
+    assert_close(host(lse), lse_ref, 1e-4 if dtype == "f32" else 2e-3, "lse")
+    assert_close(host(dq), dq_ref, tol, "dq")
+    assert_close(host(dk)[:s + c], dk_ref, tol, "dk")
+    assert_close(host(dv)[:s + c], dv_ref, tol, "dv")
+    if extra_rows:
+        assert torch.all(dk[s + c:] == 0) and torch.all(dv[s + c:] == 0)
+    return o, lse, dq, dk, dv
+
+
+def test_attn_fp32_generic():
+    attn_case("f32", 4, 4, 16, 0, 64)
+    attn_case("f32", 4, 2, 16, 100, 37, extra_rows=5)
+    attn_case("f32", 6, 2, 24, 300, 1)
+
+
+@pytest.mark.parametrize("s,c", [(0, 128), (0, 200), (256, 128), (300, 77), (1, 1), (513, 255)])
+def test_attn_bf16_dh128(s, c):
+    attn_case("bf16", 8, 2, 128, s, c, extra_rows=3)
+
+
+def test_attn_empty_chunk_is_a_no_op():
+    q = torch.empty((0, 4, 16), device="cuda")
+    k = torch.randn((8, 4, 16), device="cuda")
+    ac = sb.attn_cfg(sb.SBP_F32, 4, 4, 16, 8, 0, 0.25)
+    o, lse = sb.streambp_attn_chunk_forward(ac, q, k, k)
+    assert o.numel() == 0
+
+
+def test_attn_dkv_accumulates():
+    inp = synth.attn_inputs(4, 2, 16, 10, 20, "f32", 1)
+    q, k, v, d_o = (dev(inp[n], "f32") for n in ("q", "k", "v", "d_o"))
+    ac = sb.attn_cfg(sb.SBP_F32, 4, 2, 16, 10, 20, 0.25)
+    o, lse = sb.streambp_attn_chunk_forward(ac, q, k, v)
+    _, dk, dv = sb.streambp_attn_chunk_backward(ac, q, k, v, o, lse, d_o)
+    dk2, dv2 = dk.clone(), dv.clone()
+    sb.streambp_attn_chunk_backward(ac, q, k, v, o, lse, d_o, dk=dk2, dv=dv2)
+    assert_close(host(dk2), 2 * host(dk), 1e-6, "dk")
+    assert_close(host(dv2), 2 * host(dv), 1e-6, "dv")
+
+
+# ------------------------------------------------------------- stack glue ---
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rmsnorm_and_embedding(dtype):
+    rng = np.random.default_rng(0)
+    n, d, V = 77, 200, 50
+    x = synth.to_storage(rng.normal(size=(n, d)), dtype)
+    g = synth.to_storage(1 + rng.normal(0, 0.1, d), dtype)
+    dy = synth.to_storage(rng.normal(size=(n, d)), dtype)
+    a_ref, r = o_layer.rmsnorm_forward(x, g, 1e-6)
+    dx_ref, dg_ref = o_layer.rmsnorm_backward(np.asarray(dy, np.float64), x, g, r)
+    y = sb.streambp_rmsnorm_forward(dev(x, dtype), dev(g, dtype), 1e-6)
+    dx, dg = sb.streambp_rmsnorm_backward(dev(x, dtype), dev(g, dtype), dev(dy, dtype), 1e-6)
+    tol = 1e-5 if dtype == "f32" else 5e-3
+    assert_close(host(y), a_ref, tol, "y")
+    assert_close(host(dx), dx_ref, tol, "dx")
+    assert_close(host(dg), dg_ref, tol, "dg")
+    ids = torch.from_numpy(rng.integers(0, V, n).astype(np.int32)).cuda()
+    emb = dev(synth.to_storage(rng.normal(size=(V, d)), dtype), dtype)
+    xe = sb.streambp_embedding_forward(ids, emb)
+    assert torch.equal(xe, emb[ids.long()])                                 # gather: bit-exact
+    demb = sb.streambp_embedding_backward(ids, dev(dy, dtype), V)
+    want = np.zeros((V, d))
+    np.add.at(want, ids.cpu().numpy(), np.asarray(dy, np.float64))
+    assert_close(host(demb), want, 1e-6, "demb")
