@@ -52,6 +52,7 @@ struct LayerWs {
   void *a, *q, *o, *m, *gate, *up, *act, *dh1_t, *d_o, *dq, *dkc, *dvc;   // per chunk, dt
   float *h1, *dm, *dh1, *da, *proj;                                       // per chunk, fp32 [c, d]
   float *rstd1, *rstd2, *lse, *delta, *partial;
+  float* gemm_scratch; size_t gemm_scratch_bytes;
   size_t bytes;
 };
 
@@ -101,13 +102,21 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   w.lse = cv.take<float>(cm * c->n_q_heads);
   w.delta = cv.take<float>(cm * c->n_q_heads);
   w.partial = cv.take<float>(rmsnorm_bwd_partial_floats((int)cm, (int)d));
+  w.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, (int)std::max(d, qd)) : 0;
+  w.gemm_scratch = (float*)cv.take_bytes(w.gemm_scratch_bytes);
   w.bytes = cv.off;
   return w;
 }
 
+// split-K scratch of the entry point currently running on this host thread
+thread_local float* t_gemm_scratch = nullptr;
+thread_local size_t t_gemm_scratch_bytes = 0;
+
 GemmArgs mk(const void* A, const void* B, void* C, int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc,
             bool ta, bool tb, int in_dt, int out_dt, bool acc) {
   GemmArgs g{A, B, C, M, N, K, lda, ldb, ldc, ta, tb, in_dt, out_dt, acc};
+  g.scratch = t_gemm_scratch;
+  g.scratch_bytes = t_gemm_scratch_bytes;
   return g;
 }
 // Y[M,N] = X[M,K] W[N,K]^T
@@ -201,6 +210,7 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
   if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
 
   hipStream_t st = (hipStream_t)hip_stream;
+  t_gemm_scratch = s.gemm_scratch; t_gemm_scratch_bytes = s.gemm_scratch_bytes;
   const int dt = c->dtype;
   const size_t es = dtype_size(dt);
   const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden, F = c->mlp_width;
@@ -267,6 +277,7 @@ int32_t streambp_layer_forward(const sbp_layer_cfg* c, const sbp_layer_weights* 
   const LayerWs s = carve_layer(c, workspace);
   if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
   hipStream_t st = (hipStream_t)hip_stream;
+  t_gemm_scratch = s.gemm_scratch; t_gemm_scratch_bytes = s.gemm_scratch_bytes;
   const int dt = c->dtype;
   const size_t es = dtype_size(dt);
   const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden, F = c->mlp_width;
@@ -296,7 +307,7 @@ static int32_t check_head_cfg(const sbp_head_cfg* c) {
   return SBP_OK;
 }
 
-struct HeadWs { float* z; void* dz; float *row_loss, *seq_weight, *ell; size_t bytes; };
+struct HeadWs { float* z; void* dz; float *row_loss, *seq_weight, *ell; float* gemm_scratch; size_t gemm_scratch_bytes; size_t bytes; };
 static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   const int64_t rows = (int64_t)c->batch * c->seq_len;
   const size_t cm = (size_t)std::min<int64_t>(c->chunk, rows);
@@ -307,6 +318,8 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   h.row_loss = cv.take<float>(cm);
   h.seq_weight = cv.take<float>(c->batch);
   h.ell = cv.take<float>(1);
+  h.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, c->hidden) : 0;
+  h.gemm_scratch = (float*)cv.take_bytes(h.gemm_scratch_bytes);
   h.bytes = cv.off;
   return h;
 }
@@ -333,6 +346,7 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
   hipStream_t st = (hipStream_t)hip_stream;
   const int dt = c->dtype;
   const size_t es = dtype_size(dt);
+  t_gemm_scratch = s.gemm_scratch; t_gemm_scratch_bytes = s.gemm_scratch_bytes;
   const int64_t rows = (int64_t)c->batch * c->seq_len;
   const int cm = (int)std::min<int64_t>(c->chunk, rows);
   const int d = c->hidden, V = c->vocab;

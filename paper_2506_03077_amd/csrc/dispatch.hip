@@ -38,3 +38,14 @@ extern "C" void streambp_debug_force_generic(int gemm_on, int attn_on) {
   sbp::gemm_set_force_generic(gemm_on != 0);
   sbp::attn_set_force_generic(attn_on != 0);
 }
+
+// Direct access to the GEMM dispatcher for unit tests and kernel timing (not part of the public header).
+extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_dt, int out_dt, int acc, const void* A,
+                                   const void* B, void* C, long long lda, long long ldb, long long ldc, void* scratch,
+                                   size_t scratch_bytes, void* stream) {
+  sbp::GemmArgs g{A, B, C, M, N, K, lda, ldb, ldc, ta != 0, tb != 0, in_dt, out_dt, acc != 0};
+  g.scratch = (float*)scratch;
+  g.scratch_bytes = scratch_bytes;
+  hipError_t e = sbp::gemm(g, (hipStream_t)stream);
+  return e == hipSuccess ? (sbp::gemm_uses_mfma(g) ? 1 : 0) : -5;
+}

@@ -1,6 +1,308 @@
-// placeholder until the MFMA GEMM lands
+// bf16 MFMA GEMM for gfx950, fp32 accumulation, three operand layouts:
+//   NT  C[M,N] = A[M,K] B[N,K]^T     (forward projections: both operands K-contiguous)
+//   NN  C[M,N] = A[M,K] B[K,N]       (input gradients dX = dY W)
+//   TN  C[M,N] = A[K,M]^T B[K,N]     (weight gradients dW += dY^T X; K = chunk rows)
+//
+// Design (CDNA4):
+//  * 256x256 output tile per workgroup, 8 wavefronts (2 x 4), each wave owns a
+//    128x64 sub-tile = 4x2 v_mfma_f32_32x32x16_bf16 accumulators (128 AGPRs).
+//  * Operand tiles (256 x 64 bf16 each) go HBM -> LDS with 128-bit direct-to-LDS
+//    loads (no VGPR staging), double-buffered: tile kt+1 streams in while tile kt
+//    is consumed; one barrier per K step.
+//  * K-contiguous operands are read from LDS with ds_read_b128; operands whose
+//    reduction index is the slow dimension in memory are kept in their natural
+//    [k][m|n] layout in LDS and fetched with the transposing LDS load
+//    (ds_read_b64_tr_b16), so no transposed copy ever exists in HBM.
+//  * Both LDS layouts are XOR-swizzled (at 16-byte / 64-byte granularity) so that
+//    the fragment reads are bank-conflict free; because a direct-to-LDS load
+//    writes lane-linear, the swizzle is applied on the global-address side.
+//  * Workgroups are renumbered so that each XCD (own L2) works on a contiguous
+//    band of output tiles that share operand panels.
+//  * Ragged M (last chunk) is handled by clamping row loads and masking stores;
+//    ragged K in the TN form (chunk rows) by clamping loads and zeroing the A
+//    fragments of the out-of-range reduction rows.
+//  * Optional split-K (grid.z): partial tiles go to an fp32 scratch and a small
+//    kernel sums them in a fixed order (deterministic) into C.
 #include "launch.h"
+
+#include <algorithm>
+
 namespace sbp {
-bool gemm_mfma_eligible(const GemmArgs&) { return false; }
-hipError_t gemm_mfma(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define LDS_AS(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int NWAVE_M = 2, NWAVE_N = 4;
+constexpr int NTHREADS = NWAVE_M * NWAVE_N * 64;      // 512
+constexpr int WTM = BM / NWAVE_M, WTN = BN / NWAVE_N;  // 128 x 64 per wave
+constexpr int FM = WTM / 32, FN = WTN / 32;            // 4 x 2 MFMA tiles
+constexpr int TILE_BYTES = BM * BK * 2;                // 32 KiB per operand tile
+constexpr int LOADS_PER_THREAD = TILE_BYTES / 16 / NTHREADS;   // 4 x 16 B per operand
+
+// ---- K-contiguous operand: LDS [rows][BK], 128 B per row, 8 chunks of 16 B, chunk ^= (row>>1)&7
+__device__ __forceinline__ int kmaj_off(int row, int chunk) { return row * (BK * 2) + ((chunk ^ ((row >> 1) & 7)) << 4); }
+
+// ---- reduction-major operand: LDS [BK][rows], 512 B per k-row, 64-byte groups ^= krow&7
+__device__ __forceinline__ int mnmaj_off(int krow, int col /*element*/) {
+  const int c16 = col >> 3;
+  const int p16 = ((((c16 >> 2) ^ (krow & 7)) << 2) | (c16 & 3));
+  return krow * (BM * 2) + (p16 << 4) + ((col & 7) << 1);
 }
+
+// Issue this thread's share of one operand tile (direct-to-LDS, 16 B per lane).
+//   KMAJ : tile rows r0..r0+255 (clamped to r_max), k columns k0..k0+63
+//   MNMAJ: tile k-rows k0..k0+63 (clamped to k_max), columns c0..c0+255
+template <bool MNMAJ>
+__device__ __forceinline__ void load_tile(const bf16_t* __restrict__ g, int64_t ld, int r0, int r_max, int k0, int k_max,
+                                          char* lds_tile) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < LOADS_PER_THREAD; ++i) {
+    const int id = i * NTHREADS + tid;            // 16-byte slot in the tile, lane-linear within a wave
+    const bf16_t* src;
+    if (!MNMAJ) {
+      const int row = id >> 3, pc = id & 7;
+      const int chunk = pc ^ ((row >> 1) & 7);
+      src = g + (int64_t)min(r0 + row, r_max) * ld + k0 + chunk * 8;
+    } else {
+      const int krow = id >> 5, p16 = id & 31;
+      const int c16 = ((((p16 >> 2) ^ (krow & 7)) << 2) | (p16 & 3));
+      src = g + (int64_t)min(k0 + krow, k_max) * ld + r0 + c16 * 8;
+    }
+    // LDS destination of the wave = slot of lane 0; lanes land at +16 B each.
+    char* dst = lds_tile + (size_t)(i * NTHREADS + (tid & ~63)) * 16;
+    __builtin_amdgcn_global_load_lds(src, LDS_AS(dst), 16, 0, 0);
+  }
+}
+
+// Fragment of a 32-row block for one k16 step: lane l holds row (l%32), k = 8*(l/32)+0..7.
+template <bool MNMAJ>
+__device__ __forceinline__ bf16x8 load_frag(const char* lds_tile, int row_base, int kk) {
+  const int l = threadIdx.x & 63;
+  if (!MNMAJ) {
+    return *(const bf16x8*)(lds_tile + kmaj_off(row_base + (l & 31), kk * 2 + (l >> 5)));
+  } else {
+    // transposing load: in each group of 16 lanes, lane p supplies the address of 4 consecutive columns of
+    // k-row (p/4); lane i receives the 4 k-values of column i.
+    const int p = l & 15, g = l >> 4;
+    const int col = row_base + 16 * (g & 1) + 4 * (p & 3);
+    const int krow = kk * 16 + 8 * (g >> 1) + (p >> 2);
+    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(lds_tile + mnmaj_off(krow, col)));
+    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(lds_tile + mnmaj_off(krow + 4, col)));
+    typedef short short8v __attribute__((ext_vector_type(8)));
+    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+  }
+}
+
+template <bool TA, bool TB>
+__device__ __forceinline__ void compute_tile(const char* sA, const char* sB, int wm0, int wn0, f32x16 (&acc)[FM][FN],
+                                             int k_valid /* reduction rows valid in this tile (TN tail) */) {
+#pragma unroll
+  for (int kk = 0; kk < BK / 16; ++kk) {
+    bf16x8 a[FM], b[FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) a[i] = load_frag<TA>(sA, wm0 + i * 32, kk);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) b[j] = load_frag<TB>(sB, wn0 + j * 32, kk);
+    if (TA && k_valid < BK) {   // zero reduction rows past the end (A only: B rows are finite duplicates)
+      const int kbase = kk * 16 + 8 * ((threadIdx.x & 63) >> 5);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (kbase + e >= k_valid) a[i][e] = (bf16_t)0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+}
+
+// blockIdx.x -> (tile_m, tile_n).  Hardware deals consecutive workgroups round-robin to the 8 XCDs; undo
+// that so each XCD gets a contiguous run of tile ids, then walk tiles in column bands of GROUP_M row tiles
+// so that the workgroups resident together share A row panels and B column panels in that XCD's L2.
+__device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int n_tiles = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  constexpr int NXCD = 8;
+  if (n_tiles % NXCD == 0) id = (id % NXCD) * (n_tiles / NXCD) + id / NXCD;
+  constexpr int GROUP_M = 8;
+  const int band = GROUP_M * tiles_n;
+  const int g = id / band;
+  const int first_m = g * GROUP_M;
+  const int gsz = min(tiles_m - first_m, GROUP_M);
+  const int r = id % band;
+  tm = first_m + r % gsz;
+  tn = r / gsz;
+}
+
+// MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store to scratch slice z)
+template <bool TA, bool TB, int MODE>
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                        void* __restrict__ Cv, int M, int N, int K, int64_t lda,
+                                                        int64_t ldb, int64_t ldc, int k_per_split) {
+  __shared__ __attribute__((aligned(1024))) char sA0[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sB0[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sA1[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sB1[TILE_BYTES];
+
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  int tm, tn;
+  tile_coords(tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm0 = (wave / NWAVE_N) * WTM, wn0 = (wave % NWAVE_N) * WTN;
+
+  const int k_begin = blockIdx.z * k_per_split;
+  const int k_end = min(K, k_begin + k_per_split);
+  const int nk = (k_end - k_begin + BK - 1) / BK;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // A tile: !TA -> rows are m (clamp to M-1), TA -> rows are k (clamp to K-1), columns m (M % BM == 0 required)
+  auto issue = [&](int kt, char* sA, char* sB) {
+    const int k0 = k_begin + kt * BK;
+    load_tile<TA>(A, lda, m0, M - 1, k0, K - 1, sA);
+    load_tile<!TB>(B, ldb, n0, N - 1, k0, K - 1, sB);   // TB (B stored [N,K]) is the K-contiguous case
+  };
+
+  if (nk > 0) issue(0, sA0, sB0);
+  for (int kt = 0; kt < nk; kt += 2) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's share of tile kt has landed
+    __syncthreads();                      // everyone's share has; everyone is done reading the other stage
+    if (kt + 1 < nk) issue(kt + 1, sA1, sB1);
+    compute_tile<TA, !TB>(sA0, sB0, wm0, wn0, acc, k_end - (k_begin + kt * BK));
+    if (kt + 1 < nk) {
+      __builtin_amdgcn_s_waitcnt(0x0f70);
+      __syncthreads();
+      if (kt + 2 < nk) issue(kt + 2, sA0, sB0);
+      compute_tile<TA, !TB>(sA1, sB1, wm0, wn0, acc, k_end - (k_begin + (kt + 1) * BK));
+    }
+  }
+
+  // Epilogue.  Accumulator register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+  float* Cf = (float*)Cv;
+  bf16_t* Cb = (bf16_t*)Cv;
+  if (MODE == 3) Cf += (int64_t)blockIdx.z * M * ldc;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (row < M) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int64_t idx = (int64_t)row * ldc + n0 + wn0 + j * 32 + (lane & 31);
+          const float v = acc[i][j][r];
+          if (MODE == 1) Cb[idx] = (bf16_t)v;
+          else if (MODE == 2) Cf[idx] += v;
+          else Cf[idx] = v;
+        }
+      }
+    }
+}
+
+// C (=|+=) sum_z partial[z] in a fixed order; OUT_BF16 rounds once at the end.
+template <bool OUT_BF16, bool ACC>
+__global__ void splitk_reduce_k(const float* __restrict__ part, void* __restrict__ C, int64_t n, int splits) {
+  int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  float4 s = *(const float4*)(part + i);
+  for (int z = 1; z < splits; ++z) {
+    const float4 t = *(const float4*)(part + (int64_t)z * n + i);
+    s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+  }
+  if (OUT_BF16) {
+    bf16x4 o; o[0] = (bf16_t)s.x; o[1] = (bf16_t)s.y; o[2] = (bf16_t)s.z; o[3] = (bf16_t)s.w;
+    *(bf16x4*)((bf16_t*)C + i) = o;
+  } else {
+    float4* c = (float4*)((float*)C + i);
+    if (ACC) { float4 t = *c; s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w; }
+    *c = s;
+  }
+}
+
+bool gemm_mfma_eligible(const GemmArgs& g) {
+  if (g.in_dt != DT_BF16) return false;
+  if (g.acc && g.out_dt != DT_F32) return false;
+  if (g.M < 1 || g.N < BN || g.K < 1) return false;
+  if (g.N % BN != 0) return false;
+  if (g.ta && !g.tb) {                       // TN: both operands reduction-major; ragged K allowed
+    if (g.M % BM != 0) return false;
+  } else if (!g.ta) {                        // NT / NN
+    if (g.K % BK != 0) return false;
+  } else {
+    return false;                            // TT is never needed
+  }
+  if (g.lda % 8 || g.ldb % 8) return false;
+  if (((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15) || ((uintptr_t)g.C & 15)) return false;
+  if (g.ldc % 4) return false;
+  return true;
+}
+
+constexpr int MAX_SPLITS = 4;
+// Split-K factor: fill the 256 CUs when the output has few tiles and K is long.
+int gemm_mfma_splits(const GemmArgs& g) {
+  const int64_t tiles = cdiv(g.M, BM) * (g.N / BN);
+  const int k_tiles = (int)cdiv(g.K, BK);
+  if (tiles >= 200 || k_tiles < 16) return 1;
+  int s = (int)std::min<int64_t>(256 / tiles, k_tiles / 8);   // largest split that still fits one round of 256 CUs
+  return std::max(1, std::min(s, MAX_SPLITS));
+}
+
+size_t gemm_scratch_bytes(int max_m, int max_n) { return (size_t)MAX_SPLITS * max_m * max_n * sizeof(float); }
+
+hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
+  const int tiles_m = (int)cdiv(g.M, BM), tiles_n = g.N / BN;
+  int splits = gemm_mfma_splits(g);
+  if (splits > 1 && (g.scratch == nullptr || g.scratch_bytes < (size_t)splits * g.M * g.ldc * sizeof(float) || g.ldc != g.N))
+    splits = 1;
+  int k_per_split = g.K;
+  if (splits > 1) {
+    k_per_split = (int)(cdiv(cdiv(g.K, BK), splits) * BK);
+    splits = (int)cdiv(g.K, k_per_split);
+  }
+  dim3 grid(tiles_m * tiles_n, 1, splits);
+  const bf16_t* A = (const bf16_t*)g.A;
+  const bf16_t* B = (const bf16_t*)g.B;
+#define LAUNCH(TA, TB, MODE, CPTR) \
+  gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split)
+#define LAUNCH_LAYOUT(MODE, CPTR)                       \
+  do {                                                  \
+    if (!g.ta && g.tb) LAUNCH(false, true, MODE, CPTR); \
+    else if (!g.ta && !g.tb) LAUNCH(false, false, MODE, CPTR); \
+    else LAUNCH(true, false, MODE, CPTR);               \
+  } while (0)
+  if (splits > 1) {
+    LAUNCH_LAYOUT(3, (void*)g.scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t n = (int64_t)g.M * g.N;
+    const unsigned blocks = (unsigned)cdiv(n / 4, 256);
+    if (g.out_dt == DT_BF16) splitk_reduce_k<true, false><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
+    else if (g.acc) splitk_reduce_k<false, true><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
+    else splitk_reduce_k<false, false><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
+    return hipGetLastError();
+  }
+  if (g.out_dt == DT_BF16) LAUNCH_LAYOUT(1, g.C);
+  else if (g.acc) LAUNCH_LAYOUT(2, g.C);
+  else LAUNCH_LAYOUT(0, g.C);
+#undef LAUNCH_LAYOUT
+#undef LAUNCH
+  return hipGetLastError();
+}
+
+}  // namespace sbp

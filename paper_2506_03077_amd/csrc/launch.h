@@ -17,7 +17,11 @@ struct GemmArgs {
   bool ta, tb;
   int in_dt, out_dt;
   bool acc;
+  float* scratch = nullptr;      // optional fp32 scratch for split-K partial tiles
+  size_t scratch_bytes = 0;
 };
+// upper bound of the scratch a GEMM with M <= max_m rows and N <= max_n columns may use
+size_t gemm_scratch_bytes(int max_m, int max_n);
 hipError_t gemm(const GemmArgs& g, hipStream_t st);
 // true when the bf16 MFMA kernel can take this problem (used by tests / tile accounting)
 bool gemm_uses_mfma(const GemmArgs& g);

@@ -1,0 +1,106 @@
+"""GPU unit tests of the GEMM dispatcher (MFMA kernel and shape-agnostic kernel)
+against numpy fp64 products of the same bf16-rounded inputs.  The closed form
+of the paper's linear example (App. A.1) is checked too: with L = sum(Z),
+dW2 = Y^T 1 and dW1 = X^T (1 W2^T), accumulated chunk by chunk."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_03077_amd import binding as sb
+from paper_2506_03077_amd import synth
+
+from gpu_util import assert_close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def run(M, N, K, ta, tb, out="f32", acc=False, seed=0, expect_mfma=None, dtype="bf16"):
+    rng = np.random.default_rng(seed)
+    A = synth.to_storage(rng.normal(size=(K, M) if ta else (M, K)), dtype)
+    B = synth.to_storage(rng.normal(size=(N, K) if tb else (K, N)), dtype)
+    C0 = rng.normal(size=(M, N)).astype(np.float32) if acc else np.zeros((M, N), np.float32)
+    opA = A.T.astype(np.float64) if ta else A.astype(np.float64)
+    opB = B.T.astype(np.float64) if tb else B.astype(np.float64)
+    want = opA @ opB + C0
+    Cd = dev(C0, out) if acc else torch.full((M, N), float("nan"), device="cuda",
+                                            dtype=torch.bfloat16 if out == "bf16" else torch.float32)
+    scratch = torch.empty(4 * M * N, dtype=torch.float32, device="cuda")
+    used = sb.debug_gemm(dev(A, dtype), dev(B, dtype), Cd, M, N, K, ta, tb, acc, scratch)
+    torch.cuda.synchronize()
+    if expect_mfma is not None:
+        assert used == int(expect_mfma), f"kernel selection: used_mfma={used}"
+    assert_close(host(Cd), want, 4e-3 if out == "bf16" else 2e-5, f"C M={M} N={N} K={K} ta={ta} tb={tb}")
+
+
+LAYOUTS = [(False, True), (False, False), (True, False)]      # NT, NN, TN
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_mfma_one_tile(ta, tb):
+    run(256, 256, 256, ta, tb, expect_mfma=True)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_mfma_several_tiles_all_outputs(ta, tb):
+    run(512, 768, 320 if ta else 384, ta, tb, out="f32", expect_mfma=True)
+    run(512, 768, 384, ta, tb, out="bf16", expect_mfma=True, seed=1)
+    run(512, 768, 384, ta, tb, out="f32", acc=True, expect_mfma=True, seed=2)
+
+
+@pytest.mark.parametrize("M", [1, 37, 255, 257, 300, 700])
+def test_mfma_ragged_rows(M):
+    run(M, 512, 128, False, True, expect_mfma=True)
+    run(M, 256, 192, False, False, out="bf16", expect_mfma=True)
+
+
+@pytest.mark.parametrize("K", [1, 63, 65, 100, 333, 1000])
+def test_mfma_ragged_reduction_in_dw_form(K):
+    run(256, 512, K, True, False, acc=True, expect_mfma=True)
+
+
+def test_mfma_split_k_paths():
+    run(256, 256, 8192, False, True, expect_mfma=True)               # 1 tile, long K -> split
+    run(300, 512, 4096, False, False, out="bf16", expect_mfma=True)
+    run(512, 256, 4096, False, False, acc=True, expect_mfma=True)
+    run(256, 256, 4000, True, False, acc=True, expect_mfma=True)     # ragged split
+
+
+def test_mfma_bigger_square():
+    run(1024, 1024, 1024, False, True, out="bf16", expect_mfma=True)
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_generic_odd_shapes(ta, tb):
+    run(70, 45, 33, ta, tb, expect_mfma=False)
+    run(70, 45, 33, ta, tb, out="bf16", expect_mfma=False)
+    run(130, 172, 64, ta, tb, acc=True, expect_mfma=False, dtype="f32")
+
+
+def test_linear_example_closed_form():
+    # Y = X W1, Z = Y W2, L = sum(Z): dZ = 1, dY = 1 W2^T, dW1 = X^T dY, dW2 = Y^T 1 (App. A.1),
+    # accumulated over D chunks of rows with the dW-form GEMM (C += A^T B).
+    rng = np.random.default_rng(0)
+    D, rows, m, n, k = 3, 200, 256, 512, 256
+    X = synth.to_storage(rng.normal(size=(D * rows, m)), "bf16")
+    W1 = synth.to_storage(rng.normal(size=(m, n)) * 0.05, "bf16")
+    W2 = synth.to_storage(rng.normal(size=(n, k)) * 0.05, "bf16")
+    ones = torch.ones((rows, k), dtype=torch.bfloat16, device="cuda")
+    dW1 = torch.zeros((m, n), dtype=torch.float32, device="cuda")
+    dW2 = torch.zeros((n, k), dtype=torch.float32, device="cuda")
+    W1d, W2d = dev(W1, "bf16"), dev(W2, "bf16")
+    Ys = []
+    for i in range(D):
+        Xi = dev(X[i * rows:(i + 1) * rows], "bf16")
+        Yi = torch.empty((rows, n), dtype=torch.bfloat16, device="cuda")
+        sb.debug_gemm(Xi, W1d, Yi, rows, n, m, False, False)               # Y_i = X_i W1
+        dYi = torch.empty((rows, n), dtype=torch.bfloat16, device="cuda")
+        sb.debug_gemm(ones, W2d, dYi, rows, n, k, False, True)             # dY_i = 1 W2^T
+        sb.debug_gemm(Xi, dYi, dW1, m, n, rows, True, False, acc=True)     # dW1 += X_i^T dY_i
+        sb.debug_gemm(Yi, ones, dW2, n, k, rows, True, False, acc=True)    # dW2 += Y_i^T 1
+        Ys.append(host(Yi))
+    torch.cuda.synchronize()
+    X64, W164, W264 = X.astype(np.float64), W1.astype(np.float64), W2.astype(np.float64)
+    want_dW1 = np.outer(X64.sum(axis=0), W264.sum(axis=1))                 # X^T (1 W2^T) in closed form
+    want_dW2 = np.repeat((X64 @ W164).sum(axis=0)[:, None], k, axis=1)     # Y^T 1
+    assert_close(host(dW1), want_dW1, 5e-3, "dW1")
+    assert_close(host(dW2), want_dW2, 5e-3, "dW2")
