@@ -1,7 +1,511 @@
-// placeholder until the MFMA attention lands
+// bf16 MFMA chunk attention for gfx950 (head_dim 128): forward, dQ and dK/dV.
+//
+// Query row t of the chunk sits at global position q_start + t and sees keys
+// 0 .. q_start + t of the cached prefix (paper Sec. 3.2.2, partitioned attention;
+// Property 3.1).  Key tiles that lie entirely above the diagonal are skipped,
+// tiles on the diagonal are masked by an integer comparison of positions, rows
+// past q_start + q_len of K/V are never read.
+//
+// All three kernels use the "transposed score" formulation on the 32x32x16
+// MFMA: S^T[key, query] = K Q^T.  The accumulator layout then gives every lane
+// ONE query (column l%32) and 16 keys per 32-key block, so row max / row sum
+// are in-register plus one cross-half exchange, and exp(S^T) is already in the
+// register layout of the B operand of the next product (P^T as [key, query]
+// with keys as the reduction index) - probabilities never touch LDS.  The
+// reduction-index permutation this implies (slot j of half h <-> key
+// 16*ks + 8*(j>>2) + 4*h + (j&3)) is matched on the A side by the transposing
+// LDS load (ds_read_b64_tr_b16) that fetches V^T / K^T / Q^T / dO^T fragments
+// from tiles kept in their natural [row][head_dim] layout.
+//
+//  forward : workgroup = 128 queries of one query head, 4 waves x 32 queries;
+//            K and V tiles of 64 keys stream HBM -> LDS (direct-to-LDS, double
+//            buffered); online softmax in the exp2 domain.
+//  dQ      : same decomposition; recomputes P from the saved log-sum-exp;
+//            dQ^T += K^T dS^T.
+//  dK/dV   : workgroup = 128 keys of one KV head, 4 waves x 32 keys with K and V
+//            fragments resident in registers; loops over the query tiles at or
+//            below the diagonal and over the query heads of the group, Q and dO
+//            tiles of 64 queries stream through LDS; dV^T += dO^T P,
+//            dK^T += Q^T dS; results are added to the fp32 prefix accumulators
+//            (every element has one owner: no atomics, reproducible).
 #include "launch.h"
+
+#include <algorithm>
+
 namespace sbp {
-bool attn_mfma_eligible(int, int, int, int) { return false; }
-hipError_t attn_forward_mfma(const AttnArgs&, hipStream_t) { return hipErrorNotSupported; }
-hipError_t attn_backward_mfma(const AttnArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define LDS_AS(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int DH = 128;                  // head_dim of the MFMA path
+constexpr int ROW_BYTES = DH * 2;        // 256 B per tile row
+constexpr int AT_THREADS = 256;          // 4 waves
+constexpr int TQ = ATTN_TILE_Q;          // 128 queries per workgroup (fwd, dQ)
+constexpr int TK = ATTN_TILE_K;          // 64 keys per step (fwd, dQ)
+constexpr int KV_TILE = 128;             // keys per workgroup (dK/dV)
+constexpr int QT = 64;                   // queries per step (dK/dV)
+constexpr int TILE64_BYTES = 64 * ROW_BYTES;   // 16 KiB
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// LDS tile [rows][128 bf16], 16 chunks of 16 B per row, chunk ^= f(row) with
+// f(row) = ((row&3)<<2)|((row>>2)&3): conflict-free both for 128-bit row-fragment
+// reads (16 consecutive rows, same chunk) and for the transposing 64-bit reads
+// (4 consecutive rows x 32 B).
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+__device__ __forceinline__ int tile_off(int row, int chunk) { return row * ROW_BYTES + ((chunk ^ swz(row)) << 4); }
+
+// Direct-to-LDS load of a 64-row tile: rows row0..row0+63 of a [*, stride] bf16 matrix (row index clamped to
+// row_max so that nothing past the valid rows is ever read), 128 columns starting at g.
+__device__ __forceinline__ void dma_tile64(const bf16_t* __restrict__ g, int64_t stride, int row0, int row_max, char* lds) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int id = i * AT_THREADS + tid;
+    const int row = id >> 4, pc = id & 15;
+    const int chunk = pc ^ swz(row);
+    const bf16_t* src = g + (int64_t)min(row0 + row, row_max) * stride + chunk * 8;
+    char* dst = lds + (size_t)(i * AT_THREADS + (tid & ~63)) * 16;
+    __builtin_amdgcn_global_load_lds(src, LDS_AS(dst), 16, 0, 0);
+  }
 }
+
+// A operand, rows = tile rows, reduction = head_dim: lane l -> row row_base + l%32, columns 16*ks + 8*(l/32) .. +7
+__device__ __forceinline__ bf16x8 frag_rows(const char* lds, int row_base, int ks) {
+  const int l = threadIdx.x & 63;
+  return *(const bf16x8*)(lds + tile_off(row_base + (l & 31), ks * 2 + (l >> 5)));
+}
+
+// A operand, rows = head_dim columns of the tile (d_base + l%32), reduction = tile rows in the permuted order
+// slot (h, j) <-> tile row row_base + 8*(j>>2) + 4*h + (j&3)   (h = l/32), matching the accumulator layout.
+__device__ __forceinline__ bf16x8 frag_cols_tr(const char* lds, int row_base, int d_base) {
+  const int l = threadIdx.x & 63;
+  const int p = l & 15, g = l >> 4;
+  const int col = d_base + 16 * (g & 1) + 4 * (p & 3);
+  const int row = row_base + 4 * (g >> 1) + (p >> 2);
+  const int c = col >> 3, sub = (col & 7) << 1;
+  short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) short4v*)(lds + tile_off(row, c) + sub));
+  short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) short4v*)(lds + tile_off(row + 8, c) + sub));
+  short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int ks) {
+  bf16x8 o;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = (bf16_t)v[8 * ks + j];
+  return o;
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
+}
+
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+#define WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0f70)
+
+// row index (within a 32-row accumulator block) held in register r of a lane in half h
+__device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
+
+// ------------------------------------------------------------------ forward --
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                                 const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
+                                                                 float* __restrict__ lse, int Hq, int Hkv, int q_start,
+                                                                 int c, float scale) {
+  __shared__ __attribute__((aligned(1024))) char sK0[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sV0[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sK1[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sV1[TILE64_BYTES];
+
+  const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int qw0 = q0 + wave * 32;
+  const int my_q = qw0 + (lane & 31);
+  const bool q_valid = my_q < c;
+  const int q_row = min(my_q, c - 1);
+  const int qpos = q_start + q_row;
+  const int64_t kv_stride = (int64_t)Hkv * DH;
+  const bf16_t* kbase = k + (int64_t)kvh * DH;
+  const bf16_t* vbase = v + (int64_t)kvh * DH;
+  const int n_total = q_start + c;                                    // rows of K/V that exist for this chunk
+  const int n_keys = q_start + min(q0 + TQ, c);                       // keys visible to the workgroup
+  const int n_tiles = (n_keys + TK - 1) / TK;
+  const int wave_last_key = q_start + min(qw0 + 32, c) - 1;           // last key any query of this wave sees
+  const int wave_first_qpos = q_start + qw0;
+
+  bf16x8 bq[8];
+  {
+    const bf16_t* qp = q + ((int64_t)q_row * Hq + h) * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) bq[ks] = *(const bf16x8*)(qp + ks * 16);
+  }
+  f32x16 acc_o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc_o[i] = zero16();
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sl = scale * LOG2E;
+
+  auto step = [&](int kt, const char* sK, const char* sV) {
+    const int k0 = kt * TK;
+    if (qw0 >= c || k0 > wave_last_key) return;           // nothing visible to this wave in the tile
+    f32x16 s[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      s[b] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) s[b] = MFMA(frag_rows(sK, b * 32, ks), bq[ks], s[b]);
+    }
+    const bool diag = k0 + TK - 1 > wave_first_qpos;      // some (query, key) pair of the wave is masked
+    float mx = -INFINITY;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float x = s[b][r] * sl;
+        if (diag && (k0 + b * 32 + acc_row(r, half) > qpos)) x = -INFINITY;
+        s[b][r] = x;
+        mx = fmaxf(mx, x);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = exp2f(m_run - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(s[b][r] - m_new);
+        s[b][r] = p;
+        psum += p;
+      }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 pb = pack8(s[b], ks);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc_o[i] = MFMA(frag_cols_tr(sV, b * 32 + ks * 16, i * 32), pb, acc_o[i]);
+      }
+  };
+
+  auto issue = [&](int kt, char* sK, char* sV) {
+    dma_tile64(kbase, kv_stride, kt * TK, n_total - 1, sK);
+    dma_tile64(vbase, kv_stride, kt * TK, n_total - 1, sV);
+  };
+
+  issue(0, sK0, sV0);
+  for (int kt = 0; kt < n_tiles; kt += 2) {
+    WAIT_VM0();
+    __syncthreads();
+    if (kt + 1 < n_tiles) issue(kt + 1, sK1, sV1);
+    step(kt, sK0, sV0);
+    if (kt + 1 < n_tiles) {
+      WAIT_VM0();
+      __syncthreads();
+      if (kt + 2 < n_tiles) issue(kt + 2, sK0, sV0);
+      step(kt + 1, sK1, sV1);
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (q_valid) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* op = o + ((int64_t)my_q * Hq + h) * DH;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(acc_o[i][4 * a + e] * inv);
+        *(bf16x4*)(op + i * 32 + 8 * a + 4 * half) = w;
+      }
+    if (half == 0) lse[(int64_t)h * c + my_q] = (m_run + log2f(l_tot)) * LN2;
+  }
+}
+
+// ----------------------------------------------------------------------- dQ --
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_bwd_dq_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                                    const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
+                                                                    const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                    bf16_t* __restrict__ dq, int Hq, int Hkv, int q_start, int c,
+                                                                    float scale) {
+  __shared__ __attribute__((aligned(1024))) char sK0[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sV0[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sK1[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sV1[TILE64_BYTES];
+
+  const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int qw0 = q0 + wave * 32;
+  const int my_q = qw0 + (lane & 31);
+  const bool q_valid = my_q < c;
+  const int q_row = min(my_q, c - 1);
+  const int qpos = q_start + q_row;
+  const int64_t kv_stride = (int64_t)Hkv * DH;
+  const bf16_t* kbase = k + (int64_t)kvh * DH;
+  const bf16_t* vbase = v + (int64_t)kvh * DH;
+  const int n_total = q_start + c;
+  const int n_keys = q_start + min(q0 + TQ, c);
+  const int n_tiles = (n_keys + TK - 1) / TK;
+  const int wave_last_key = q_start + min(qw0 + 32, c) - 1;
+  const int wave_first_qpos = q_start + qw0;
+
+  bf16x8 bq[8], bdo[8];
+  {
+    const int64_t off = ((int64_t)q_row * Hq + h) * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) { bq[ks] = *(const bf16x8*)(q + off + ks * 16); bdo[ks] = *(const bf16x8*)(d_o + off + ks * 16); }
+  }
+  const float lse2 = lse[(int64_t)h * c + q_row] * LOG2E;
+  const float dlt = delta[(int64_t)h * c + q_row];
+  const float sl = scale * LOG2E;
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] = zero16();
+
+  auto step = [&](int kt, const char* sK, const char* sV) {
+    const int k0 = kt * TK;
+    if (qw0 >= c || k0 > wave_last_key) return;
+    const bool diag = k0 + TK - 1 > wave_first_qpos;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) s = MFMA(frag_rows(sK, b * 32, ks), bq[ks], s);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) dp = MFMA(frag_rows(sV, b * 32, ks), bdo[ks], dp);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = exp2f(s[r] * sl - lse2);
+        if (diag && (k0 + b * 32 + acc_row(r, half) > qpos)) p = 0.f;
+        s[r] = p * (dp[r] - dlt);                              // dS^T (the factor `scale` is applied at the end)
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 db = pack8(s, ks);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sK, b * 32 + ks * 16, i * 32), db, acc[i]);
+      }
+    }
+  };
+  auto issue = [&](int kt, char* sK, char* sV) {
+    dma_tile64(kbase, kv_stride, kt * TK, n_total - 1, sK);
+    dma_tile64(vbase, kv_stride, kt * TK, n_total - 1, sV);
+  };
+
+  issue(0, sK0, sV0);
+  for (int kt = 0; kt < n_tiles; kt += 2) {
+    WAIT_VM0();
+    __syncthreads();
+    if (kt + 1 < n_tiles) issue(kt + 1, sK1, sV1);
+    step(kt, sK0, sV0);
+    if (kt + 1 < n_tiles) {
+      WAIT_VM0();
+      __syncthreads();
+      if (kt + 2 < n_tiles) issue(kt + 2, sK0, sV0);
+      step(kt + 1, sK1, sV1);
+    }
+  }
+
+  if (q_valid) {
+    bf16_t* op = dq + ((int64_t)my_q * Hq + h) * DH;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(acc[i][4 * a + e] * scale);
+        *(bf16x4*)(op + i * 32 + 8 * a + 4 * half) = w;
+      }
+  }
+}
+
+// -------------------------------------------------------------------- dK/dV --
+__global__ __launch_bounds__(AT_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                                     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
+                                                                     const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                     float* __restrict__ dk, float* __restrict__ dv, int Hq, int Hkv,
+                                                                     int q_start, int c, float scale) {
+  __shared__ __attribute__((aligned(1024))) char sQ0[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sD0[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sQ1[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sD1[TILE64_BYTES];
+  __shared__ __attribute__((aligned(16))) float sL[2][QT];     // log-sum-exp of the tile's queries
+  __shared__ __attribute__((aligned(16))) float sDl[2][QT];    // delta of the tile's queries
+
+  const int G = Hq / Hkv;
+  const int key0 = blockIdx.x * KV_TILE, kvh = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int n_total = q_start + c;
+  const int kw0 = key0 + wave * 32;
+  const int my_key = kw0 + (lane & 31);
+  const int key_row = min(my_key, n_total - 1);
+  const int64_t kv_stride = (int64_t)Hkv * DH;
+  const int64_t q_stride = (int64_t)Hq * DH;
+
+  bf16x8 bk[8], bv[8];
+  {
+    const int64_t off = (int64_t)key_row * kv_stride + (int64_t)kvh * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) { bk[ks] = *(const bf16x8*)(k + off + ks * 16); bv[ks] = *(const bf16x8*)(v + off + ks * 16); }
+  }
+  f32x16 acc_k[4], acc_v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { acc_k[i] = zero16(); acc_v[i] = zero16(); }
+  const float sl = scale * LOG2E;
+
+  // query tiles that can see at least one key of this workgroup: query position >= key0
+  const int qt_first = max(0, key0 - q_start) / QT;
+  const int n_qt = (c + QT - 1) / QT;
+  const int n_iter = (n_qt - qt_first) * G;
+
+  auto issue = [&](int it, char* sQ, char* sD, int buf) {
+    const int qt = qt_first + it / G, hh = kvh * G + it % G;
+    dma_tile64(q + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQ);
+    dma_tile64(d_o + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sD);
+    if (wave < 2) {   // 64 log-sum-exp values (wave 0) and 64 deltas (wave 1), 4 B per lane, also direct to LDS
+      const int row = min(qt * QT + lane, c - 1);
+      const float* src = (wave == 0 ? lse : delta) + (int64_t)hh * c + row;
+      __builtin_amdgcn_global_load_lds(src, LDS_AS(wave == 0 ? &sL[buf][0] : &sDl[buf][0]), 4, 0, 0);
+    }
+  };
+  auto step = [&](int it, const char* sQ, const char* sD, int buf) {
+    const int qt = qt_first + it / G;
+    const int qbase = qt * QT;
+    if (kw0 >= n_total) return;                                   // wave has no valid key
+    if (q_start + min(qbase + QT, c) - 1 < kw0) return;           // every query of the tile precedes the wave's keys
+    const bool diag = (q_start + qbase < kw0 + 31) || (qbase + QT > c);   // some pair masked, or ragged query tile
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) s = MFMA(frag_rows(sQ, b * 32, ks), bk[ks], s);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) dp = MFMA(frag_rows(sD, b * 32, ks), bv[ks], dp);
+      // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const float4 l4 = *(const float4*)&sL[buf][b * 32 + 8 * a + 4 * half];
+        const float4 d4 = *(const float4*)&sDl[buf][b * 32 + 8 * a + 4 * half];
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * a + e;
+          float p = exp2f(s[r] * sl - lv[e] * LOG2E);
+          if (diag) {
+            const int qi = qbase + b * 32 + 8 * a + 4 * half + e;
+            if (qi >= c || my_key > q_start + qi) p = 0.f;
+          }
+          s[r] = p;
+          dp[r] = p * (dp[r] - dl[e]);
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 pb = pack8(s, ks), db = pack8(dp, ks);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc_v[i] = MFMA(frag_cols_tr(sD, b * 32 + ks * 16, i * 32), pb, acc_v[i]);
+          acc_k[i] = MFMA(frag_cols_tr(sQ, b * 32 + ks * 16, i * 32), db, acc_k[i]);
+        }
+      }
+    }
+  };
+
+  if (n_iter > 0) issue(0, sQ0, sD0, 0);
+  for (int it = 0; it < n_iter; it += 2) {
+    WAIT_VM0();
+    __syncthreads();
+    if (it + 1 < n_iter) issue(it + 1, sQ1, sD1, 1);
+    step(it, sQ0, sD0, 0);
+    if (it + 1 < n_iter) {
+      WAIT_VM0();
+      __syncthreads();
+      if (it + 2 < n_iter) issue(it + 2, sQ0, sD0, 0);
+      step(it + 1, sQ1, sD1, 1);
+    }
+  }
+
+  if (my_key < n_total) {
+    float* kp = dk + (int64_t)my_key * kv_stride + (int64_t)kvh * DH;
+    float* vp = dv + (int64_t)my_key * kv_stride + (int64_t)kvh * DH;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int d0 = i * 32 + 8 * a + 4 * half;
+        float4 t = *(float4*)(kp + d0);
+        t.x += acc_k[i][4 * a + 0] * scale; t.y += acc_k[i][4 * a + 1] * scale;
+        t.z += acc_k[i][4 * a + 2] * scale; t.w += acc_k[i][4 * a + 3] * scale;
+        *(float4*)(kp + d0) = t;
+        float4 u = *(float4*)(vp + d0);
+        u.x += acc_v[i][4 * a + 0]; u.y += acc_v[i][4 * a + 1]; u.z += acc_v[i][4 * a + 2]; u.w += acc_v[i][4 * a + 3];
+        *(float4*)(vp + d0) = u;
+      }
+  }
+}
+
+// delta[h, t] = sum_j d_o[t,h,j] * o[t,h,j]  (one wave per (t, h))
+__global__ __launch_bounds__(256) void attn_delta_mfma_k(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
+                                                         float* __restrict__ delta, int Hq, int c) {
+  const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);      // t * Hq + h
+  if (pair >= (int64_t)c * Hq) return;
+  const int lane = threadIdx.x & 63;
+  const int t = (int)(pair / Hq), h = (int)(pair % Hq);
+  const int64_t base = pair * DH + lane * 2;
+  float s = (float)o[base] * (float)d_o[base] + (float)o[base + 1] * (float)d_o[base + 1];
+  s = wave_sum(s);
+  if (lane == 0) delta[(int64_t)h * c + t] = s;
+}
+
+bool attn_mfma_eligible(int dt, int dh, int Hq, int Hkv) { return dt == DT_BF16 && dh == DH && Hq % Hkv == 0; }
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+hipError_t attn_forward_generic(const AttnArgs& a, hipStream_t st);
+hipError_t attn_backward_generic(const AttnArgs& a, hipStream_t st);
+
+hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st) {
+  if (a.q_len == 0) return hipSuccess;
+  if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o)) return attn_forward_generic(a, st);
+  dim3 grid((unsigned)cdiv(a.q_len, TQ), a.Hq);
+  attn_fwd_mfma_k<<<grid, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (bf16_t*)a.o, a.lse,
+                                               a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
+  return hipGetLastError();
+}
+
+hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st) {
+  if (a.q_len == 0) return hipSuccess;
+  if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o) || !aligned16(a.d_o) || !aligned16(a.dq) ||
+      !aligned16(a.dk) || !aligned16(a.dv))
+    return attn_backward_generic(a, st);
+  const int64_t pairs = (int64_t)a.q_len * a.Hq;
+  attn_delta_mfma_k<<<(unsigned)cdiv(pairs, 4), 256, 0, st>>>((const bf16_t*)a.o, (const bf16_t*)a.d_o, a.delta, a.Hq, a.q_len);
+  dim3 gq((unsigned)cdiv(a.q_len, TQ), a.Hq);
+  attn_bwd_dq_mfma_k<<<gq, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
+                                                a.lse, a.delta, (bf16_t*)a.dq, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
+  dim3 gk((unsigned)cdiv(a.q_start + a.q_len, KV_TILE), a.Hkv);
+  attn_bwd_dkv_mfma_k<<<gk, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
+                                                 a.lse, a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
+  return hipGetLastError();
+}
+
+}  // namespace sbp
