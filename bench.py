@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""StreamBP backward benchmark: one 7B-shaped decoder layer + LM head at 32k tokens.
+
+A step = one pass of the whole hot path over one synthetic sequence:
+LM-head + cross-entropy StreamBP (chunk 2048 rows of logits at a time) followed
+by the layer-wise StreamBP of one decoder layer (K/V pre-pass, then per chunk:
+reforward, MLP / attention backward, dW accumulation), with all inputs already
+resident in HBM.  Prints ONE JSON line (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--seq-len T] [--chunk C]
+                    [--no-cpu-baseline] [--no-profile]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16 MFMA); vendor figure ~2.5 PF
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_flops(cfg, T, active_rows):
+    """Work the method must do (Sec. 3.2): 6*P per token for the linear maps (reforward, dX, dW), 14*dh per
+    visible causal (query, key) pair per query head (4 forward + 10 backward), 6*d*V per row of the head."""
+    d, Hq, Hkv, dh, F, V = (cfg[k] for k in ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "mlp_width", "vocab"))
+    p_lin = d * Hq * dh + 2 * d * Hkv * dh + Hq * dh * d + 3 * d * F
+    linear = 6.0 * p_lin * T
+    attn = 14.0 * dh * Hq * (T * (T + 1) / 2.0)
+    head_all = 6.0 * d * V * T
+    head_active = 6.0 * d * V * active_rows
+    return dict(linear=linear, attention=attn, head_all_rows=head_all, head_active_rows=head_active,
+                total=linear + attn + head_all)
+
+
+def cpu_baseline(cfg, seconds_hint=20.0):
+    """The fp64 oracle as it stands, timed on this machine's host cores on a bounded sample of the same
+    workload: one 7B-shaped layer forward+backward at T_s tokens and the LM head on R_s rows."""
+    import numpy as np
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    from oracle import head as o_head
+    from oracle import layer as o_layer
+    from paper_2506_03077_amd import synth
+    T_s, R_s = 2048, 768
+    lc = dict(cfg, dtype="bf16")
+    inp = synth.layer_inputs(lc, seed=0, seq_len=T_s, batch=1)
+    ocfg = dict(n_q_heads=cfg["n_q_heads"], n_kv_heads=cfg["n_kv_heads"], head_dim=cfg["head_dim"])
+    t0 = time.perf_counter()
+    o_layer.layer_forward_backward(inp["x"], inp["w"], ocfg, inp["dy"])
+    t_layer = time.perf_counter() - t0
+    hin = synth.head_inputs(lc, seed=0, seq_len=R_s, batch=1, prompt_frac=0.0)
+    t0 = time.perf_counter()
+    o_head.sft(hin["h"], hin["w"], hin["targets"], 1.0 / R_s)
+    t_head = time.perf_counter() - t0
+    per_token = t_layer / T_s + t_head / R_s
+    return dict(value=1.0 / per_token, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=(f"fp64 numpy oracle, full-sequence backprop: one layer fwd+bwd at T={T_s} ({t_layer:.1f} s) + "
+                        f"LM head on {R_s} rows ({t_head:.1f} s), 7B-shaped widths; per-token times added "
+                        f"(attention cost at T={T_s}, not 32k)"))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--seq-len", type=int, default=None)
+    ap.add_argument("--chunk", type=int, default=None)
+    ap.add_argument("--head-chunk", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2506_03077_amd import binding as sb
+    from paper_2506_03077_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    sb.lib()   # fails loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = dict(synth.CONFIGS["7b"])
+    T = args.seq_len or cfg["seq_len"]
+    c = args.chunk or cfg["chunk"]
+    hc_rows = args.head_chunk or c
+    d, V = cfg["hidden"], cfg["vocab"]
+    bf = torch.bfloat16
+
+    # ---- synthetic inputs, generated on the device (seeded): weights N(0, 0.02), hidden states N(0, 1),
+    # gains 1 + N(0, 0.02), target ids uniform in [0, V) with the first 25% of positions ignored (prompt).
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+
+    def normal(shape, std, mean=0.0):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(bf)
+
+    Hq, Hkv, dh, F = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"]
+    w = dict(wq=normal((Hq * dh, d), 0.02), wk=normal((Hkv * dh, d), 0.02), wv=normal((Hkv * dh, d), 0.02),
+             wo=normal((d, Hq * dh), 0.02), wgate=normal((F, d), 0.02), wup=normal((F, d), 0.02),
+             wdown=normal((d, F), 0.02), g1=normal((d,), 0.02, 1.0), g2=normal((d,), 0.02, 1.0))
+    w_head = normal((V, d), 0.02)
+    x = normal((1, T, d), 1.0)          # layer input (the checkpoint)
+    h = normal((1, T, d), 1.0)          # hidden states entering the head
+    targets = torch.randint(0, V, (1, T), generator=gen, device=dev, dtype=torch.int32)
+    n_prompt = T // 4
+    targets[:, :n_prompt] = -1
+    n_act = T - n_prompt
+
+    lcfg = sb.layer_cfg(sb.SBP_BF16, 1, T, c, d, Hq, Hkv, dh, F)
+    hcfg = sb.head_cfg(sb.SBP_BF16, 1, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act)
+    ws_layer = torch.empty(sb.streambp_layer_workspace_bytes(lcfg), dtype=torch.uint8, device=dev)
+    ws_head = torch.empty(sb.streambp_lmhead_workspace_bytes(hcfg), dtype=torch.uint8, device=dev)
+    dw = sb.new_layer_grads(w)
+    dw_head = torch.zeros((V, d), dtype=torch.float32, device=dev)
+    dh_out = torch.empty_like(h)
+    dx = torch.empty_like(x)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    n_active = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def step():
+        sb.streambp_lmhead_ce_backward(hcfg, w_head, h, targets, dh=dh_out, dw=dw_head, loss=loss, n_active=n_active,
+                                       workspace=ws_head)
+        # the head's dH is the upstream gradient of the layer (the final norm is left out of the timed step)
+        sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / max(args.steps, 1)
+
+    assert int(n_active.item()) == n_act
+    assert bool(torch.isfinite(dx.float()).all()) and bool(torch.isfinite(loss).all())
+
+    fl = algorithmic_flops(cfg, T, n_act)
+    out = {
+        "metric": "backward tokens/s per layer+LM head at 32k seq",
+        "value": T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"7B-shaped decoder layer (d=3584, 28q/4kv x128, F=18944) + LM head (V=152064), "
+                               f"T={T}, chunk={c}, head chunk={hc_rows}, batch 1, SFT loss on last 75% of positions",
+                   "algorithmic_tflop_per_step": fl["total"] / 1e12,
+                   "achieved_tflops": fl["total"] / dt / 1e12,
+                   "frac_of_bf16_mfma_peak": fl["total"] / dt / 1e12 / PEAK_BF16_TFLOPS,
+                   "peak_activation_bytes": {"layer_workspace": ws_layer.numel(), "head_workspace": ws_head.numel(),
+                                             "full_sequence_logits_fp32_would_be": T * V * 4},
+                   "torch_max_memory_allocated": int(torch.cuda.max_memory_allocated())},
+    }
+
+    # ---- roofline of the dominant kernel (weight-gradient GEMM, TN form), durations from HIP events recorded
+    # around every launch on the launch stream during one more pass over the same workload.
+    if not args.no_profile:
+        sb.debug_profile_begin(20000)
+        step()
+        torch.cuda.synchronize()
+        prof = sb.debug_profile_end()
+        per_kind = {k: dict(launches=v["count"], ms=v["ms"], tflops=(v["flops"] / v["ms"] / 1e9 if v["ms"] > 0 else 0.0))
+                    for k, v in prof.items() if v["count"]}
+        dom = max((k for k in prof if prof[k]["count"]), key=lambda k: prof[k]["ms"])
+        pv = prof[dom]
+        achieved = pv["flops"] / pv["ms"] / 1e9
+        out["roofline"] = {"bound": "mfma", "kernel": dom, "launches_per_step": pv["count"],
+                           "avg_launch_ms": pv["ms"] / pv["count"], "avg_launch_tflop": pv["flops"] / pv["count"] / 1e12,
+                           "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
+        out["config"]["per_kernel_family"] = per_kind
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -97,6 +97,10 @@ def lib():
         L.streambp_debug_force_generic.argtypes = [C.c_int, C.c_int]
         L.streambp_debug_gemm.restype = C.c_int
         L.streambp_debug_gemm.argtypes = [C.c_int] * 8 + [vp, vp, vp, C.c_longlong, C.c_longlong, C.c_longlong, vp, sz, vp]
+        L.streambp_debug_profile_begin.restype = C.c_int
+        L.streambp_debug_profile_begin.argtypes = [C.c_int]
+        L.streambp_debug_profile_end.restype = C.c_int
+        L.streambp_debug_profile_end.argtypes = [C.POINTER(C.c_longlong), C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -318,3 +322,23 @@ def debug_gemm(A, B, C_out, M, N, K, ta, tb, acc=False, scratch=None, stream=Non
     if rc < 0:
         raise StreamBPError(rc, "debug_gemm launch failed")
     return rc
+
+
+PROFILE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "gemm_generic", "attn_fwd", "attn_bwd")
+
+
+def debug_profile_begin(max_records=100000):
+    """Start per-launch HIP-event timing of the GEMM / attention dispatchers (events are created here)."""
+    rc = lib().streambp_debug_profile_begin(max_records)
+    if rc != 0:
+        raise StreamBPError(rc, "profile_begin failed")
+
+
+def debug_profile_end():
+    """Stop timing; returns {kind: dict(count, ms, flops)} summed over the launches since begin."""
+    n = len(PROFILE_KINDS)
+    cnt, ms, work = (C.c_longlong * n)(), (C.c_double * n)(), (C.c_double * n)()
+    rc = lib().streambp_debug_profile_end(cnt, ms, work)
+    if rc != 0:
+        raise StreamBPError(rc, "profile_end failed")
+    return {k: dict(count=int(cnt[i]), ms=float(ms[i]), flops=float(work[i])) for i, k in enumerate(PROFILE_KINDS)}

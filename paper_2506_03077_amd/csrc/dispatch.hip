@@ -2,6 +2,8 @@
 // shape-agnostic kernels otherwise.
 #include "launch.h"
 
+#include <vector>
+
 namespace sbp {
 
 hipError_t gemm_generic(const GemmArgs& g, hipStream_t st);
@@ -22,13 +24,46 @@ void attn_set_force_generic(bool on) { g_force_generic_attn = on; }
 bool gemm_uses_mfma(const GemmArgs& g) { return !g_force_generic_gemm && gemm_mfma_eligible(g); }
 bool attn_uses_mfma(int dt, int dh, int Hq, int Hkv) { return !g_force_generic_attn && attn_mfma_eligible(dt, dh, Hq, Hkv); }
 
+// ---- optional per-launch timing (off by default; events are created when profiling is switched on,
+// never inside an entry point) -------------------------------------------------------------------
+namespace prof {
+enum Kind { GEMM_NT = 0, GEMM_NN, GEMM_TN, GEMM_GENERIC, ATTN_FWD, ATTN_BWD, N_KIND };
+struct Rec { int kind; double work; hipEvent_t e0, e1; };
+static bool g_on = false;
+static std::vector<hipEvent_t> g_pool;
+static std::vector<Rec> g_recs;
+static size_t g_next = 0;
+
+struct Scope {
+  hipStream_t st; bool active = false; Rec rec{};
+  Scope(int kind, double work, hipStream_t s) : st(s) {
+    if (!g_on || g_next + 2 > g_pool.size()) return;
+    rec.kind = kind; rec.work = work; rec.e0 = g_pool[g_next++]; rec.e1 = g_pool[g_next++];
+    active = hipEventRecord(rec.e0, st) == hipSuccess;
+  }
+  ~Scope() {
+    if (active && hipEventRecord(rec.e1, st) == hipSuccess) g_recs.push_back(rec);
+  }
+};
+}  // namespace prof
+
+static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs of the chunk, all query heads
+  const double c = a.q_len, s = a.q_start;
+  return (double)a.Hq * (c * s + c * (c + 1.0) / 2.0);
+}
+
 hipError_t gemm(const GemmArgs& g, hipStream_t st) {
-  return gemm_uses_mfma(g) ? gemm_mfma(g, st) : gemm_generic(g, st);
+  const bool mfma = gemm_uses_mfma(g);
+  const int kind = !mfma ? prof::GEMM_GENERIC : (g.ta ? prof::GEMM_TN : (g.tb ? prof::GEMM_NT : prof::GEMM_NN));
+  prof::Scope sc(kind, 2.0 * g.M * g.N * g.K, st);
+  return mfma ? gemm_mfma(g, st) : gemm_generic(g, st);
 }
 hipError_t attn_forward(const AttnArgs& a, hipStream_t st) {
+  prof::Scope sc(prof::ATTN_FWD, 4.0 * a.dh * causal_pairs(a), st);
   return attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) ? attn_forward_mfma(a, st) : attn_forward_generic(a, st);
 }
 hipError_t attn_backward(const AttnArgs& a, hipStream_t st) {
+  prof::Scope sc(prof::ATTN_BWD, 10.0 * a.dh * causal_pairs(a), st);
   return attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) ? attn_backward_mfma(a, st) : attn_backward_generic(a, st);
 }
 
@@ -48,4 +83,37 @@ extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_d
   g.scratch_bytes = scratch_bytes;
   hipError_t e = sbp::gemm(g, (hipStream_t)stream);
   return e == hipSuccess ? (sbp::gemm_uses_mfma(g) ? 1 : 0) : -5;
+}
+
+// Per-launch timing of the GEMM / attention dispatchers with HIP events on the launch stream.
+// begin: creates 2*max_records events and switches recording on.  end: synchronises the events, returns per
+// kind (NT, NN, TN, generic GEMM, attention forward, attention backward) the launch count, the summed
+// duration in ms and the summed algorithmic flops, then destroys the events.
+extern "C" int streambp_debug_profile_begin(int max_records) {
+  using namespace sbp::prof;
+  if (g_on) return -1;
+  g_pool.resize((size_t)max_records * 2);
+  for (auto& e : g_pool)
+    if (hipEventCreate(&e) != hipSuccess) return -5;
+  g_recs.clear();
+  g_recs.reserve(max_records);
+  g_next = 0;
+  g_on = true;
+  return 0;
+}
+extern "C" int streambp_debug_profile_end(long long* count, double* ms, double* work) {
+  using namespace sbp::prof;
+  if (!g_on) return -1;
+  g_on = false;
+  for (int k = 0; k < N_KIND; ++k) { count[k] = 0; ms[k] = 0.0; work[k] = 0.0; }
+  int rc = 0;
+  for (const Rec& r : g_recs) {
+    float t = 0.f;
+    if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess) { rc = -5; continue; }
+    count[r.kind] += 1; ms[r.kind] += t; work[r.kind] += r.work;
+  }
+  for (auto& e : g_pool) hipEventDestroy(e);
+  g_pool.clear();
+  g_recs.clear();
+  return rc;
 }
