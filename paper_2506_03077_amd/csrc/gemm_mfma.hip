@@ -36,16 +36,22 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define LDS_AS(p) ((__attribute__((address_space(3))) void*)(p))
 
+
 constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int NSTAGE = 2;                              // LDS ring of operand tiles; NSTAGE-1 tiles are in flight
 constexpr int NWAVE_M = 2, NWAVE_N = 4;
 constexpr int NTHREADS = NWAVE_M * NWAVE_N * 64;      // 512
 constexpr int WTM = BM / NWAVE_M, WTN = BN / NWAVE_N;  // 128 x 64 per wave
 constexpr int FM = WTM / 32, FN = WTN / 32;            // 4 x 2 MFMA tiles
 constexpr int TILE_BYTES = BM * BK * 2;                // 32 KiB per operand tile
 constexpr int LOADS_PER_THREAD = TILE_BYTES / 16 / NTHREADS;   // 4 x 16 B per operand
+constexpr int LOADS_PER_TILE = 2 * LOADS_PER_THREAD;           // wave-level VMEM instructions per k-tile
 
-// ---- K-contiguous operand: LDS [rows][BK], 128 B per row, 8 chunks of 16 B, chunk ^= (row>>1)&7
-__device__ __forceinline__ int kmaj_off(int row, int chunk) { return row * (BK * 2) + ((chunk ^ ((row >> 1) & 7)) << 4); }
+// ---- K-contiguous operand: LDS [rows][BK], 128 B per row = 8 chunks of 16 B, chunk ^= (row>>1)&7:
+//      16 consecutive rows at one logical chunk cover all 64 banks exactly once.
+constexpr int CPR = BK / 8;                            // 16-byte chunks per row
+__device__ __forceinline__ int kmaj_swz(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ int kmaj_off(int row, int chunk) { return row * (BK * 2) + ((chunk ^ kmaj_swz(row)) << 4); }
 
 // ---- reduction-major operand: LDS [BK][rows], 512 B per k-row, 64-byte groups ^= krow&7
 __device__ __forceinline__ int mnmaj_off(int krow, int col /*element*/) {
@@ -54,29 +60,38 @@ __device__ __forceinline__ int mnmaj_off(int krow, int col /*element*/) {
   return krow * (BM * 2) + (p16 << 4) + ((col & 7) << 1);
 }
 
+// 128-bit direct-to-LDS load: every lane supplies its own global address, the wave's 64 x 16 B land
+// contiguously at LDS address lds_wave_base.  Written as inline assembly so that the compiler does not
+// fold the explicit, counted vmcnt waits of the multi-stage pipeline into vmcnt(0).
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_wave_base) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
 // Issue this thread's share of one operand tile (direct-to-LDS, 16 B per lane).
-//   KMAJ : tile rows r0..r0+255 (clamped to r_max), k columns k0..k0+63
-//   MNMAJ: tile k-rows k0..k0+63 (clamped to k_max), columns c0..c0+255
+//   KMAJ : tile rows r0..r0+255 (clamped to r_max), k columns k0..k0+31
+//   MNMAJ: tile k-rows k0..k0+31 (clamped to k_max), columns r0..r0+255
 template <bool MNMAJ>
 __device__ __forceinline__ void load_tile(const bf16_t* __restrict__ g, int64_t ld, int r0, int r_max, int k0, int k_max,
-                                          char* lds_tile) {
+                                          const char* lds_tile) {
   const int tid = threadIdx.x;
+  const uint32_t wave_base = __builtin_amdgcn_readfirstlane(lds_addr(lds_tile) + (uint32_t)(tid & ~63) * 16u);
 #pragma unroll
   for (int i = 0; i < LOADS_PER_THREAD; ++i) {
     const int id = i * NTHREADS + tid;            // 16-byte slot in the tile, lane-linear within a wave
     const bf16_t* src;
     if (!MNMAJ) {
-      const int row = id >> 3, pc = id & 7;
-      const int chunk = pc ^ ((row >> 1) & 7);
+      const int row = id / CPR, pc = id % CPR;
+      const int chunk = pc ^ kmaj_swz(row);
       src = g + (int64_t)min(r0 + row, r_max) * ld + k0 + chunk * 8;
     } else {
       const int krow = id >> 5, p16 = id & 31;
       const int c16 = ((((p16 >> 2) ^ (krow & 7)) << 2) | (p16 & 3));
       src = g + (int64_t)min(k0 + krow, k_max) * ld + r0 + c16 * 8;
     }
-    // LDS destination of the wave = slot of lane 0; lanes land at +16 B each.
-    char* dst = lds_tile + (size_t)(i * NTHREADS + (tid & ~63)) * 16;
-    __builtin_amdgcn_global_load_lds(src, LDS_AS(dst), 16, 0, 0);
+    dma16(src, wave_base + (uint32_t)(i * NTHREADS * 16));
   }
 }
 
@@ -103,25 +118,37 @@ __device__ __forceinline__ bf16x8 load_frag(const char* lds_tile, int row_base, 
 template <bool TA, bool TB>
 __device__ __forceinline__ void compute_tile(const char* sA, const char* sB, int wm0, int wn0, f32x16 (&acc)[FM][FN],
                                              int k_valid /* reduction rows valid in this tile (TN tail) */) {
+  // Fragments are double-buffered in registers: the LDS reads of k16 step kk+1 are in flight while the
+  // MFMAs of step kk issue.
+  bf16x8 a[2][FM], b[2][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) a[0][i] = load_frag<TA>(sA, wm0 + i * 32, 0);
+#pragma unroll
+  for (int j = 0; j < FN; ++j) b[0][j] = load_frag<TB>(sB, wn0 + j * 32, 0);
 #pragma unroll
   for (int kk = 0; kk < BK / 16; ++kk) {
-    bf16x8 a[FM], b[FN];
+    const int cur = kk & 1, nxt = cur ^ 1;
+    if (kk + 1 < BK / 16) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i) a[i] = load_frag<TA>(sA, wm0 + i * 32, kk);
+      for (int i = 0; i < FM; ++i) a[nxt][i] = load_frag<TA>(sA, wm0 + i * 32, kk + 1);
 #pragma unroll
-    for (int j = 0; j < FN; ++j) b[j] = load_frag<TB>(sB, wn0 + j * 32, kk);
+      for (int j = 0; j < FN; ++j) b[nxt][j] = load_frag<TB>(sB, wn0 + j * 32, kk + 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // keep the prefetch above the MFMAs (the scheduler would sink it to its use)
     if (TA && k_valid < BK) {   // zero reduction rows past the end (A only: B rows are finite duplicates)
       const int kbase = kk * 16 + 8 * ((threadIdx.x & 63) >> 5);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (kbase + e >= k_valid) a[i][e] = (bf16_t)0.0f;
+          if (kbase + e >= k_valid) a[cur][i][e] = (bf16_t)0.0f;
     }
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-      for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < FN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -143,15 +170,15 @@ __device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, i
   tn = r / gsz;
 }
 
+// vmcnt(n) with expcnt / lgkmcnt left unconstrained
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
+
 // MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store to scratch slice z)
 template <bool TA, bool TB, int MODE>
 __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                         void* __restrict__ Cv, int M, int N, int K, int64_t lda,
                                                         int64_t ldb, int64_t ldc, int k_per_split) {
-  __shared__ __attribute__((aligned(1024))) char sA0[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sB0[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sA1[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sB1[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
 
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   int tm, tn;
@@ -173,26 +200,29 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // A tile: !TA -> rows are m (clamp to M-1), TA -> rows are k (clamp to K-1), columns m (M % BM == 0 required)
-  auto issue = [&](int kt, char* sA, char* sB) {
+  auto issue = [&](int kt) {
     const int k0 = k_begin + kt * BK;
-    load_tile<TA>(A, lda, m0, M - 1, k0, K - 1, sA);
-    load_tile<!TB>(B, ldb, n0, N - 1, k0, K - 1, sB);   // TB (B stored [N,K]) is the K-contiguous case
+    const int st = kt % NSTAGE;
+    load_tile<TA>(A, lda, m0, M - 1, k0, K - 1, smem[st][0]);
+    load_tile<!TB>(B, ldb, n0, N - 1, k0, K - 1, smem[st][1]);   // TB (B stored [N,K]) is the K-contiguous case
   };
 
-  if (nk > 0) issue(0, sA0, sB0);
-  for (int kt = 0; kt < nk; kt += 2) {
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's share of tile kt has landed
-    __syncthreads();                      // everyone's share has; everyone is done reading the other stage
-    if (kt + 1 < nk) issue(kt + 1, sA1, sB1);
-    compute_tile<TA, !TB>(sA0, sB0, wm0, wn0, acc, k_end - (k_begin + kt * BK));
-    if (kt + 1 < nk) {
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-      __syncthreads();
-      if (kt + 2 < nk) issue(kt + 2, sA0, sB0);
-      compute_tile<TA, !TB>(sA1, sB1, wm0, wn0, acc, k_end - (k_begin + (kt + 1) * BK));
-    }
+  // Ring of NSTAGE tiles, NSTAGE-1 in flight.  At step kt: wait until tile kt has landed (the loads of the
+  // up to NSTAGE-2 younger tiles may still be outstanding), barrier (all waves' shares have landed and
+  // everyone is done reading the stage of tile kt-1), refill that stage with tile kt+NSTAGE-1, compute.
+#pragma unroll
+  for (int p = 0; p < NSTAGE - 1; ++p)
+    if (p < nk) issue(p);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int younger = min(NSTAGE - 2, nk - 1 - kt);        // tiles issued after tile kt so far
+    if (NSTAGE > 3 && younger >= 2) WAIT_VMCNT(2 * LOADS_PER_TILE);
+    else if (NSTAGE > 2 && younger == 1) WAIT_VMCNT(LOADS_PER_TILE);
+    else WAIT_VMCNT(0);
+    __syncthreads();
+    const int st = kt % NSTAGE;
+    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+    compute_tile<TA, !TB>(smem[st][0], smem[st][1], wm0, wn0, acc, k_end - (k_begin + kt * BK));
   }
-
   // Epilogue.  Accumulator register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   float* Cf = (float*)Cv;
   bf16_t* Cb = (bf16_t*)Cv;
@@ -208,7 +238,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
           const int64_t idx = (int64_t)row * ldc + n0 + wn0 + j * 32 + (lane & 31);
           const float v = acc[i][j][r];
           if (MODE == 1) Cb[idx] = (bf16_t)v;
-          else if (MODE == 2) Cf[idx] += v;
+          else if (MODE == 2) unsafeAtomicAdd(&Cf[idx], v);   // one add per element per launch: same rounding as a
+                                                               // read-modify-write, but the wave does not wait for C
           else Cf[idx] = v;
         }
       }
