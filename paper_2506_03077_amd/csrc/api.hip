@@ -49,7 +49,7 @@ struct LayerWs {
   void *K, *V;                 // [T, Hkv*dh] dt   cached for the whole sequence
   float *dK, *dV;              // [T, Hkv*dh] fp32 prefix accumulators
   float2* rope;                // [T, dh/2] cos/sin
-  void *a, *q, *o, *m, *gate, *up, *act, *dh1_t, *d_o, *dq, *dkc, *dvc;   // per chunk, dt
+  void *a, *q, *o, *m, *gate, *up, *act, *dact, *dh1_t, *d_o, *dq, *dkc, *dvc;   // per chunk, dt
   float *h1, *dm, *dh1, *da, *proj;                                       // per chunk, fp32 [c, d]
   float *rstd1, *rstd2, *lse, *delta, *partial;
   float* gemm_scratch; size_t gemm_scratch_bytes;
@@ -87,6 +87,7 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   w.gate = cv.take_bytes(cm * F * es);
   w.up = cv.take_bytes(cm * F * es);
   w.act = cv.take_bytes(cm * F * es);
+  w.dact = cv.take_bytes(cm * F * es);
   w.dh1_t = cv.take_bytes(cm * d * es);
   w.d_o = cv.take_bytes(cm * qd * es);
   w.dq = cv.take_bytes(cm * qd * es);
@@ -151,8 +152,9 @@ int32_t kv_prepass(const sbp_layer_cfg* c, const sbp_layer_weights* w, const Lay
   for (int r0 = 0; r0 < T; r0 += cm) {
     const int n = std::min(cm, T - r0);
     HIPCHK(rmsnorm_fwd(dt, at(xb, r0, d, es), nullptr, w->g1, s.a, nullptr, s.rstd1, n, d, c->rms_eps, st));
-    HIPCHK(gemm(fwd_gemm(s.a, w->wk, at(s.K, r0, kd, es), n, kd, d, dt, dt), st));
-    HIPCHK(gemm(fwd_gemm(s.a, w->wv, at(s.V, r0, kd, es), n, kd, d, dt, dt), st));
+    const GemmArgs kv[2] = {fwd_gemm(s.a, w->wk, at(s.K, r0, kd, es), n, kd, d, dt, dt),
+                            fwd_gemm(s.a, w->wv, at(s.V, r0, kd, es), n, kd, d, dt, dt)};
+    HIPCHK(gemm_batch(kv, 2, st));
     HIPCHK(rope_apply(dt, at(s.K, r0, kd, es), s.rope + (size_t)r0 * (c->head_dim / 2), n, c->n_kv_heads, c->head_dim, false, st));
   }
   return SBP_OK;
@@ -175,8 +177,10 @@ int32_t chunk_reforward(const sbp_layer_cfg* c, const sbp_layer_weights* w, cons
   HIPCHK(attn_forward(aa, st));
   HIPCHK(gemm(fwd_gemm(s.o, w->wo, s.proj, n, d, qd, dt, DT_F32), st));
   HIPCHK(rmsnorm_fwd(dt, xc, s.proj, w->g2, s.m, s.h1, s.rstd2, n, d, c->rms_eps, st));
-  HIPCHK(gemm(fwd_gemm(s.m, w->wgate, s.gate, n, F, d, dt, dt), st));
-  HIPCHK(gemm(fwd_gemm(s.m, w->wup, s.up, n, F, d, dt, dt), st));
+  {
+    const GemmArgs gu[2] = {fwd_gemm(s.m, w->wgate, s.gate, n, F, d, dt, dt), fwd_gemm(s.m, w->wup, s.up, n, F, d, dt, dt)};
+    HIPCHK(gemm_batch(gu, 2, st));
+  }
   HIPCHK(swiglu_fwd(dt, s.gate, s.up, s.act, (int64_t)n * F, st));
   return SBP_OK;
 }
@@ -232,17 +236,13 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       const int r0 = ci * cm, n = std::min(cm, T - r0);
       if ((rc = chunk_reforward(c, w, s, xb, r0, n, st))) return rc;
       const char* dyc = at(dyb, r0, d, es);
-      // ---- MLP backward
-      HIPCHK(gemm(dw_gemm(dyc, s.act, g->wdown, n, d, F, dt), st));
-      HIPCHK(gemm(dx_gemm(dyc, w->wdown, s.act, n, d, F, dt, dt, false), st));      // dact overwrites act
-      HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.act, (int64_t)n * F, st));               // gate <- dgate, up <- dup
-      HIPCHK(gemm(dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt), st));
-      HIPCHK(gemm(dw_gemm(s.up, s.m, g->wup, n, F, d, dt), st));
+      // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
+      HIPCHK(gemm(dx_gemm(dyc, w->wdown, s.dact, n, d, F, dt, dt, false), st));
+      HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.dact, (int64_t)n * F, st));              // gate <- dgate, up <- dup
       HIPCHK(gemm(dx_gemm(s.gate, w->wgate, s.dm, n, F, d, dt, DT_F32, false), st));
       HIPCHK(gemm(dx_gemm(s.up, w->wup, s.dm, n, F, d, dt, DT_F32, true), st));
       HIPCHK(rmsnorm_bwd(dt, s.dm, s.h1, true, w->g2, s.rstd2, dyc, false, s.dh1, s.dh1_t, g->g2, s.partial, n, d, st));
       // ---- attention-side backward
-      HIPCHK(gemm(dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt), st));
       HIPCHK(gemm(dx_gemm(s.dh1_t, w->wo, s.d_o, n, d, qd, dt, dt, false), st));
       AttnArgs aa{};
       aa.dt = dt; aa.Hq = c->n_q_heads; aa.Hkv = c->n_kv_heads; aa.dh = c->head_dim;
@@ -251,15 +251,20 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       aa.d_o = s.d_o; aa.dq = s.dq; aa.dk = s.dK; aa.dv = s.dV; aa.delta = s.delta;
       HIPCHK(attn_backward(aa, st));
       HIPCHK(rope_apply(dt, s.dq, s.rope + (size_t)r0 * half, n, c->n_q_heads, c->head_dim, true, st));
-      HIPCHK(gemm(dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt), st));
       HIPCHK(gemm(dx_gemm(s.dq, w->wq, s.da, n, qd, d, dt, DT_F32, false), st));
       // ---- K/V side of rows [r0, r0+n): final now
       HIPCHK(kv_grad_finish(dt, s.dK + (size_t)r0 * kd, s.dV + (size_t)r0 * kd, s.rope + (size_t)r0 * half, s.dkc, s.dvc,
                             n, c->n_kv_heads, c->head_dim, st));
-      HIPCHK(gemm(dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt), st));
-      HIPCHK(gemm(dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt), st));
       HIPCHK(gemm(dx_gemm(s.dkc, w->wk, s.da, n, kd, d, dt, DT_F32, true), st));
       HIPCHK(gemm(dx_gemm(s.dvc, w->wv, s.da, n, kd, d, dt, DT_F32, true), st));
+      // ---- all seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand), one launch
+      {
+        const GemmArgs dws[7] = {dw_gemm(dyc, s.act, g->wdown, n, d, F, dt),   dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt),
+                                 dw_gemm(s.up, s.m, g->wup, n, F, d, dt),     dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt),
+                                 dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt),     dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt),
+                                 dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt)};
+        HIPCHK(gemm_batch(dws, 7, st));
+      }
       HIPCHK(rmsnorm_bwd(dt, s.da, at(xb, r0, d, es), false, w->g1, s.rstd1, s.dh1, true, nullptr, at(dxb, r0, d, es),
                          g->g1, s.partial, n, d, st));
     }

@@ -47,7 +47,8 @@ constexpr int ROW_BYTES = DH * 2;        // 256 B per tile row
 constexpr int AT_THREADS = 256;          // 4 waves
 constexpr int TQ = ATTN_TILE_Q;          // 128 queries per workgroup (fwd, dQ)
 constexpr int TK = ATTN_TILE_K;          // 64 keys per step (fwd, dQ)
-constexpr int KV_TILE = 128;             // keys per workgroup (dK/dV)
+constexpr int KV_TILE = 128;             // keys per workgroup (dK/dV): 4 waves x 32 keys
+constexpr int KV_THREADS = 256;
 constexpr int QT = 64;                   // queries per step (dK/dV)
 constexpr int TILE64_BYTES = 64 * ROW_BYTES;   // 16 KiB
 constexpr float LOG2E = 1.4426950408889634f;
@@ -62,15 +63,16 @@ __device__ __forceinline__ int tile_off(int row, int chunk) { return row * ROW_B
 
 // Direct-to-LDS load of a 64-row tile: rows row0..row0+63 of a [*, stride] bf16 matrix (row index clamped to
 // row_max so that nothing past the valid rows is ever read), 128 columns starting at g.
+template <int NT = AT_THREADS>
 __device__ __forceinline__ void dma_tile64(const bf16_t* __restrict__ g, int64_t stride, int row0, int row_max, char* lds) {
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int id = i * AT_THREADS + tid;
+  for (int i = 0; i < 1024 / NT; ++i) {
+    const int id = i * NT + tid;
     const int row = id >> 4, pc = id & 15;
     const int chunk = pc ^ swz(row);
     const bf16_t* src = g + (int64_t)min(row0 + row, row_max) * stride + chunk * 8;
-    char* dst = lds + (size_t)(i * AT_THREADS + (tid & ~63)) * 16;
+    char* dst = lds + (size_t)(i * NT + (tid & ~63)) * 16;
     __builtin_amdgcn_global_load_lds(src, LDS_AS(dst), 16, 0, 0);
   }
 }
@@ -166,34 +168,40 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_mfma_k(const bf16_t* _
       for (int ks = 0; ks < 8; ++ks) s[b] = MFMA(frag_rows(sK, b * 32, ks), bq[ks], s[b]);
     }
     const bool diag = k0 + TK - 1 > wave_first_qpos;      // some (query, key) pair of the wave is masked
-    float mx = -INFINITY;
+    if (diag) {                                           // wave-uniform: only tiles on the diagonal pay for the mask
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (k0 + b * 32 + acc_row(r, half) > qpos) s[b][r] = -INFINITY;
+    }
+    float mx = s[0][0];                                   // max of the raw scores (scale > 0 keeps the order)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = s[b][r] * sl;
-        if (diag && (k0 + b * 32 + acc_row(r, half) > qpos)) x = -INFINITY;
-        s[b][r] = x;
-        mx = fmaxf(mx, x);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = exp2f(m_run - m_new);
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[b][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sl;
+    // The running max (and with it the rescale of O) only moves when some query of the wave sees a new maximum.
+    if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[b][r] - m_new);
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], sl, -m_run));
         s[b][r] = p;
         psum += p;
       }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+    l_run += psum;
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -291,10 +299,14 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_bwd_dq_mfma_k(const bf16_t
       for (int ks = 0; ks < 8; ++ks) s = MFMA(frag_rows(sK, b * 32, ks), bq[ks], s);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) dp = MFMA(frag_rows(sV, b * 32, ks), bdo[ks], dp);
+      if (diag) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (k0 + b * 32 + acc_row(r, half) > qpos) s[r] = -INFINITY;     // exp2(-inf) = 0
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = exp2f(s[r] * sl - lse2);
-        if (diag && (k0 + b * 32 + acc_row(r, half) > qpos)) p = 0.f;
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sl, -lse2));
         s[r] = p * (dp[r] - dlt);                              // dS^T (the factor `scale` is applied at the end)
       }
 #pragma unroll
@@ -339,7 +351,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_bwd_dq_mfma_k(const bf16_t
 }
 
 // -------------------------------------------------------------------- dK/dV --
-__global__ __launch_bounds__(AT_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(KV_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                                      const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
                                                                      const float* __restrict__ lse, const float* __restrict__ delta,
                                                                      float* __restrict__ dk, float* __restrict__ dv, int Hq, int Hkv,
@@ -348,6 +360,7 @@ __global__ __launch_bounds__(AT_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
   __shared__ __attribute__((aligned(1024))) char sD0[TILE64_BYTES];
   __shared__ __attribute__((aligned(1024))) char sQ1[TILE64_BYTES];
   __shared__ __attribute__((aligned(1024))) char sD1[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sV[KV_TILE / 64][TILE64_BYTES];   // V rows of the workgroup's keys
   __shared__ __attribute__((aligned(16))) float sL[2][QT];     // log-sum-exp of the tile's queries
   __shared__ __attribute__((aligned(16))) float sDl[2][QT];    // delta of the tile's queries
 
@@ -361,12 +374,19 @@ __global__ __launch_bounds__(AT_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
   const int64_t kv_stride = (int64_t)Hkv * DH;
   const int64_t q_stride = (int64_t)Hq * DH;
 
-  bf16x8 bk[8], bv[8];
+  // K fragments of the wave's 32 keys stay in registers; the V fragments are re-read from LDS (keeping both
+  // resident costs more registers than the kernel has).
+  bf16x8 bk[8];
   {
     const int64_t off = (int64_t)key_row * kv_stride + (int64_t)kvh * DH + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) { bk[ks] = *(const bf16x8*)(k + off + ks * 16); bv[ks] = *(const bf16x8*)(v + off + ks * 16); }
+    for (int ks = 0; ks < 8; ++ks) bk[ks] = *(const bf16x8*)(k + off + ks * 16);
   }
+#pragma unroll
+  for (int t = 0; t < KV_TILE / 64; ++t)      // landed by the first wait + barrier of the main loop
+    dma_tile64<KV_THREADS>(v + (int64_t)kvh * DH, kv_stride, key0 + 64 * t, n_total - 1, sV[t]);
+  const char* sVw = sV[wave >> 1];
+  const int v_row0 = (wave & 1) * 32;
   f32x16 acc_k[4], acc_v[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) { acc_k[i] = zero16(); acc_v[i] = zero16(); }
@@ -379,8 +399,8 @@ __global__ __launch_bounds__(AT_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
 
   auto issue = [&](int it, char* sQ, char* sD, int buf) {
     const int qt = qt_first + it / G, hh = kvh * G + it % G;
-    dma_tile64(q + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQ);
-    dma_tile64(d_o + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sD);
+    dma_tile64<KV_THREADS>(q + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQ);
+    dma_tile64<KV_THREADS>(d_o + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sD);
     if (wave < 2) {   // 64 log-sum-exp values (wave 0) and 64 deltas (wave 1), 4 B per lane, also direct to LDS
       const int row = min(qt * QT + lane, c - 1);
       const float* src = (wave == 0 ? lse : delta) + (int64_t)hh * c + row;
@@ -399,8 +419,15 @@ __global__ __launch_bounds__(AT_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) s = MFMA(frag_rows(sQ, b * 32, ks), bk[ks], s);
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) dp = MFMA(frag_rows(sD, b * 32, ks), bv[ks], dp);
+      for (int ks = 0; ks < 8; ++ks) dp = MFMA(frag_rows(sD, b * 32, ks), frag_rows(sVw, v_row0, ks), dp);
       // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
+      if (diag) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qi = qbase + b * 32 + acc_row(r, half);
+          if (qi >= c || my_key > q_start + qi) s[r] = -INFINITY;          // exp2(-inf) = 0
+        }
+      }
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         const float4 l4 = *(const float4*)&sL[buf][b * 32 + 8 * a + 4 * half];
@@ -409,11 +436,7 @@ __global__ __launch_bounds__(AT_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * a + e;
-          float p = exp2f(s[r] * sl - lv[e] * LOG2E);
-          if (diag) {
-            const int qi = qbase + b * 32 + 8 * a + 4 * half + e;
-            if (qi >= c || my_key > q_start + qi) p = 0.f;
-          }
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sl, -lv[e] * LOG2E));
           s[r] = p;
           dp[r] = p * (dp[r] - dl[e]);
         }
@@ -503,7 +526,7 @@ hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st) {
   attn_bwd_dq_mfma_k<<<gq, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
                                                 a.lse, a.delta, (bf16_t*)a.dq, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
   dim3 gk((unsigned)cdiv(a.q_start + a.q_len, KV_TILE), a.Hkv);
-  attn_bwd_dkv_mfma_k<<<gk, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
+  attn_bwd_dkv_mfma_k<<<gk, KV_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
                                                  a.lse, a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
   return hipGetLastError();
 }

@@ -9,6 +9,8 @@ namespace sbp {
 hipError_t gemm_generic(const GemmArgs& g, hipStream_t st);
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st);
 bool gemm_mfma_eligible(const GemmArgs& g);
+bool gemm_mfma_group_eligible(const GemmArgs* gs, int n);
+hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st);
 hipError_t attn_forward_generic(const AttnArgs& a, hipStream_t st);
 hipError_t attn_backward_generic(const AttnArgs& a, hipStream_t st);
 hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st);
@@ -57,6 +59,20 @@ hipError_t gemm(const GemmArgs& g, hipStream_t st) {
   const int kind = !mfma ? prof::GEMM_GENERIC : (g.ta ? prof::GEMM_TN : (g.tb ? prof::GEMM_NT : prof::GEMM_NN));
   prof::Scope sc(kind, 2.0 * g.M * g.N * g.K, st);
   return mfma ? gemm_mfma(g, st) : gemm_generic(g, st);
+}
+hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st) {
+  if (!g_force_generic_gemm && gemm_mfma_group_eligible(gs, n)) {
+    double work = 0.0;
+    for (int i = 0; i < n; ++i) work += 2.0 * gs[i].M * gs[i].N * gs[i].K;
+    const int kind = gs[0].ta ? prof::GEMM_TN : (gs[0].tb ? prof::GEMM_NT : prof::GEMM_NN);
+    prof::Scope sc(kind, work, st);
+    return gemm_mfma_group(gs, n, st);
+  }
+  for (int i = 0; i < n; ++i) {
+    hipError_t e = gemm(gs[i], st);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 hipError_t attn_forward(const AttnArgs& a, hipStream_t st) {
   prof::Scope sc(prof::ATTN_FWD, 4.0 * a.dh * causal_pairs(a), st);

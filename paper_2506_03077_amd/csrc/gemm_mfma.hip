@@ -152,14 +152,9 @@ __device__ __forceinline__ void compute_tile(const char* sA, const char* sB, int
   }
 }
 
-// blockIdx.x -> (tile_m, tile_n).  Hardware deals consecutive workgroups round-robin to the 8 XCDs; undo
-// that so each XCD gets a contiguous run of tile ids, then walk tiles in column bands of GROUP_M row tiles
-// so that the workgroups resident together share A row panels and B column panels in that XCD's L2.
-__device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, int& tn) {
-  const int n_tiles = tiles_m * tiles_n;
-  int id = blockIdx.x;
-  constexpr int NXCD = 8;
-  if (n_tiles % NXCD == 0) id = (id % NXCD) * (n_tiles / NXCD) + id / NXCD;
+// Tile id -> (tile_m, tile_n): walk tiles in column bands of GROUP_M row tiles so that the workgroups resident
+// together share A row panels and B column panels in their XCD's L2.
+__device__ __forceinline__ void band_coords(int id, int tiles_m, int tiles_n, int& tm, int& tn) {
   constexpr int GROUP_M = 8;
   const int band = GROUP_M * tiles_n;
   const int g = id / band;
@@ -169,26 +164,25 @@ __device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int& tm, i
   tm = first_m + r % gsz;
   tn = r / gsz;
 }
+// Hardware deals consecutive workgroups round-robin to the 8 XCDs (each with its own L2); undo that so each
+// XCD gets a contiguous run of tile ids.
+__device__ __forceinline__ int xcd_contiguous_id(int id, int n_tiles) {
+  constexpr int NXCD = 8;
+  return (n_tiles % NXCD == 0) ? (id % NXCD) * (n_tiles / NXCD) + id / NXCD : id;
+}
 
 // vmcnt(n) with expcnt / lgkmcnt left unconstrained
 #define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
 
-// MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store to scratch slice z)
+// One 256x256 output tile: K range [k_begin, k_end).
+// MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store, C already offset)
 template <bool TA, bool TB, int MODE>
-__global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                                        void* __restrict__ Cv, int M, int N, int K, int64_t lda,
-                                                        int64_t ldb, int64_t ldc, int k_per_split) {
-  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
-
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-  int tm, tn;
-  tile_coords(tiles_m, tiles_n, tm, tn);
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ Cv,
+                                          int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc, int k_begin, int k_end,
+                                          int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES]) {
   const int m0 = tm * BM, n0 = tn * BN;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm0 = (wave / NWAVE_N) * WTM, wn0 = (wave % NWAVE_N) * WTN;
-
-  const int k_begin = blockIdx.z * k_per_split;
-  const int k_end = min(K, k_begin + k_per_split);
   const int nk = (k_end - k_begin + BK - 1) / BK;
 
   f32x16 acc[FM][FN];
@@ -223,10 +217,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
     if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
     compute_tile<TA, !TB>(smem[st][0], smem[st][1], wm0, wn0, acc, k_end - (k_begin + kt * BK));
   }
+
   // Epilogue.  Accumulator register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   float* Cf = (float*)Cv;
   bf16_t* Cb = (bf16_t*)Cv;
-  if (MODE == 3) Cf += (int64_t)blockIdx.z * M * ldc;
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -244,6 +238,45 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
         }
       }
     }
+}
+
+template <bool TA, bool TB, int MODE>
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                        void* __restrict__ Cv, int M, int N, int K, int64_t lda,
+                                                        int64_t ldb, int64_t ldc, int k_per_split) {
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  int tm, tn;
+  band_coords(xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tm, tn);
+  const int k_begin = blockIdx.z * k_per_split;
+  const int k_end = min(K, k_begin + k_per_split);
+  if (MODE == 3) Cv = (float*)Cv + (int64_t)blockIdx.z * M * ldc;
+  gemm_tile<TA, TB, MODE>(A, B, Cv, M, N, K, lda, ldb, ldc, k_begin, k_end, tm, tn, smem);
+}
+
+// Several independent GEMMs of one layout / output mode in a single launch: the tiles of all problems form one
+// grid, so small problems fill the tail of large ones instead of each paying its own partial last round.
+constexpr int MAX_GROUP = 8;
+struct GroupProblem {
+  const bf16_t* A; const bf16_t* B; void* C;
+  int M, N, K;
+  int64_t lda, ldb, ldc;
+  int tile_begin, tiles_m, tiles_n;
+};
+struct GroupArgs { GroupProblem p[MAX_GROUP]; int n; int total_tiles; };
+
+template <bool TA, bool TB, int MODE>
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_group_k(const GroupArgs ga) {
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];
+  const int id = xcd_contiguous_id(blockIdx.x, ga.total_tiles);
+  int pi = 0;
+#pragma unroll
+  for (int i = 1; i < MAX_GROUP; ++i)
+    if (i < ga.n && id >= ga.p[i].tile_begin) pi = i;
+  const GroupProblem& g = ga.p[pi];
+  int tm, tn;
+  band_coords(id - g.tile_begin, g.tiles_m, g.tiles_n, tm, tn);
+  gemm_tile<TA, TB, MODE>(g.A, g.B, g.C, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0, g.K, tm, tn, smem);
 }
 
 // C (=|+=) sum_z partial[z] in a fixed order; OUT_BF16 rounds once at the end.
@@ -333,6 +366,47 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   else LAUNCH_LAYOUT(0, g.C);
 #undef LAUNCH_LAYOUT
 #undef LAUNCH
+  return hipGetLastError();
+}
+
+
+// Grouped launch.  Requires every problem to be eligible, of the same layout / output type / accumulate mode.
+bool gemm_mfma_group_eligible(const GemmArgs* gs, int n) {
+  if (n < 2 || n > MAX_GROUP) return false;
+  int64_t tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!gemm_mfma_eligible(gs[i])) return false;
+    if (gs[i].ta != gs[0].ta || gs[i].tb != gs[0].tb || gs[i].out_dt != gs[0].out_dt || gs[i].acc != gs[0].acc) return false;
+    tiles += cdiv(gs[i].M, BM) * (gs[i].N / BN);
+  }
+  return tiles >= 200 && tiles < (1 << 30);   // otherwise per-problem launches with split-K fill the chip better
+}
+
+hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
+  GroupArgs ga{};
+  ga.n = n;
+  int tiles = 0;
+  for (int i = 0; i < n; ++i) {
+    GroupProblem& p = ga.p[i];
+    p.A = (const bf16_t*)gs[i].A; p.B = (const bf16_t*)gs[i].B; p.C = gs[i].C;
+    p.M = gs[i].M; p.N = gs[i].N; p.K = gs[i].K; p.lda = gs[i].lda; p.ldb = gs[i].ldb; p.ldc = gs[i].ldc;
+    p.tiles_m = (int)cdiv(gs[i].M, BM); p.tiles_n = gs[i].N / BN; p.tile_begin = tiles;
+    tiles += p.tiles_m * p.tiles_n;
+  }
+  ga.total_tiles = tiles;
+  const GemmArgs& g = gs[0];
+#define GLAUNCH(TA, TB, MODE) gemm_mfma_group_k<TA, TB, MODE><<<tiles, NTHREADS, 0, st>>>(ga)
+#define GLAUNCH_LAYOUT(MODE)                     \
+  do {                                           \
+    if (!g.ta && g.tb) GLAUNCH(false, true, MODE); \
+    else if (!g.ta && !g.tb) GLAUNCH(false, false, MODE); \
+    else GLAUNCH(true, false, MODE);             \
+  } while (0)
+  if (g.out_dt == DT_BF16) GLAUNCH_LAYOUT(1);
+  else if (g.acc) GLAUNCH_LAYOUT(2);
+  else GLAUNCH_LAYOUT(0);
+#undef GLAUNCH_LAYOUT
+#undef GLAUNCH
   return hipGetLastError();
 }
 

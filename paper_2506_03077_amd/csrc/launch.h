@@ -23,6 +23,8 @@ struct GemmArgs {
 // upper bound of the scratch a GEMM with M <= max_m rows and N <= max_n columns may use
 size_t gemm_scratch_bytes(int max_m, int max_n);
 hipError_t gemm(const GemmArgs& g, hipStream_t st);
+// n independent GEMMs (distinct outputs); one grouped launch when the MFMA kernel can take them all
+hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st);
 // true when the bf16 MFMA kernel can take this problem (used by tests / tile accounting)
 bool gemm_uses_mfma(const GemmArgs& g);
 // force the generic kernel (debug / A-B tests)
