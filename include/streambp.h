@@ -206,6 +206,47 @@ int32_t streambp_embedding_forward(int32_t dtype, int64_t n_rows, int32_t hidden
 int32_t streambp_embedding_backward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab,
                                     const int32_t *ids, const void *dx, float *demb, void *hip_stream);
 
+/* ----------------------------------------------------------------- stack -- */
+
+/* Layer-wise StreamBP through a stack of identical-shape layers from per-layer
+ * checkpoints (Sec. 2: checkpointed layer inputs; Sec. 3.1: the gradient of a
+ * layer's output is the input of the backward of the layer before it):
+ *   x_0 = emb[ids];  x_{l+1} = layer_l(x_l);  h = RMSNorm(x_L; g_final);
+ *   L = objective(h W_head^T, targets).
+ * ckpt[l] (l = 0..L) are caller-owned [B, T, d] buffers: ckpt[l] holds the
+ * input of layer l, ckpt[L] the output of the last layer. */
+typedef struct {
+  sbp_layer_cfg layer;      /* shape of every layer; its chunk is the layer chunk */
+  int32_t n_layers;
+  int32_t vocab;
+  int32_t head_chunk;       /* rows of logits alive at once                       */
+  int32_t objective;        /* as in sbp_head_cfg                                 */
+  float loss_scale, clip_eps, kl_beta;
+  int32_t kl_mode;
+  float final_eps;          /* eps of the final RMSNorm                           */
+} sbp_stack_cfg;
+
+size_t streambp_stack_workspace_bytes(const sbp_stack_cfg *cfg);
+
+/* Chunked forward that fills the checkpoints.  emb [V, d] and ids [B, T] may both
+ * be NULL, in which case ckpt[0] must already hold the stack input. */
+int32_t streambp_stack_forward(const sbp_stack_cfg *cfg, const sbp_layer_weights *layers /*[L]*/,
+                               const void *emb, const int32_t *ids, void *const *ckpt /*[L+1]*/,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Backward: LM head + objective on RMSNorm(ckpt[L]), final norm, then layers
+ * L-1 .. 0, each by streambp_layer_backward on its checkpoint.
+ *   dlayers [L] (+=), dg_final [d] fp32 (+=), dw_head [V, d] fp32 (+=; DPO: zero on entry),
+ *   demb [V, d] fp32 (+=, may be NULL together with ids), loss (+=), n_active (out);
+ *   dx0 [B, T, d] out (may be NULL): gradient wrt the stack input. */
+int32_t streambp_stack_backward(const sbp_stack_cfg *cfg, const sbp_layer_weights *layers,
+                                const void *g_final, const void *w_head, void *const *ckpt,
+                                const int32_t *ids, const int32_t *targets, const float *old_logp,
+                                const float *ref_logp, const float *advantages,
+                                const sbp_layer_grads *dlayers, float *dg_final, float *dw_head,
+                                float *demb, void *dx0, float *loss, int64_t *n_active,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------ misc -- */
 
 const char *streambp_version(void);

@@ -49,6 +49,12 @@ class AttnCfg(C.Structure):
                 ("q_start", C.c_int32), ("q_len", C.c_int32), ("scale", C.c_float)]
 
 
+class StackCfg(C.Structure):
+    _fields_ = [("layer", LayerCfg), ("n_layers", C.c_int32), ("vocab", C.c_int32), ("head_chunk", C.c_int32),
+                ("objective", C.c_int32), ("loss_scale", C.c_float), ("clip_eps", C.c_float), ("kl_beta", C.c_float),
+                ("kl_mode", C.c_int32), ("final_eps", C.c_float)]
+
+
 _lib = None
 
 
@@ -97,6 +103,13 @@ def lib():
         L.streambp_debug_force_generic.argtypes = [C.c_int, C.c_int]
         L.streambp_debug_gemm.restype = C.c_int
         L.streambp_debug_gemm.argtypes = [C.c_int] * 8 + [vp, vp, vp, C.c_longlong, C.c_longlong, C.c_longlong, vp, sz, vp]
+        L.streambp_stack_workspace_bytes.restype = sz
+        L.streambp_stack_workspace_bytes.argtypes = [C.POINTER(StackCfg)]
+        L.streambp_stack_forward.restype = i32
+        L.streambp_stack_forward.argtypes = [C.POINTER(StackCfg), C.POINTER(LayerWeights), vp, vp, C.POINTER(vp), vp, sz, vp]
+        L.streambp_stack_backward.restype = i32
+        L.streambp_stack_backward.argtypes = [C.POINTER(StackCfg), C.POINTER(LayerWeights), vp, vp, C.POINTER(vp), vp, vp, vp, vp,
+                                              vp, C.POINTER(LayerGrads), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.streambp_debug_profile_begin.restype = C.c_int
         L.streambp_debug_profile_begin.argtypes = [C.c_int]
         L.streambp_debug_profile_end.restype = C.c_int
@@ -342,3 +355,57 @@ def debug_profile_end():
     if rc != 0:
         raise StreamBPError(rc, "profile_end failed")
     return {k: dict(count=int(cnt[i]), ms=float(ms[i]), flops=float(work[i])) for i, k in enumerate(PROFILE_KINDS)}
+
+
+def stack_cfg(layer: LayerCfg, n_layers, vocab, head_chunk, objective=SBP_OBJ_SFT, loss_scale=1.0, clip_eps=0.2,
+              kl_beta=0.04, kl_mode=0, final_eps=1e-6):
+    return StackCfg(layer, n_layers, vocab, head_chunk, objective, loss_scale, clip_eps, kl_beta, kl_mode, final_eps)
+
+
+def streambp_stack_workspace_bytes(cfg: StackCfg) -> int:
+    return int(lib().streambp_stack_workspace_bytes(C.byref(cfg)))
+
+
+def _ptr_array(tensors):
+    return (C.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
+
+
+def streambp_stack_forward(cfg: StackCfg, layers, ckpt, emb=None, ids=None, workspace=None, stream=None):
+    """layers: list of weight dicts; ckpt: list of L+1 [B,T,d] tensors (filled: ckpt[l] = input of layer l)."""
+    if workspace is None:
+        workspace = _workspace(streambp_stack_workspace_bytes(cfg), ckpt[0].device)
+    ws = (LayerWeights * len(layers))(*[_weights_struct(w) for w in layers])
+    _check(lib().streambp_stack_forward(C.byref(cfg), ws, _ptr(emb), _ptr(ids), _ptr_array(ckpt), _ptr(workspace),
+                                        workspace.numel(), _stream(stream)))
+    return ckpt
+
+
+def streambp_stack_backward(cfg: StackCfg, layers, g_final, w_head, ckpt, targets, ids=None, old_logp=None, ref_logp=None,
+                            advantages=None, dlayers=None, dg_final=None, dw_head=None, demb=None, dx0=None, loss=None,
+                            n_active=None, workspace=None, stream=None):
+    """Returns dict(dlayers, dg_final, dw_head, demb, dx0, loss, n_active); gradient tensors are accumulated into."""
+    torch = _torch()
+    dev = ckpt[0].device
+    if dlayers is None:
+        dlayers = [new_layer_grads(w) for w in layers]
+    if dg_final is None:
+        dg_final = torch.zeros(g_final.shape, dtype=torch.float32, device=dev)
+    if dw_head is None:
+        dw_head = torch.zeros(w_head.shape, dtype=torch.float32, device=dev)
+    if ids is not None and demb is None:
+        demb = torch.zeros(w_head.shape, dtype=torch.float32, device=dev)
+    if dx0 is None:
+        dx0 = torch.empty_like(ckpt[0])
+    if loss is None:
+        loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    if n_active is None:
+        n_active = torch.zeros(1, dtype=torch.int64, device=dev)
+    if workspace is None:
+        workspace = _workspace(streambp_stack_workspace_bytes(cfg), dev)
+    ws = (LayerWeights * len(layers))(*[_weights_struct(w) for w in layers])
+    gs = (LayerGrads * len(layers))(*[LayerGrads(*[_ptr(g[n]) for n in WEIGHT_NAMES]) for g in dlayers])
+    _check(lib().streambp_stack_backward(C.byref(cfg), ws, _ptr(g_final), _ptr(w_head), _ptr_array(ckpt), _ptr(ids),
+                                         _ptr(targets), _ptr(old_logp), _ptr(ref_logp), _ptr(advantages), gs,
+                                         _ptr(dg_final), _ptr(dw_head), _ptr(demb), _ptr(dx0), _ptr(loss), _ptr(n_active),
+                                         _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dict(dlayers=dlayers, dg_final=dg_final, dw_head=dw_head, demb=demb, dx0=dx0, loss=loss, n_active=n_active)

@@ -442,6 +442,102 @@ int64_t streambp_attn_tile_pairs(int32_t q_start, int32_t q_len, int32_t* tile_q
   return pairs;
 }
 
+// ------------------------------------------------------------ stack loop --
+namespace {
+struct StackWs { void *h, *dh, *ga, *gb; void* sub; size_t sub_bytes; size_t bytes; };
+sbp_head_cfg stack_head_cfg(const sbp_stack_cfg* c) {
+  sbp_head_cfg h{};
+  h.dtype = c->layer.dtype; h.batch = c->layer.batch; h.seq_len = c->layer.seq_len; h.chunk = c->head_chunk;
+  h.hidden = c->layer.hidden; h.vocab = c->vocab; h.objective = c->objective; h.loss_scale = c->loss_scale;
+  h.clip_eps = c->clip_eps; h.kl_beta = c->kl_beta; h.kl_mode = c->kl_mode;
+  return h;
+}
+int32_t check_stack_cfg(const sbp_stack_cfg* c) {
+  if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
+  int32_t rc = check_layer_cfg(&c->layer);
+  if (rc) return rc;
+  if (c->n_layers < 1) return fail(SBP_ERR_SHAPE, "n_layers must be >= 1");
+  if (!(c->final_eps >= 0.f)) return fail(SBP_ERR_SHAPE, "final_eps must be >= 0");
+  const sbp_head_cfg h = stack_head_cfg(c);
+  return check_head_cfg(&h);
+}
+StackWs carve_stack(const sbp_stack_cfg* c, void* ws) {
+  const size_t rows = (size_t)c->layer.batch * c->layer.seq_len, d = c->layer.hidden, es = dtype_size(c->layer.dtype);
+  const sbp_head_cfg h = stack_head_cfg(c);
+  Carver cv(ws);
+  StackWs s;
+  s.h = cv.take_bytes(rows * d * es);      // RMSNorm(ckpt[L])
+  s.dh = cv.take_bytes(rows * d * es);     // gradient wrt h
+  s.ga = cv.take_bytes(rows * d * es);     // running dL/dx, ping
+  s.gb = cv.take_bytes(rows * d * es);     // pong
+  s.sub_bytes = std::max(std::max(streambp_layer_workspace_bytes(&c->layer), streambp_lmhead_workspace_bytes(&h)),
+                         streambp_rmsnorm_workspace_bytes((int64_t)rows, (int32_t)d));
+  s.sub = cv.take_bytes(s.sub_bytes);
+  s.bytes = cv.off;
+  return s;
+}
+}  // namespace
+
+extern "C" size_t streambp_stack_workspace_bytes(const sbp_stack_cfg* cfg) {
+  if (check_stack_cfg(cfg) != SBP_OK) return 0;
+  return carve_stack(cfg, nullptr).bytes;
+}
+
+extern "C" int32_t streambp_stack_forward(const sbp_stack_cfg* c, const sbp_layer_weights* layers, const void* emb,
+                                          const int32_t* ids, void* const* ckpt, void* workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
+  int32_t rc = check_stack_cfg(c);
+  if (rc) return rc;
+  if (!layers || !ckpt || !workspace) return fail(SBP_ERR_NULL, "layers, ckpt and workspace must be non-NULL");
+  if ((emb == nullptr) != (ids == nullptr)) return fail(SBP_ERR_NULL, "emb and ids must be given together");
+  for (int l = 0; l <= c->n_layers; ++l) if (!ckpt[l]) return fail(SBP_ERR_NULL, "ckpt[%d] is NULL", l);
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const StackWs s = carve_stack(c, workspace);
+  if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
+  const int64_t rows = (int64_t)c->layer.batch * c->layer.seq_len;
+  if (emb && (rc = streambp_embedding_forward(c->layer.dtype, rows, c->layer.hidden, c->vocab, ids, emb, ckpt[0], hip_stream))) return rc;
+  for (int l = 0; l < c->n_layers; ++l)
+    if ((rc = streambp_layer_forward(&c->layer, &layers[l], ckpt[l], ckpt[l + 1], s.sub, s.sub_bytes, hip_stream))) return rc;
+  return SBP_OK;
+}
+
+extern "C" int32_t streambp_stack_backward(const sbp_stack_cfg* c, const sbp_layer_weights* layers, const void* g_final,
+                                           const void* w_head, void* const* ckpt, const int32_t* ids, const int32_t* targets,
+                                           const float* old_logp, const float* ref_logp, const float* advantages,
+                                           const sbp_layer_grads* dlayers, float* dg_final, float* dw_head, float* demb,
+                                           void* dx0, float* loss, int64_t* n_active, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream) {
+  int32_t rc = check_stack_cfg(c);
+  if (rc) return rc;
+  if (!layers || !g_final || !w_head || !ckpt || !targets || !dlayers || !dg_final || !dw_head || !loss || !n_active || !workspace)
+    return fail(SBP_ERR_NULL, "a required pointer is NULL");
+  if ((demb == nullptr) != (ids == nullptr)) return fail(SBP_ERR_NULL, "demb and ids must be given together");
+  for (int l = 0; l <= c->n_layers; ++l) if (!ckpt[l]) return fail(SBP_ERR_NULL, "ckpt[%d] is NULL", l);
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const StackWs s = carve_stack(c, workspace);
+  if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
+  const int64_t rows = (int64_t)c->layer.batch * c->layer.seq_len;
+  const int d = c->layer.hidden, dt = c->layer.dtype;
+  const sbp_head_cfg hc = stack_head_cfg(c);
+  const int L = c->n_layers;
+  // head on h = RMSNorm(x_L), then the final norm's adjoint
+  if ((rc = streambp_rmsnorm_forward(dt, rows, d, c->final_eps, ckpt[L], g_final, s.h, hip_stream))) return rc;
+  if ((rc = streambp_lmhead_ce_backward(&hc, w_head, s.h, targets, old_logp, ref_logp, advantages, s.dh, dw_head, loss, n_active,
+                                        s.sub, s.sub_bytes, hip_stream))) return rc;
+  if ((rc = streambp_rmsnorm_backward(dt, rows, d, c->final_eps, ckpt[L], g_final, s.dh, s.ga, dg_final, s.sub, s.sub_bytes, hip_stream))) return rc;
+  // layers L-1 .. 0: dL/dx of layer l is dL/dy of layer l-1 (Sec. 3.1)
+  void* gin = s.ga;
+  void* gout = s.gb;
+  for (int l = L - 1; l >= 0; --l) {
+    void* dst = (l == 0 && dx0) ? dx0 : gout;
+    if ((rc = streambp_layer_backward(&c->layer, &layers[l], ckpt[l], gin, dst, &dlayers[l], s.sub, s.sub_bytes, hip_stream))) return rc;
+    gout = gin;
+    gin = dst;
+  }
+  if (demb && (rc = streambp_embedding_backward(dt, rows, d, c->vocab, ids, gin, demb, hip_stream))) return rc;
+  return SBP_OK;
+}
+
 // ------------------------------------------------------------ stack glue --
 size_t streambp_rmsnorm_workspace_bytes(int64_t n_rows, int32_t hidden) {
   if (n_rows < 0 || n_rows > INT32_MAX || hidden < 1) return 0;

@@ -1,7 +1,8 @@
 // LM-head row kernels: per-row log-sum-exp over the chunk's logits, the
 // per-token objective coefficient (SFT / GRPO / DPO, paper Sec. 3.2.1) and
-// dz = coef * (onehot(target) - softmax(z)).  One workgroup per row; the label
-// gather z[target] and the ignore mask are integer-indexed and exact.
+// dz = coef * (onehot(target) - softmax(z)).  One workgroup per row, two passes
+// over the row (statistics, then dz); the label gather z[target] and the ignore
+// mask are integer-indexed and exact.
 #include "launch.h"
 #include <algorithm>
 
@@ -17,16 +18,40 @@ __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
   T* dz = (T*)a.dz + (int64_t)row * a.V;
   const int tgt = a.targets[row];
   if (tgt < 0) {   // ignored row: exact zeros, no loss term
-    for (int v = tid; v < a.V; v += HR_THREADS) stf(dz + v, 0.f);
+    const int64_t row_bytes = (int64_t)a.V * sizeof(T);
+    if ((row_bytes & 15) == 0) {
+      uint4* p16 = (uint4*)dz;
+      for (int v = tid; v < row_bytes / 16; v += HR_THREADS) p16[v] = make_uint4(0, 0, 0, 0);
+    } else {
+      for (int v = tid; v < a.V; v += HR_THREADS) stf(dz + v, 0.f);
+    }
     if (tid == 0) a.row_loss[row] = 0.f;
     return;
   }
-  float mx = -INFINITY;
-  for (int v = tid; v < a.V; v += HR_THREADS) mx = fmaxf(mx, z[v]);
-  mx = block_max(mx, red);
-  float se = 0.f;
-  for (int v = tid; v < a.V; v += HR_THREADS) se += __expf(z[v] - mx);
-  se = block_sum(se, red);
+  // One pass for the statistics: every thread keeps a running (max, sum of exp) pair over its elements
+  // and rescales the sum when its max moves; the pairs are then merged across the workgroup.
+  float mx = -INFINITY, se = 0.f;
+  const bool vec = (a.V & 3) == 0;
+  if (vec) {
+    const float4* z4 = (const float4*)z;
+    for (int v = tid; v < a.V / 4; v += HR_THREADS) {
+      const float4 t = z4[v];
+      const float m4 = fmaxf(fmaxf(t.x, t.y), fmaxf(t.z, t.w));
+      if (m4 > mx) { se *= __expf(mx - m4); mx = m4; }
+      se += __expf(t.x - mx) + __expf(t.y - mx) + __expf(t.z - mx) + __expf(t.w - mx);
+    }
+  } else {
+    for (int v = tid; v < a.V; v += HR_THREADS) {
+      const float t = z[v];
+      if (t > mx) { se *= __expf(mx - t); mx = t; }
+      se += __expf(t - mx);
+    }
+  }
+  {
+    const float gmx = block_max(mx, red);
+    se = block_sum(mx == -INFINITY ? 0.f : se * __expf(mx - gmx), red);
+    mx = gmx;
+  }
   const float lse = mx + logf(se);
   const float logp = z[tgt] - lse;
 
@@ -55,9 +80,25 @@ __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
     loss_term = sign * (logp - a.ref_logp[row]);   // summand of ell
   }
   if (tid == 0) a.row_loss[row] = loss_term;
-  for (int v = tid; v < a.V; v += HR_THREADS) {
-    const float sm = __expf(z[v] - lse);
-    stf(dz + v, coef * ((v == tgt ? 1.0f : 0.0f) - sm));
+  if (vec && sizeof(T) == 2) {
+    typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+    const float4* z4 = (const float4*)z;
+    bf16x4* dz4 = (bf16x4*)dz;
+    for (int v = tid; v < a.V / 4; v += HR_THREADS) {
+      const float4 t = z4[v];
+      const int v0 = v * 4;
+      bf16x4 o;
+      o[0] = (bf16_t)(coef * ((v0 + 0 == tgt ? 1.0f : 0.0f) - __expf(t.x - lse)));
+      o[1] = (bf16_t)(coef * ((v0 + 1 == tgt ? 1.0f : 0.0f) - __expf(t.y - lse)));
+      o[2] = (bf16_t)(coef * ((v0 + 2 == tgt ? 1.0f : 0.0f) - __expf(t.z - lse)));
+      o[3] = (bf16_t)(coef * ((v0 + 3 == tgt ? 1.0f : 0.0f) - __expf(t.w - lse)));
+      dz4[v] = o;
+    }
+  } else {
+    for (int v = tid; v < a.V; v += HR_THREADS) {
+      const float sm = __expf(z[v] - lse);
+      stf(dz + v, coef * ((v == tgt ? 1.0f : 0.0f) - sm));
+    }
   }
 }
 

@@ -1,0 +1,74 @@
+"""GPU parity of the layer-wise stack loop: embedding -> L layers (chunked forward fills the per-layer
+checkpoints) -> final RMSNorm -> LM head + SFT loss, then StreamBP backwards through head, norm, layers and
+the embedding, against the fp64 oracle composed the plain way (full-sequence backprop, no chunking)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import head as o_head
+from oracle import layer as o_layer
+from paper_2506_03077_amd import binding as sb
+from paper_2506_03077_amd import synth
+
+from gpu_util import TOL, assert_close, code, dev, host, lib_layer_cfg, oracle_cfg
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_stack(ids, emb, layers, g_final, w_head, targets, cfg, loss_scale):
+    x = emb.astype(np.float64)[ids]
+    caches = []
+    for w in layers:
+        x, cache = o_layer.layer_forward(x, w, oracle_cfg(cfg))
+        caches.append(cache)
+    h, r = o_layer.rmsnorm_forward(x, g_final, 1e-6)
+    hd = o_head.sft(h[None], w_head, targets[None], loss_scale)
+    dy, dg_final = o_layer.rmsnorm_backward(hd["dh"][0], x, g_final, r)
+    grads = []
+    for cache in reversed(caches):
+        dy, g = o_layer.layer_backward(cache, dy)
+        grads.append(g)
+    grads.reverse()
+    demb = np.zeros_like(emb, dtype=np.float64)
+    np.add.at(demb, ids, dy)
+    return dict(loss=hd["loss"], dlayers=grads, dg_final=dg_final, dw_head=hd["dw"], demb=demb, dx0=dy, y_last=x,
+                n_active=hd["n_active"])
+
+
+@pytest.mark.parametrize("name,L,T,chunk,head_chunk", [("tiny", 3, 256, 64, 100), ("mid16", 2, 300, 128, 128)])
+def test_stack_forward_backward(name, L, T, chunk, head_chunk):
+    cfg = dict(synth.CONFIGS["tiny"]) if name == "tiny" else dict(dtype="bf16", hidden=256, n_q_heads=4, n_kv_heads=2,
+                                                                  head_dim=128, mlp_width=512, vocab=1024)
+    dt = cfg["dtype"]
+    tok = synth.token_stream(cfg, seed=1, seq_len=T)
+    layers = [synth.layer_weights(cfg, seed=10 + l) for l in range(L)]
+    hin = synth.head_inputs(cfg, seed=3, seq_len=1, vocab=cfg["vocab"])
+    w_head = hin["w"]
+    g_final = synth.to_storage(1 + np.random.default_rng(5).normal(0, 0.02, cfg["hidden"]), dt)
+    emb = synth.to_storage(tok["emb"] * 50.0, dt)                # unit-scale inputs to the first layer
+    n_act = T - 1
+    ref = oracle_stack(tok["ids"], emb, layers, g_final, w_head, tok["targets"], cfg, 1.0 / n_act)
+
+    lw = [{k: dev(v, dt) for k, v in w.items()} for w in layers]
+    lc = lib_layer_cfg(cfg, T, chunk)
+    sc = sb.stack_cfg(lc, L, cfg["vocab"], head_chunk, sb.SBP_OBJ_SFT, 1.0 / n_act)
+    ckpt = [torch.empty((1, T, cfg["hidden"]), dtype=torch.bfloat16 if dt == "bf16" else torch.float32, device="cuda")
+            for _ in range(L + 1)]
+    ids = torch.from_numpy(tok["ids"]).cuda()
+    sb.streambp_stack_forward(sc, lw, ckpt, dev(emb, dt), ids)
+    out = sb.streambp_stack_backward(sc, lw, dev(g_final, dt), dev(w_head, dt), ckpt, torch.from_numpy(tok["targets"]).cuda(),
+                                     ids=ids)
+    torch.cuda.synchronize()
+    tol = TOL[dt]
+    ftol = tol if dt == "f32" else 1e-2
+    assert torch.equal(ckpt[0][0], dev(emb, dt)[ids.long()])                      # gather: exact
+    assert_close(host(ckpt[L])[0], ref["y_last"], ftol, "stack output")
+    assert int(out["n_active"].item()) == ref["n_active"] == n_act
+    assert abs(float(out["loss"].item()) - ref["loss"]) <= ftol * abs(ref["loss"])
+    assert_close(host(out["dw_head"]), ref["dw_head"], tol, "dw_head")
+    assert_close(host(out["dg_final"]), ref["dg_final"], tol, "dg_final")
+    assert_close(host(out["dx0"])[0], ref["dx0"], tol, "dx0")
+    assert_close(host(out["demb"]), ref["demb"], tol, "demb")
+    for l in range(L):
+        for n in sb.WEIGHT_NAMES:
+            assert_close(host(out["dlayers"][l][n]), ref["dlayers"][l][n], tol, f"layer {l} d{n}")
