@@ -312,7 +312,11 @@ static int32_t check_head_cfg(const sbp_head_cfg* c) {
   return SBP_OK;
 }
 
-struct HeadWs { float* z; void* dz; float *row_loss, *seq_weight, *ell; float* gemm_scratch; size_t gemm_scratch_bytes; size_t bytes; };
+struct HeadWs {
+  float* z; void* dz; float *row_loss, *seq_weight, *ell;
+  int32_t *index, *chunk_rows; void *hc, *dhc;   // active-row compaction: row list, rows per chunk, gathered h / dh rows
+  float* gemm_scratch; size_t gemm_scratch_bytes; size_t bytes;
+};
 static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   const int64_t rows = (int64_t)c->batch * c->seq_len;
   const size_t cm = (size_t)std::min<int64_t>(c->chunk, rows);
@@ -323,6 +327,10 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   h.row_loss = cv.take<float>(cm);
   h.seq_weight = cv.take<float>(c->batch);
   h.ell = cv.take<float>(1);
+  h.index = cv.take<int32_t>((size_t)rows);
+  h.chunk_rows = cv.take<int32_t>((size_t)cdiv(rows, (int64_t)cm));
+  h.hc = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
+  h.dhc = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
   h.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, c->hidden) : 0;
   h.gemm_scratch = (float*)cv.take_bytes(h.gemm_scratch_bytes);
   h.bytes = cv.off;
@@ -358,22 +366,37 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
 
   HIPCHK(count_active(targets, c->batch, c->seq_len, s.seq_weight, n_active, st));
   if (c->objective == SBP_OBJ_DPO) HIPCHK(fill_zero(s.ell, sizeof(float), st));
-  // Positions are independent (Sec. 3.2.1), so the B*T rows are chunked as one flat list.
-  for (int64_t r0 = 0; r0 < rows; r0 += cm) {
-    const int n = (int)std::min<int64_t>(cm, rows - r0);
-    const char* hc = at(h, (size_t)r0, d, es);
-    HIPCHK(gemm(fwd_gemm(hc, w, s.z, n, V, d, dt, DT_F32), st));
+  // Rows with an ignored target contribute nothing (dz = 0): only the active rows are pushed through the
+  // GEMMs.  Positions are independent (Sec. 3.2.1), so the active rows of all sequences are chunked as one
+  // flat list; the list and the per-chunk row counts live on the device (no host synchronisation), and the
+  // kernels of a chunk read their row count at run time.
+  const int n_chunks = (int)cdiv(rows, (int64_t)cm);
+  HIPCHK(compact_active(targets, rows, cm, s.index, s.chunk_rows, n_chunks, st));
+  HIPCHK(fill_zero(dh, (size_t)rows * d * es, st));          // ignored rows of dh: exact zeros
+  for (int ci = 0; ci < n_chunks; ++ci) {
+    const int32_t* idx = s.index + (size_t)ci * cm;
+    const int* n_dev = s.chunk_rows + ci;
+    const int n = (int)std::min<int64_t>(cm, rows - (int64_t)ci * cm);      // upper bound of the chunk's rows
+    HIPCHK(gather_rows(dt, h, idx, n_dev, s.hc, n, d, st));
+    GemmArgs gz = fwd_gemm(s.hc, w, s.z, n, V, d, dt, DT_F32);
+    gz.rows_dev = n_dev;
+    HIPCHK(gemm(gz, st));
     HeadRowArgs a{};
-    a.dt = dt; a.objective = c->objective; a.z = s.z; a.dz = s.dz; a.targets = targets + r0;
-    a.old_logp = old_logp ? old_logp + r0 : nullptr;
-    a.ref_logp = ref_logp ? ref_logp + r0 : nullptr;
-    a.advantages = advantages; a.seq_weight = s.seq_weight; a.row0 = r0; a.rows = n; a.V = V; a.T = c->seq_len;
+    a.dt = dt; a.objective = c->objective; a.z = s.z; a.dz = s.dz; a.targets = targets;
+    a.old_logp = old_logp; a.ref_logp = ref_logp;
+    a.advantages = advantages; a.seq_weight = s.seq_weight; a.row0 = 0; a.row_index = idx; a.rows_dev = n_dev;
+    a.rows = n; a.V = V; a.T = c->seq_len;
     a.loss_scale = c->loss_scale; a.clip_eps = c->clip_eps; a.kl_beta = c->kl_beta; a.kl_mode = c->kl_mode;
     a.row_loss = s.row_loss;
     HIPCHK(head_rows(a, st));
-    HIPCHK(reduce_add(s.row_loss, n, c->objective == SBP_OBJ_DPO ? s.ell : loss, st));
-    HIPCHK(gemm(dx_gemm(s.dz, w, at(dh, (size_t)r0, d, es), n, V, d, dt, dt, false), st));
-    HIPCHK(gemm(dw_gemm(s.dz, hc, dw, n, V, d, dt), st));
+    HIPCHK(reduce_add(s.row_loss, n, c->objective == SBP_OBJ_DPO ? s.ell : loss, st, n_dev));
+    GemmArgs gh = dx_gemm(s.dz, w, s.dhc, n, V, d, dt, dt, false);
+    gh.rows_dev = n_dev;
+    HIPCHK(gemm(gh, st));
+    HIPCHK(scatter_rows(dt, s.dhc, idx, n_dev, dh, n, d, st));
+    GemmArgs gw = dw_gemm(s.dz, s.hc, dw, n, V, d, dt);
+    gw.rows_dev = n_dev;
+    HIPCHK(gemm(gw, st));
   }
   if (c->objective == SBP_OBJ_DPO)
     HIPCHK(dpo_finish(dt, s.ell, c->kl_beta, dh, rows * d, dw, (int64_t)V * d, loss, st));

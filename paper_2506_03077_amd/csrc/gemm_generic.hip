@@ -12,7 +12,12 @@ constexpr int GK = 16;   // reduction slice
 template <typename TI, typename TO, bool ACC>
 __global__ __launch_bounds__(256) void gemm_generic_k(const TI* __restrict__ A, const TI* __restrict__ B,
                                                       TO* __restrict__ C, int M, int N, int K,
-                                                      int64_t lda, int64_t ldb, int64_t ldc, int ta, int tb) {
+                                                      int64_t lda, int64_t ldb, int64_t ldc, int ta, int tb,
+                                                      const int* __restrict__ rows_dev) {
+  if (rows_dev) {   // run-time row count (M for NT / NN, the reduction K for the dW form)
+    const int rows = max(0, *rows_dev);
+    if (ta) K = min(K, rows); else M = min(M, rows);
+  }
   __shared__ float As[GK][GT + 1];
   __shared__ float Bs[GK][GT + 1];
   const int tid = threadIdx.x;
@@ -68,7 +73,7 @@ hipError_t gemm_generic(const GemmArgs& g, hipStream_t st) {
   dim3 grid((unsigned)cdiv(g.N, GT), (unsigned)cdiv(g.M, GT));
 #define GG(TI, TO, ACC)                                                                                 \
   gemm_generic_k<TI, TO, ACC><<<grid, 256, 0, st>>>((const TI*)g.A, (const TI*)g.B, (TO*)g.C, g.M, g.N, g.K, \
-                                                    g.lda, g.ldb, g.ldc, g.ta ? 1 : 0, g.tb ? 1 : 0)
+                                                    g.lda, g.ldb, g.ldc, g.ta ? 1 : 0, g.tb ? 1 : 0, g.rows_dev)
   if (g.in_dt == DT_BF16) {
     if (g.out_dt == DT_BF16) GG(bf16_t, bf16_t, false);
     else if (g.acc) GG(bf16_t, float, true);

@@ -243,14 +243,21 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 template <bool TA, bool TB, int MODE>
 __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                         void* __restrict__ Cv, int M, int N, int K, int64_t lda,
-                                                        int64_t ldb, int64_t ldc, int k_per_split) {
+                                                        int64_t ldb, int64_t ldc, int k_per_split,
+                                                        const int* __restrict__ rows_dev) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   int tm, tn;
   band_coords(xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tm, tn);
+  if (MODE == 3) Cv = (float*)Cv + (int64_t)blockIdx.z * M * ldc;   // partial slices are laid out for the host-side M
+  if (rows_dev) {                     // run-time row count: rows are M (NT / NN) or the reduction K (dW form)
+    const int rows = max(0, *rows_dev);
+    if (TA) K = min(K, rows); else M = min(M, rows);
+    if (!TA && tm * BM >= M) return;  // no valid row in this tile
+  }
   const int k_begin = blockIdx.z * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
-  if (MODE == 3) Cv = (float*)Cv + (int64_t)blockIdx.z * M * ldc;
+  if (k_end <= k_begin && MODE == 2) return;   // nothing to add
   gemm_tile<TA, TB, MODE>(A, B, Cv, M, N, K, lda, ldb, ldc, k_begin, k_end, tm, tn, smem);
 }
 
@@ -322,7 +329,7 @@ constexpr int MAX_SPLITS = 4;
 int gemm_mfma_splits(const GemmArgs& g) {
   const int64_t tiles = cdiv(g.M, BM) * (g.N / BN);
   const int k_tiles = (int)cdiv(g.K, BK);
-  if (tiles >= 200 || k_tiles < 16) return 1;
+  if (tiles >= 200 || k_tiles < 16 || (g.ta && g.rows_dev)) return 1;
   int s = (int)std::min<int64_t>(256 / tiles, k_tiles / 8);   // largest split that still fits one round of 256 CUs
   return std::max(1, std::min(s, MAX_SPLITS));
 }
@@ -343,7 +350,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const bf16_t* A = (const bf16_t*)g.A;
   const bf16_t* B = (const bf16_t*)g.B;
 #define LAUNCH(TA, TB, MODE, CPTR) \
-  gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split)
+  gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split, g.rows_dev)
 #define LAUNCH_LAYOUT(MODE, CPTR)                       \
   do {                                                  \
     if (!g.ta && g.tb) LAUNCH(false, true, MODE, CPTR); \
@@ -375,7 +382,7 @@ bool gemm_mfma_group_eligible(const GemmArgs* gs, int n) {
   if (n < 2 || n > MAX_GROUP) return false;
   int64_t tiles = 0;
   for (int i = 0; i < n; ++i) {
-    if (!gemm_mfma_eligible(gs[i])) return false;
+    if (!gemm_mfma_eligible(gs[i]) || gs[i].rows_dev) return false;
     if (gs[i].ta != gs[0].ta || gs[i].tb != gs[0].tb || gs[i].out_dt != gs[0].out_dt || gs[i].acc != gs[0].acc) return false;
     tiles += cdiv(gs[i].M, BM) * (gs[i].N / BN);
   }

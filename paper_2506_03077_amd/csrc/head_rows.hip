@@ -14,9 +14,12 @@ template <typename T>
 __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
   __shared__ float red[16];
   const int row = blockIdx.x, tid = threadIdx.x;
+  if (a.rows_dev && row >= *a.rows_dev) return;                 // beyond the valid rows of a compacted chunk
   const float* z = a.z + (int64_t)row * a.V;
   T* dz = (T*)a.dz + (int64_t)row * a.V;
-  const int tgt = a.targets[row];
+  const int64_t orig = a.row_index ? (int64_t)a.row_index[row] : a.row0 + row;   // row in the caller's [B*T] order
+  const int64_t aux = a.row_index ? orig : (int64_t)row;        // index into targets / old_logp / ref_logp as passed
+  const int tgt = a.targets[aux];
   if (tgt < 0) {   // ignored row: exact zeros, no loss term
     const int64_t row_bytes = (int64_t)a.V * sizeof(T);
     if ((row_bytes & 15) == 0) {
@@ -60,24 +63,24 @@ __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
     coef = -a.loss_scale;
     loss_term = -a.loss_scale * logp;
   } else if (a.objective == 1) {              // GRPO
-    const int64_t seq = (a.row0 + row) / a.T;
+    const int64_t seq = orig / a.T;
     const float wgt = a.seq_weight[seq], adv = a.advantages[seq];
-    const float r = a.old_logp ? expf(logp - a.old_logp[row]) : 1.0f;
+    const float r = a.old_logp ? expf(logp - a.old_logp[aux]) : 1.0f;
     const float unclipped = r * adv;
     const float clipped = fminf(fmaxf(r, 1.0f - a.clip_eps), 1.0f + a.clip_eps) * adv;
     const float surr = fminf(unclipped, clipped);
     const float dsurr = (unclipped <= clipped) ? unclipped : 0.0f;
-    const float ref = a.ref_logp[row];
+    const float ref = a.ref_logp[aux];
     float kl, dkl;
     if (a.kl_mode == 0) { kl = logp - ref; dkl = 1.0f; }
     else { const float e = expf(ref - logp); kl = e - (ref - logp) - 1.0f; dkl = 1.0f - e; }
     loss_term = -wgt * (surr - a.kl_beta * kl);
     coef = -wgt * (dsurr - a.kl_beta * dkl);
   } else {                                    // DPO, before the final in-place correction
-    const int64_t seq = (a.row0 + row) / a.T;
+    const int64_t seq = orig / a.T;
     const float sign = (seq == 0) ? 1.0f : -1.0f;
     coef = a.kl_beta * sign;
-    loss_term = sign * (logp - a.ref_logp[row]);   // summand of ell
+    loss_term = sign * (logp - a.ref_logp[aux]);   // summand of ell
   }
   if (tid == 0) a.row_loss[row] = loss_term;
   if (vec && sizeof(T) == 2) {
@@ -110,16 +113,76 @@ hipError_t head_rows(const HeadRowArgs& a, hipStream_t st) {
 }
 
 // out += sum(v[0..n)) with a fixed summation tree (one workgroup).
-__global__ __launch_bounds__(256) void reduce_add_k(const float* __restrict__ v, int n, float* __restrict__ out) {
+__global__ __launch_bounds__(256) void reduce_add_k(const float* __restrict__ v, int n, float* __restrict__ out,
+                                                    const int* __restrict__ n_dev) {
   __shared__ float red[16];
+  if (n_dev) n = min(n, max(0, *n_dev));
   float s = 0.f;
   for (int i = threadIdx.x; i < n; i += 256) s += v[i];
   s = block_sum(s, red);
   if (threadIdx.x == 0) *out += s;
 }
-hipError_t reduce_add(const float* v, int n, float* out, hipStream_t st) {
+hipError_t reduce_add(const float* v, int n, float* out, hipStream_t st, const int* n_dev) {
   if (n == 0) return hipSuccess;
-  reduce_add_k<<<1, 256, 0, st>>>(v, n, out);
+  reduce_add_k<<<1, 256, 0, st>>>(v, n, out, n_dev);
+  return hipGetLastError();
+}
+
+// Stable compaction of the active rows (target >= 0) by one workgroup: per-thread counts over a contiguous
+// slice, an exclusive scan of the 1024 counts in LDS, then each thread writes its slice's indices in order.
+__global__ __launch_bounds__(1024) void compact_active_k(const int32_t* __restrict__ targets, int64_t rows, int chunk,
+                                                         int32_t* __restrict__ index, int32_t* __restrict__ chunk_rows,
+                                                         int n_chunks) {
+  __shared__ int cnt[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (rows + 1023) / 1024;
+  const int64_t b = min(rows, (int64_t)tid * per), e = min(rows, b + per);
+  int c = 0;
+  for (int64_t r = b; r < e; ++r) c += targets[r] >= 0 ? 1 : 0;
+  cnt[tid] = c;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {       // inclusive Hillis-Steele scan
+    const int v = tid >= off ? cnt[tid - off] : 0;
+    __syncthreads();
+    cnt[tid] += v;
+    __syncthreads();
+  }
+  int pos = cnt[tid] - c;
+  for (int64_t r = b; r < e; ++r)
+    if (targets[r] >= 0) index[pos++] = (int32_t)r;
+  const int total = cnt[1023];
+  for (int i = tid; i < n_chunks; i += 1024) chunk_rows[i] = min(chunk, max(0, total - i * chunk));
+}
+hipError_t compact_active(const int32_t* targets, int64_t rows, int chunk, int32_t* index, int32_t* chunk_rows, int n_chunks,
+                          hipStream_t st) {
+  compact_active_k<<<1, 1024, 0, st>>>(targets, rows, chunk, index, chunk_rows, n_chunks);
+  return hipGetLastError();
+}
+
+template <typename T, bool SCATTER>
+__global__ __launch_bounds__(256) void move_rows_k(const T* __restrict__ src, const int32_t* __restrict__ index,
+                                                   const int* __restrict__ rows_dev, T* __restrict__ dst, int d) {
+  const int r = blockIdx.x;
+  const bool valid = r < *rows_dev;
+  if (SCATTER) {
+    if (!valid) return;
+    const int64_t o = index[r];
+    for (int j = threadIdx.x; j < d; j += 256) dst[o * d + j] = src[(int64_t)r * d + j];
+  } else {
+    const int64_t o = valid ? index[r] : 0;
+    for (int j = threadIdx.x; j < d; j += 256) dst[(int64_t)r * d + j] = valid ? src[o * d + j] : (T)0.0f;
+  }
+}
+hipError_t gather_rows(int dt, const void* src, const int32_t* index, const int* rows_dev, void* dst, int max_rows, int d, hipStream_t st) {
+  if (max_rows == 0) return hipSuccess;
+  if (dt == DT_BF16) move_rows_k<bf16_t, false><<<max_rows, 256, 0, st>>>((const bf16_t*)src, index, rows_dev, (bf16_t*)dst, d);
+  else move_rows_k<float, false><<<max_rows, 256, 0, st>>>((const float*)src, index, rows_dev, (float*)dst, d);
+  return hipGetLastError();
+}
+hipError_t scatter_rows(int dt, const void* src, const int32_t* index, const int* rows_dev, void* dst, int max_rows, int d, hipStream_t st) {
+  if (max_rows == 0) return hipSuccess;
+  if (dt == DT_BF16) move_rows_k<bf16_t, true><<<max_rows, 256, 0, st>>>((const bf16_t*)src, index, rows_dev, (bf16_t*)dst, d);
+  else move_rows_k<float, true><<<max_rows, 256, 0, st>>>((const float*)src, index, rows_dev, (float*)dst, d);
   return hipGetLastError();
 }
 

@@ -19,6 +19,10 @@ struct GemmArgs {
   bool acc;
   float* scratch = nullptr;      // optional fp32 scratch for split-K partial tiles
   size_t scratch_bytes = 0;
+  // Optional device-side count of valid "rows" (the M dimension of NT / NN problems, the K dimension of the
+  // dW form): the kernels read it at run time and skip the work beyond it; the host-side M (resp. K) is the
+  // upper bound the launch is sized for.
+  const int* rows_dev = nullptr;
 };
 // upper bound of the scratch a GEMM with M <= max_m rows and N <= max_n columns may use
 size_t gemm_scratch_bytes(int max_m, int max_n);
@@ -92,15 +96,24 @@ struct HeadRowArgs {
   const float* advantages;  // [B] or NULL
   const float* seq_weight;  // [B] GRPO: 1/(B*T_o,j); NULL otherwise
   int64_t row0;             // global row index of the chunk's first row (row / T = sequence)
+  const int32_t* row_index; // optional: original row of each chunk row (compacted chunks); then targets / old_logp /
+                            // ref_logp are indexed by it and row0 is ignored
+  const int* rows_dev;      // optional device-side count of valid chunk rows (<= rows)
   int rows, V, T;
   float loss_scale, clip_eps, kl_beta; int kl_mode;
   float* row_loss;          // [rows] scratch: per-row loss term (DPO: per-row signed log-ratio)
 };
 hipError_t head_rows(const HeadRowArgs& a, hipStream_t st);
 // loss += sum(row_loss[0..rows)) in a fixed order
-hipError_t reduce_add(const float* v, int n, float* out, hipStream_t st);
+hipError_t reduce_add(const float* v, int n, float* out, hipStream_t st, const int* n_dev = nullptr);
 // per-sequence active counts -> seq_weight[j] = 1/(B*T_o,j) (0 if empty), n_active total
 hipError_t count_active(const int32_t* targets, int B, int T, float* seq_weight, int64_t* n_active, hipStream_t st);
+// index[0..n_active) = rows with target >= 0 in increasing order; chunk_rows[i] = clamp(n_active - i*chunk, 0, chunk)
+hipError_t compact_active(const int32_t* targets, int64_t rows, int chunk, int32_t* index, int32_t* chunk_rows, int n_chunks,
+                          hipStream_t st);
+// dst[r,:] = src[index[r],:] for r < *rows_dev, zero rows after;  scatter: dst[index[r],:] = src[r,:] for r < *rows_dev
+hipError_t gather_rows(int dt, const void* src, const int32_t* index, const int* rows_dev, void* dst, int max_rows, int d, hipStream_t st);
+hipError_t scatter_rows(int dt, const void* src, const int32_t* index, const int* rows_dev, void* dst, int max_rows, int d, hipStream_t st);
 // DPO fix-up: factor = sigmoid(beta*ell)-1 ; scales dh (dt) and dw (fp32) in place, loss += -log sigmoid(beta*ell)
 hipError_t dpo_finish(int dt, const float* ell, float beta, void* dh, int64_t n_dh, float* dw, int64_t n_dw,
                       float* loss, hipStream_t st);
