@@ -22,12 +22,13 @@
 //            buffered); online softmax in the exp2 domain.
 //  dQ      : same decomposition; recomputes P from the saved log-sum-exp;
 //            dQ^T += K^T dS^T.
-//  dK/dV   : workgroup = 128 keys of one KV head, 4 waves x 32 keys with K and V
-//            fragments resident in registers; loops over the query tiles at or
-//            below the diagonal and over the query heads of the group, Q and dO
-//            tiles of 64 queries stream through LDS; dV^T += dO^T P,
-//            dK^T += Q^T dS; results are added to the fp32 prefix accumulators
-//            (every element has one owner: no atomics, reproducible).
+//  dK/dV   : workgroup = 128 keys of one KV head, 4 key blocks x 2 roles: one wave of
+//            a block computes P and dV^T += dO^T P, its partner dP, dS and
+//            dK^T += Q^T dS (P crosses through LDS); loops over the query tiles at
+//            or below the diagonal and over the query heads of the group, Q and dO
+//            tiles of 64 queries stream through LDS; results are added to the fp32
+//            prefix accumulators (every element has one owner: no atomics,
+//            reproducible).
 #include "launch.h"
 
 #include <algorithm>
@@ -47,8 +48,8 @@ constexpr int ROW_BYTES = DH * 2;        // 256 B per tile row
 constexpr int AT_THREADS = 256;          // 4 waves
 constexpr int TQ = ATTN_TILE_Q;          // 128 queries per workgroup (fwd, dQ)
 constexpr int TK = ATTN_TILE_K;          // 64 keys per step (fwd, dQ)
-constexpr int KV_TILE = 128;             // keys per workgroup (dK/dV): 4 waves x 32 keys
-constexpr int KV_THREADS = 256;
+constexpr int KV_TILE = 128;             // keys per workgroup (dK/dV): 4 key blocks x 2 roles = 8 waves
+constexpr int KV_THREADS = 512;
 constexpr int QT = 64;                   // queries per step (dK/dV)
 constexpr int TILE64_BYTES = 64 * ROW_BYTES;   // 16 KiB
 constexpr float LOG2E = 1.4426950408889634f;
@@ -351,45 +352,49 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_bwd_dq_mfma_k(const bf16_t
 }
 
 // -------------------------------------------------------------------- dK/dV --
-__global__ __launch_bounds__(KV_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                                     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
-                                                                     const float* __restrict__ lse, const float* __restrict__ delta,
-                                                                     float* __restrict__ dk, float* __restrict__ dv, int Hq, int Hkv,
-                                                                     int q_start, int c, float scale) {
+// Workgroup = 128 keys of one KV head, 8 waves = 4 key blocks of 32 x 2 roles, so that each SIMD holds the two
+// waves of one key block:
+//   role P (waves 0-3): S = Q K^T -> P = exp2(S*sl - lse) (masked) -> hands P to its partner through LDS
+//                       -> dV^T += dO^T P
+//   role S (waves 4-7): dP = dO V^T -> takes P -> dS = P * (dP - delta) -> dK^T += Q^T dS
+// Each role keeps only its own operand fragments (K or V) and its own accumulator (dV or dK) in registers:
+// half the registers of a do-everything wave, so two waves fit per SIMD and the softmax arithmetic of one
+// overlaps the MFMAs of the other.  P is exchanged in fp32 (one 4 KiB slot per key block and query block).
+// The loop walks the query tiles at or below the diagonal and, for each, the query heads of the group.
+__global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                                  const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
+                                                                  const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                  float* __restrict__ dk, float* __restrict__ dv, int Hq, int Hkv,
+                                                                  int q_start, int c, float scale) {
   __shared__ __attribute__((aligned(1024))) char sQ0[TILE64_BYTES];
   __shared__ __attribute__((aligned(1024))) char sD0[TILE64_BYTES];
   __shared__ __attribute__((aligned(1024))) char sQ1[TILE64_BYTES];
   __shared__ __attribute__((aligned(1024))) char sD1[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sV[KV_TILE / 64][TILE64_BYTES];   // V rows of the workgroup's keys
-  __shared__ __attribute__((aligned(16))) float sL[2][QT];     // log-sum-exp of the tile's queries
-  __shared__ __attribute__((aligned(16))) float sDl[2][QT];    // delta of the tile's queries
+  __shared__ __attribute__((aligned(16))) float sP[4][2][64 * 16];   // [key block][query block][lane * 16 + r]
+  __shared__ __attribute__((aligned(16))) float sL[2][QT];           // log-sum-exp of the tile's queries
+  __shared__ __attribute__((aligned(16))) float sDl[2][QT];          // delta of the tile's queries
 
   const int G = Hq / Hkv;
   const int key0 = blockIdx.x * KV_TILE, kvh = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
+  const int kb = wave & 3;
+  const bool role_p = wave < 4;
   const int n_total = q_start + c;
-  const int kw0 = key0 + wave * 32;
+  const int kw0 = key0 + kb * 32;
   const int my_key = kw0 + (lane & 31);
   const int key_row = min(my_key, n_total - 1);
   const int64_t kv_stride = (int64_t)Hkv * DH;
   const int64_t q_stride = (int64_t)Hq * DH;
 
-  // K fragments of the wave's 32 keys stay in registers; the V fragments are re-read from LDS (keeping both
-  // resident costs more registers than the kernel has).
-  bf16x8 bk[8];
+  bf16x8 breg[8];   // B operand of the first product: K rows (role P) or V rows (role S) of my key
   {
-    const int64_t off = (int64_t)key_row * kv_stride + (int64_t)kvh * DH + half * 8;
+    const bf16_t* src = (role_p ? k : v) + (int64_t)key_row * kv_stride + (int64_t)kvh * DH + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) bk[ks] = *(const bf16x8*)(k + off + ks * 16);
+    for (int ks = 0; ks < 8; ++ks) breg[ks] = *(const bf16x8*)(src + ks * 16);
   }
+  f32x16 acc[4];   // dV^T (role P) or dK^T (role S): rows = head_dim, column = my key
 #pragma unroll
-  for (int t = 0; t < KV_TILE / 64; ++t)      // landed by the first wait + barrier of the main loop
-    dma_tile64<KV_THREADS>(v + (int64_t)kvh * DH, kv_stride, key0 + 64 * t, n_total - 1, sV[t]);
-  const char* sVw = sV[wave >> 1];
-  const int v_row0 = (wave & 1) * 32;
-  f32x16 acc_k[4], acc_v[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) { acc_k[i] = zero16(); acc_v[i] = zero16(); }
+  for (int i = 0; i < 4; ++i) acc[i] = zero16();
   const float sl = scale * LOG2E;
 
   // query tiles that can see at least one key of this workgroup: query position >= key0
@@ -407,47 +412,78 @@ __global__ __launch_bounds__(KV_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
       __builtin_amdgcn_global_load_lds(src, LDS_AS(wave == 0 ? &sL[buf][0] : &sDl[buf][0]), 4, 0, 0);
     }
   };
+  // One 64-query tile = two 32-query blocks.  Both roles execute the same two barriers per tile.
   auto step = [&](int it, const char* sQ, const char* sD, int buf) {
     const int qt = qt_first + it / G;
     const int qbase = qt * QT;
-    if (kw0 >= n_total) return;                                   // wave has no valid key
-    if (q_start + min(qbase + QT, c) - 1 < kw0) return;           // every query of the tile precedes the wave's keys
+    // nothing to do for this wave: no valid key, or every query of the tile precedes the wave's keys
+    const bool active = kw0 < n_total && q_start + min(qbase + QT, c) - 1 >= kw0;
     const bool diag = (q_start + qbase < kw0 + 31) || (qbase + QT > c);   // some pair masked, or ragged query tile
+    f32x16 t[2];   // role P: probabilities of the two blocks; role S: dP of the two blocks
+    if (active) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      f32x16 s = zero16(), dp = zero16();
+      for (int b = 0; b < 2; ++b) {
+        t[b] = zero16();
+        const char* src = role_p ? sQ : sD;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) s = MFMA(frag_rows(sQ, b * 32, ks), bk[ks], s);
+        for (int ks = 0; ks < 8; ++ks) t[b] = MFMA(frag_rows(src, b * 32, ks), breg[ks], t[b]);
+      }
+      if (role_p) {
+        // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) dp = MFMA(frag_rows(sD, b * 32, ks), frag_rows(sVw, v_row0, ks), dp);
-      // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
-      if (diag) {
+        for (int b = 0; b < 2; ++b) {
+          if (diag) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qi = qbase + b * 32 + acc_row(r, half);
-          if (qi >= c || my_key > q_start + qi) s[r] = -INFINITY;          // exp2(-inf) = 0
+            for (int r = 0; r < 16; ++r) {
+              const int qi = qbase + b * 32 + acc_row(r, half);
+              if (qi >= c || my_key > q_start + qi) t[b][r] = -INFINITY;      // exp2(-inf) = 0
+            }
+          }
+#pragma unroll
+          for (int a = 0; a < 4; ++a) {
+            const float4 l4 = *(const float4*)&sL[buf][b * 32 + 8 * a + 4 * half];
+            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+            float4 p4;
+            float* pp = (float*)&p4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(t[b][4 * a + e], sl, -lv[e] * LOG2E));
+              t[b][4 * a + e] = p;
+              pp[e] = p;
+            }
+            *(float4*)&sP[kb][b][(a * 64 + lane) * 4] = p4;     // slot layout [a][lane][e]: conflict-free
+          }
         }
       }
+    }
+    __syncthreads();   // P of both blocks is visible to the partner
+    if (active) {
+      if (role_p) {
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const float4 l4 = *(const float4*)&sL[buf][b * 32 + 8 * a + 4 * half];
-        const float4 d4 = *(const float4*)&sDl[buf][b * 32 + 8 * a + 4 * half];
-        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * a + e;
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sl, -lv[e] * LOG2E));
-          s[r] = p;
-          dp[r] = p * (dp[r] - dl[e]);
-        }
-      }
+          for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 pb = pack8(t[b], ks);
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 pb = pack8(s, ks), db = pack8(dp, ks);
+            for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sD, b * 32 + ks * 16, i * 32), pb, acc[i]);
+          }
+      } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          acc_v[i] = MFMA(frag_cols_tr(sD, b * 32 + ks * 16, i * 32), pb, acc_v[i]);
-          acc_k[i] = MFMA(frag_cols_tr(sQ, b * 32 + ks * 16, i * 32), db, acc_k[i]);
+        for (int b = 0; b < 2; ++b) {
+#pragma unroll
+          for (int a = 0; a < 4; ++a) {
+            const float4 p4 = *(const float4*)&sP[kb][b][(a * 64 + lane) * 4];
+            const float4 d4 = *(const float4*)&sDl[buf][b * 32 + 8 * a + 4 * half];
+            const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[b][4 * a + e] = pv[e] * (t[b][4 * a + e] - dl[e]);   // dS (scale applied at the end)
+          }
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 db = pack8(t[b], ks);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sQ, b * 32 + ks * 16, i * 32), db, acc[i]);
+          }
         }
       }
     }
@@ -456,7 +492,7 @@ __global__ __launch_bounds__(KV_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
   if (n_iter > 0) issue(0, sQ0, sD0, 0);
   for (int it = 0; it < n_iter; it += 2) {
     WAIT_VM0();
-    __syncthreads();
+    __syncthreads();    // tile `it` has landed for everyone; everyone is done with the other buffers and with sP
     if (it + 1 < n_iter) issue(it + 1, sQ1, sD1, 1);
     step(it, sQ0, sD0, 0);
     if (it + 1 < n_iter) {
@@ -468,20 +504,16 @@ __global__ __launch_bounds__(KV_THREADS, 1) void attn_bwd_dkv_mfma_k(const bf16_
   }
 
   if (my_key < n_total) {
-    float* kp = dk + (int64_t)my_key * kv_stride + (int64_t)kvh * DH;
-    float* vp = dv + (int64_t)my_key * kv_stride + (int64_t)kvh * DH;
+    float* out = (role_p ? dv : dk) + (int64_t)my_key * kv_stride + (int64_t)kvh * DH;
+    const float f = role_p ? 1.0f : scale;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         const int d0 = i * 32 + 8 * a + 4 * half;
-        float4 t = *(float4*)(kp + d0);
-        t.x += acc_k[i][4 * a + 0] * scale; t.y += acc_k[i][4 * a + 1] * scale;
-        t.z += acc_k[i][4 * a + 2] * scale; t.w += acc_k[i][4 * a + 3] * scale;
-        *(float4*)(kp + d0) = t;
-        float4 u = *(float4*)(vp + d0);
-        u.x += acc_v[i][4 * a + 0]; u.y += acc_v[i][4 * a + 1]; u.z += acc_v[i][4 * a + 2]; u.w += acc_v[i][4 * a + 3];
-        *(float4*)(vp + d0) = u;
+        float4 u = *(float4*)(out + d0);
+        u.x += acc[i][4 * a + 0] * f; u.y += acc[i][4 * a + 1] * f; u.z += acc[i][4 * a + 2] * f; u.w += acc[i][4 * a + 3] * f;
+        *(float4*)(out + d0) = u;
       }
   }
 }
