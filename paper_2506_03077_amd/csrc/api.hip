@@ -454,12 +454,13 @@ int32_t streambp_attn_chunk_backward(const sbp_attn_cfg* c, const void* q, const
 }
 
 int64_t streambp_attn_tile_pairs(int32_t q_start, int32_t q_len, int32_t* tile_q, int32_t* tile_k) {
-  if (tile_q) *tile_q = ATTN_TILE_Q;
+  // Work is skipped per wave: a wave owns ATTN_WAVE_Q query rows and walks key tiles of ATTN_TILE_K.
+  if (tile_q) *tile_q = ATTN_WAVE_Q;
   if (tile_k) *tile_k = ATTN_TILE_K;
   if (q_start < 0 || q_len <= 0) return 0;
   int64_t pairs = 0;
-  for (int64_t t0 = 0; t0 < q_len; t0 += ATTN_TILE_Q) {
-    const int64_t last_q = q_start + std::min<int64_t>(t0 + ATTN_TILE_Q, q_len) - 1;   // last query position of the tile
+  for (int64_t t0 = 0; t0 < q_len; t0 += ATTN_WAVE_Q) {
+    const int64_t last_q = q_start + std::min<int64_t>(t0 + ATTN_WAVE_Q, q_len) - 1;   // last query position of the wave
     pairs += last_q / ATTN_TILE_K + 1;                                                 // key tiles that start at or before it
   }
   return pairs;

@@ -17,7 +17,7 @@
 // LDS load (ds_read_b64_tr_b16) that fetches V^T / K^T / Q^T / dO^T fragments
 // from tiles kept in their natural [row][head_dim] layout.
 //
-//  forward : workgroup = 128 queries of one query head, 4 waves x 32 queries;
+//  forward : workgroup = 256 queries of one query head, 8 waves x 32 queries;
 //            K and V tiles of 64 keys stream HBM -> LDS (direct-to-LDS, double
 //            buffered); online softmax in the exp2 domain.
 //  dQ      : same decomposition; recomputes P from the saved log-sum-exp;
@@ -45,7 +45,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int DH = 128;                  // head_dim of the MFMA path
 constexpr int ROW_BYTES = DH * 2;        // 256 B per tile row
-constexpr int AT_THREADS = 256;          // 4 waves
+constexpr int AT_THREADS = 512;          // 8 waves (forward, dQ): 2 per SIMD
 constexpr int TQ = ATTN_TILE_Q;          // 128 queries per workgroup (fwd, dQ)
 constexpr int TK = ATTN_TILE_K;          // 64 keys per step (fwd, dQ)
 constexpr int KV_TILE = 128;             // keys per workgroup (dK/dV): 4 key blocks x 2 roles = 8 waves
@@ -121,7 +121,7 @@ __device__ __forceinline__ f32x16 zero16() {
 __device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
 // ------------------------------------------------------------------ forward --
-__global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                                  const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                                  float* __restrict__ lse, int Hq, int Hkv, int q_start,
                                                                  int c, float scale) {
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_mfma_k(const bf16_t* _
 }
 
 // ----------------------------------------------------------------------- dQ --
-__global__ __launch_bounds__(AT_THREADS, 2) void attn_bwd_dq_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                                     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
                                                                     const float* __restrict__ lse, const float* __restrict__ delta,
                                                                     bf16_t* __restrict__ dq, int Hq, int Hkv, int q_start, int c,

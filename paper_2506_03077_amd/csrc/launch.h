@@ -81,7 +81,8 @@ hipError_t attn_forward(const AttnArgs& a, hipStream_t st);
 hipError_t attn_backward(const AttnArgs& a, hipStream_t st);
 bool attn_uses_mfma(int dt, int dh, int Hq, int Hkv);
 void attn_set_force_generic(bool on);
-constexpr int ATTN_TILE_Q = 128;   // rows of queries per workgroup in the MFMA kernels
+constexpr int ATTN_TILE_Q = 256;   // rows of queries per workgroup in the MFMA kernels (8 waves x 32 rows)
+constexpr int ATTN_WAVE_Q = 32;    // rows of queries per wave: the granularity at which key tiles are skipped
 constexpr int ATTN_TILE_K = 64;    // keys per inner step
 
 // ---- LM head rows ----
