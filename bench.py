@@ -23,6 +23,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16 MFMA); vendor figure ~2.5 PF
 PEAK_HBM_GBS = 8000.0
+# HBM-side bytes per launch of the dominant kernel, measured with two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, WRITE_SIZE, scaled by a 1 GiB copy-like kernel: profiles/bench_7b_layer_lmhead_32k_hbm_traffic.txt).
+# It cannot be read inside the timed process, so the last measured figure is recorded here.
+MEASURED_TRAFFIC = {"gemm_mfma_k<false, false, 3>": 1.099e9}
 
 
 def algorithmic_flops(cfg, T, active_rows):
@@ -54,7 +58,7 @@ def cpu_baseline(cfg, seconds_hint=20.0):
     from oracle import head as o_head
     from oracle import layer as o_layer
     from paper_2506_03077_amd import synth
-    T_s, R_s = 2048, 768
+    T_s, R_s = 4096, 1536
     lc = dict(cfg, dtype="bf16")
     inp = synth.layer_inputs(lc, seed=0, seq_len=T_s, batch=1)
     ocfg = dict(n_q_heads=cfg["n_q_heads"], n_kv_heads=cfg["n_kv_heads"], head_dim=cfg["head_dim"])
@@ -82,6 +86,11 @@ def main():
     ap.add_argument("--head-chunk", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (reference for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc runs (goes into roofline.traffic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -142,6 +151,13 @@ def main():
         # the head's dH is the upstream gradient of the layer (the final norm is left out of the timed step)
         sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
 
+    if args.pmc_calibrate:   # 2^28 fp32 elements: the add kernel fetches 1 GiB and writes 1 GiB
+        ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        cb = torch.empty_like(ca)
+        torch.add(ca, 1.0, out=cb)
+        torch.cuda.synchronize()
+        del ca, cb
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -171,28 +187,32 @@ def main():
                    "torch_max_memory_allocated": int(torch.cuda.max_memory_allocated())},
     }
 
-    # ---- roofline of the dominant kernel (weight-gradient GEMM, TN form), durations from HIP events recorded
-    # around every launch on the launch stream during one more pass over the same workload.
+    # ---- roofline of the dominant kernel (largest total time), durations from HIP events recorded on the
+    # launch stream around every launch during one more pass over the same workload.
     if not args.no_profile:
         sb.debug_profile_begin(20000)
         step()
         torch.cuda.synchronize()
         prof = sb.debug_profile_end()
-        # Algorithmic flops per family are analytic (the dispatcher cannot know how many rows a chunk of the
-        # head really had: that count lives on the device): each GEMM family does 2*P*T of the layer's linear
-        # work plus 2*d*V*n_active of the head's; attention 4*dh (forward) / 10*dh (backward) per causal pair.
-        fam = {"gemm_nt": fl["gemm_family"], "gemm_nn": fl["gemm_family"], "gemm_tn": fl["gemm_family"],
-               "attn_fwd": fl["attention"] * 4.0 / 14.0, "attn_bwd": fl["attention"] * 10.0 / 14.0}
-        per_kind = {k: dict(launches=v["count"], ms=v["ms"], tflops=(fam[k] / v["ms"] / 1e9 if k in fam else None))
-                    for k, v in prof.items() if v["count"]}
-        dom = max((k for k in prof if prof[k]["count"] and k in fam), key=lambda k: prof[k]["ms"])
-        pv = prof[dom]
-        achieved = fam[dom] / pv["ms"] / 1e9
-        out["roofline"] = {"bound": "mfma", "kernel": dom, "launches_per_step": pv["count"],
-                           "avg_launch_ms": pv["ms"] / pv["count"], "avg_launch_tflop": fam[dom] / pv["count"] / 1e12,
-                           "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
-        out["config"]["per_kernel_family"] = per_kind
+        # Flops per kernel: 2MNK summed over its launches.  For the LM-head GEMMs the row count of a chunk lives
+        # on the device (ignored rows are compacted away), so the library reports their work from the host-side
+        # upper bound separately; the real row total is n_active of B*T rows, hence the factor below.
+        active_frac = n_act / float(T)
+        per_kernel = {}
+        for kname, v in prof.items():
+            if not v["count"]:
+                continue
+            fl_k = v["flops"] + v["flops_bounded"] * active_frac
+            per_kernel[kname] = dict(launches=v["count"], ms=v["ms"], avg_launch_ms=v["ms"] / v["count"],
+                                     tflops=fl_k / v["ms"] / 1e9, tflop=fl_k / 1e12)
+        dom = max(per_kernel, key=lambda kname: per_kernel[kname]["ms"])
+        pk = per_kernel[dom]
+        out["roofline"] = {"bound": "mfma", "kernel": dom, "launches_per_step": pk["launches"],
+                           "avg_launch_ms": pk["avg_launch_ms"], "avg_launch_tflop": pk["tflop"] / pk["launches"],
+                           "achieved": pk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": pk["tflops"] / PEAK_BF16_TFLOPS,
+                           "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC.get(dom)}
+        out["config"]["per_kernel"] = per_kernel
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

@@ -113,7 +113,9 @@ def lib():
         L.streambp_debug_profile_begin.restype = C.c_int
         L.streambp_debug_profile_begin.argtypes = [C.c_int]
         L.streambp_debug_profile_end.restype = C.c_int
-        L.streambp_debug_profile_end.argtypes = [C.POINTER(C.c_longlong), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.streambp_debug_profile_end.argtypes = [C.POINTER(C.c_longlong), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                                 C.POINTER(C.c_double)]
+        L.streambp_debug_profile_kinds.restype = C.c_int
         _lib = L
     return _lib
 
@@ -337,24 +339,36 @@ def debug_gemm(A, B, C_out, M, N, K, ta, tb, acc=False, scratch=None, stream=Non
     return rc
 
 
-PROFILE_KINDS = ("gemm_nt", "gemm_nn", "gemm_tn", "gemm_generic", "attn_fwd", "attn_bwd")
+def _profile_kind_names():
+    lay = (("false, true", "NT"), ("false, false", "NN"), ("true, false", "TN"))
+    names = [f"gemm_mfma_k<{t}, {m}>" for t, _ in lay for m in range(4)]
+    names += [f"gemm_mfma_group_k<{t}, {m}>" for t, _ in lay for m in range(4)]
+    names += ["gemm_generic_k", "attn_fwd (launch sequence)", "attn_bwd (delta + dq + dkv launch sequence)"]
+    return tuple(names)
+
+
+PROFILE_KINDS = _profile_kind_names()   # GEMM entries are the kernel symbols rocprofv3 reports (sbp:: prefix dropped)
 
 
 def debug_profile_begin(max_records=100000):
-    """Start per-launch HIP-event timing of the GEMM / attention dispatchers (events are created here)."""
+    """Start per-launch HIP-event timing of the GEMM kernels / attention launch sequences (events are created here)."""
     rc = lib().streambp_debug_profile_begin(max_records)
     if rc != 0:
         raise StreamBPError(rc, "profile_begin failed")
 
 
 def debug_profile_end():
-    """Stop timing; returns {kind: dict(count, ms, flops)} summed over the launches since begin."""
+    """Stop timing; returns {kind: dict(count, ms, flops, flops_bounded)} summed over the launches since begin.
+    flops_bounded is the work of launches whose row count was only known on the device, computed from the host-side
+    upper bound (scale it by the fraction of rows that were really there)."""
     n = len(PROFILE_KINDS)
-    cnt, ms, work = (C.c_longlong * n)(), (C.c_double * n)(), (C.c_double * n)()
-    rc = lib().streambp_debug_profile_end(cnt, ms, work)
+    assert n == lib().streambp_debug_profile_kinds()
+    cnt, ms, work, wb = (C.c_longlong * n)(), (C.c_double * n)(), (C.c_double * n)(), (C.c_double * n)()
+    rc = lib().streambp_debug_profile_end(cnt, ms, work, wb)
     if rc != 0:
         raise StreamBPError(rc, "profile_end failed")
-    return {k: dict(count=int(cnt[i]), ms=float(ms[i]), flops=float(work[i])) for i, k in enumerate(PROFILE_KINDS)}
+    return {k: dict(count=int(cnt[i]), ms=float(ms[i]), flops=float(work[i]), flops_bounded=float(wb[i]))
+            for i, k in enumerate(PROFILE_KINDS)}
 
 
 def stack_cfg(layer: LayerCfg, n_layers, vocab, head_chunk, objective=SBP_OBJ_SFT, loss_scale=1.0, clip_eps=0.2,
@@ -409,3 +423,11 @@ def streambp_stack_backward(cfg: StackCfg, layers, g_final, w_head, ckpt, target
                                          _ptr(dg_final), _ptr(dw_head), _ptr(demb), _ptr(dx0), _ptr(loss), _ptr(n_active),
                                          _ptr(workspace), workspace.numel(), _stream(stream)))
     return dict(dlayers=dlayers, dg_final=dg_final, dw_head=dw_head, demb=demb, dx0=dx0, loss=loss, n_active=n_active)
+
+
+def streambp_rmsnorm_workspace_bytes(n_rows, hidden) -> int:
+    return int(lib().streambp_rmsnorm_workspace_bytes(n_rows, hidden))
+
+
+def streambp_last_error():
+    return lib().streambp_last_error().decode()

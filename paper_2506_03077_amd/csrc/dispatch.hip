@@ -29,24 +29,20 @@ bool attn_uses_mfma(int dt, int dh, int Hq, int Hkv) { return !g_force_generic_a
 // ---- optional per-launch timing (off by default; events are created when profiling is switched on,
 // never inside an entry point) -------------------------------------------------------------------
 namespace prof {
-enum Kind { GEMM_NT = 0, GEMM_NN, GEMM_TN, GEMM_GENERIC, ATTN_FWD, ATTN_BWD, N_KIND };
-struct Rec { int kind; double work; hipEvent_t e0, e1; };
+struct Rec { int kind; double work; bool bounded; hipEvent_t e0, e1; };
 static bool g_on = false;
 static std::vector<hipEvent_t> g_pool;
 static std::vector<Rec> g_recs;
 static size_t g_next = 0;
 
-struct Scope {
-  hipStream_t st; bool active = false; Rec rec{};
-  Scope(int kind, double work, hipStream_t s) : st(s) {
-    if (!g_on || g_next + 2 > g_pool.size()) return;
-    rec.kind = kind; rec.work = work; rec.e0 = g_pool[g_next++]; rec.e1 = g_pool[g_next++];
-    active = hipEventRecord(rec.e0, st) == hipSuccess;
-  }
-  ~Scope() {
-    if (active && hipEventRecord(rec.e1, st) == hipSuccess) g_recs.push_back(rec);
-  }
-};
+Scope::Scope(int kind_, double work_, bool bounded_, hipStream_t s) : st(s), kind(kind_), work(work_), bounded(bounded_) {
+  if (!g_on || g_next + 2 > g_pool.size()) return;
+  e0 = g_pool[g_next++]; e1 = g_pool[g_next++];
+  active = hipEventRecord(e0, st) == hipSuccess;
+}
+Scope::~Scope() {
+  if (active && hipEventRecord(e1, st) == hipSuccess) g_recs.push_back(Rec{kind, work, bounded, e0, e1});
+}
 }  // namespace prof
 
 static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs of the chunk, all query heads
@@ -55,17 +51,12 @@ static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs 
 }
 
 hipError_t gemm(const GemmArgs& g, hipStream_t st) {
-  const bool mfma = gemm_uses_mfma(g);
-  const int kind = !mfma ? prof::GEMM_GENERIC : (g.ta ? prof::GEMM_TN : (g.tb ? prof::GEMM_NT : prof::GEMM_NN));
-  prof::Scope sc(kind, 2.0 * g.M * g.N * g.K, st);
-  return mfma ? gemm_mfma(g, st) : gemm_generic(g, st);
+  if (gemm_uses_mfma(g)) return gemm_mfma(g, st);      // times itself (it knows which kernel variant it launches)
+  prof::Scope sc(prof::GEMM_GENERIC, 2.0 * g.M * g.N * g.K, g.rows_dev != nullptr, st);
+  return gemm_generic(g, st);
 }
 hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st) {
   if (!g_force_generic_gemm && gemm_mfma_group_eligible(gs, n)) {
-    double work = 0.0;
-    for (int i = 0; i < n; ++i) work += 2.0 * gs[i].M * gs[i].N * gs[i].K;
-    const int kind = gs[0].ta ? prof::GEMM_TN : (gs[0].tb ? prof::GEMM_NT : prof::GEMM_NN);
-    prof::Scope sc(kind, work, st);
     return gemm_mfma_group(gs, n, st);
   }
   for (int i = 0; i < n; ++i) {
@@ -75,11 +66,11 @@ hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st) {
   return hipSuccess;
 }
 hipError_t attn_forward(const AttnArgs& a, hipStream_t st) {
-  prof::Scope sc(prof::ATTN_FWD, 4.0 * a.dh * causal_pairs(a), st);
+  prof::Scope sc(prof::ATTN_FWD, 4.0 * a.dh * causal_pairs(a), false, st);
   return attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) ? attn_forward_mfma(a, st) : attn_forward_generic(a, st);
 }
 hipError_t attn_backward(const AttnArgs& a, hipStream_t st) {
-  prof::Scope sc(prof::ATTN_BWD, 10.0 * a.dh * causal_pairs(a), st);
+  prof::Scope sc(prof::ATTN_BWD, 10.0 * a.dh * causal_pairs(a), false, st);
   return attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) ? attn_backward_mfma(a, st) : attn_backward_generic(a, st);
 }
 
@@ -101,10 +92,12 @@ extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_d
   return e == hipSuccess ? (sbp::gemm_uses_mfma(g) ? 1 : 0) : -5;
 }
 
-// Per-launch timing of the GEMM / attention dispatchers with HIP events on the launch stream.
-// begin: creates 2*max_records events and switches recording on.  end: synchronises the events, returns per
-// kind (NT, NN, TN, generic GEMM, attention forward, attention backward) the launch count, the summed
-// duration in ms and the summed algorithmic flops, then destroys the events.
+// Per-launch timing with HIP events recorded on the launch stream around each GEMM kernel / attention launch
+// sequence.  begin: creates 2*max_records events and switches recording on.  end: synchronises the events and
+// returns per kind (see prof:: in launch.h; N_KIND entries) the launch count, the summed duration in ms, the
+// summed work of launches with host-known sizes and the summed (upper-bound) work of launches whose row count
+// was read on the device; then destroys the events.
+extern "C" int streambp_debug_profile_kinds(void) { return sbp::prof::N_KIND; }
 extern "C" int streambp_debug_profile_begin(int max_records) {
   using namespace sbp::prof;
   if (g_on) return -1;
@@ -117,16 +110,17 @@ extern "C" int streambp_debug_profile_begin(int max_records) {
   g_on = true;
   return 0;
 }
-extern "C" int streambp_debug_profile_end(long long* count, double* ms, double* work) {
+extern "C" int streambp_debug_profile_end(long long* count, double* ms, double* work, double* work_bounded) {
   using namespace sbp::prof;
   if (!g_on) return -1;
   g_on = false;
-  for (int k = 0; k < N_KIND; ++k) { count[k] = 0; ms[k] = 0.0; work[k] = 0.0; }
+  for (int k = 0; k < N_KIND; ++k) { count[k] = 0; ms[k] = 0.0; work[k] = 0.0; work_bounded[k] = 0.0; }
   int rc = 0;
   for (const Rec& r : g_recs) {
     float t = 0.f;
     if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess) { rc = -5; continue; }
-    count[r.kind] += 1; ms[r.kind] += t; work[r.kind] += r.work;
+    count[r.kind] += 1; ms[r.kind] += t;
+    (r.bounded ? work_bounded : work)[r.kind] += r.work;
   }
   for (auto& e : g_pool) hipEventDestroy(e);
   g_pool.clear();

@@ -152,17 +152,26 @@ __device__ __forceinline__ void compute_tile(const char* sA, const char* sB, int
   }
 }
 
-// Tile id -> (tile_m, tile_n): walk tiles in column bands of GROUP_M row tiles so that the workgroups resident
+// Tile id -> (tile_m, tile_n): walk tiles in column bands of group_m row tiles so that the workgroups resident
 // together share A row panels and B column panels in their XCD's L2.
-__device__ __forceinline__ void band_coords(int id, int tiles_m, int tiles_n, int& tm, int& tn) {
-  constexpr int GROUP_M = 8;
-  const int band = GROUP_M * tiles_n;
+__device__ __forceinline__ void band_coords(int id, int tiles_m, int tiles_n, int group_m, int& tm, int& tn) {
+  const int band = group_m * tiles_n;
   const int g = id / band;
-  const int first_m = g * GROUP_M;
-  const int gsz = min(tiles_m - first_m, GROUP_M);
+  const int first_m = g * group_m;
+  const int gsz = min(tiles_m - first_m, group_m);
   const int r = id % band;
   tm = first_m + r % gsz;
   tn = r / gsz;
+}
+// Band height.  With XCD-contiguous ids each XCD works on a run of n_tiles/8 consecutive ids, i.e. a block of
+// group_m rows x run/group_m columns of tiles; the fabric traffic of that XCD is proportional to rows + columns,
+// so the block is made as square as the problem allows.  (Interleaved ids, used by the accumulate form, give
+// every XCD one row of each band and all columns; 8 rows per band suit that.)
+__device__ __forceinline__ int band_height(int tiles_m, int n_tiles, bool xcd_contiguous) {
+  if (!xcd_contiguous) return 8;
+  const int run = max(1, n_tiles / 8);
+  int h = (int)(sqrtf((float)run) + 0.5f);
+  return max(1, min(h, min(tiles_m, 8)));
 }
 // Hardware deals consecutive workgroups round-robin to the 8 XCDs (each with its own L2); undo that so each
 // XCD gets a contiguous run of tile ids.  Measured: +3-4% for the store-only forms; the accumulate form (atomic adds
@@ -250,7 +259,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
   int tm, tn;
-  band_coords(MODE == 2 ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n, tm, tn);
+  band_coords(MODE == 2 ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n,
+              band_height(tiles_m, tiles_m * tiles_n, MODE != 2), tm, tn);
   if (MODE == 3) Cv = (float*)Cv + (int64_t)blockIdx.z * M * ldc;   // partial slices are laid out for the host-side M
   if (rows_dev) {                     // run-time row count: rows are M (NT / NN) or the reduction K (dW form)
     const int rows = max(0, *rows_dev);
@@ -284,7 +294,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_group_k(const GroupArgs ga
     if (i < ga.n && id >= ga.p[i].tile_begin) pi = i;
   const GroupProblem& g = ga.p[pi];
   int tm, tn;
-  band_coords(id - g.tile_begin, g.tiles_m, g.tiles_n, tm, tn);
+  band_coords(id - g.tile_begin, g.tiles_m, g.tiles_n, band_height(g.tiles_m, g.tiles_m * g.tiles_n, MODE != 2), tm, tn);
   gemm_tile<TA, TB, MODE>(g.A, g.B, g.C, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0, g.K, tm, tn, smem);
 }
 
@@ -359,8 +369,15 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
     else if (!g.ta && !g.tb) LAUNCH(false, false, MODE, CPTR); \
     else LAUNCH(true, false, MODE, CPTR);               \
   } while (0)
+  const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
+  const int mode = splits > 1 ? 3 : (g.out_dt == DT_BF16 ? 1 : (g.acc ? 2 : 0));
+  const int kind = prof::GEMM_SINGLE + layout * 4 + mode;
+  const double work = 2.0 * g.M * g.N * g.K;
   if (splits > 1) {
-    LAUNCH_LAYOUT(3, (void*)g.scratch);
+    {
+      prof::Scope sc(kind, work, g.rows_dev != nullptr, st);   // times the GEMM kernel, not the reduction after it
+      LAUNCH_LAYOUT(3, (void*)g.scratch);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t n = (int64_t)g.M * g.N;
@@ -370,6 +387,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
     else splitk_reduce_k<false, false><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
     return hipGetLastError();
   }
+  prof::Scope sc(kind, work, g.rows_dev != nullptr, st);
   if (g.out_dt == DT_BF16) LAUNCH_LAYOUT(1, g.C);
   else if (g.acc) LAUNCH_LAYOUT(2, g.C);
   else LAUNCH_LAYOUT(0, g.C);
@@ -404,6 +422,11 @@ hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
   }
   ga.total_tiles = tiles;
   const GemmArgs& g = gs[0];
+  double work = 0.0;
+  for (int i = 0; i < n; ++i) work += 2.0 * gs[i].M * gs[i].N * gs[i].K;
+  const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
+  const int mode = g.out_dt == DT_BF16 ? 1 : (g.acc ? 2 : 0);
+  prof::Scope sc(prof::GEMM_GROUP + layout * 4 + mode, work, false, st);
 #define GLAUNCH(TA, TB, MODE) gemm_mfma_group_k<TA, TB, MODE><<<tiles, NTHREADS, 0, st>>>(ga)
 #define GLAUNCH_LAYOUT(MODE)                     \
   do {                                           \

@@ -34,6 +34,19 @@ bool gemm_uses_mfma(const GemmArgs& g);
 // force the generic kernel (debug / A-B tests)
 void gemm_set_force_generic(bool on);
 
+// ---- optional per-launch timing (off unless streambp_debug_profile_begin was called) ----
+namespace prof {
+// kinds 0..11: gemm_mfma_k<layout, mode> with layout NT=0, NN=1, TN=2 and mode 0..3; 12..23: the grouped kernel;
+// then the shape-agnostic GEMM and the attention forward / backward launch sequences
+enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, N_KIND = 27 };
+struct Scope {
+  hipStream_t st; bool active = false; int kind = 0; double work = 0; bool bounded = false; hipEvent_t e0{}, e1{};
+  // bounded: `work` was computed from a host-side upper bound of a run-time row count
+  Scope(int kind, double work, bool bounded, hipStream_t st);
+  ~Scope();
+};
+}  // namespace prof
+
 // ---- elementwise / row kernels (dt = storage type of the T-typed tensors) ----
 // cos/sin table [n_pos, dh/2] (float2), angles evaluated in fp64.
 hipError_t rope_table(float2* tab, int n_pos, int dh, float theta, int pos_offset, hipStream_t st);

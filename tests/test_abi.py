@@ -31,6 +31,16 @@ def test_library_exports_every_declared_symbol():
     assert b"gfx950" in L.streambp_version()
 
 
+def test_binding_mirrors_every_entry_point():
+    # argument-marshalling wrappers carry the C names
+    for n in declared_functions():
+        if n in ("streambp_last_error",):
+            continue
+        assert hasattr(sb, n), f"binding lacks {n}"
+    for n in ("layer_cfg", "head_cfg", "attn_cfg", "stack_cfg", "debug_gemm", "debug_profile_begin", "debug_profile_end"):
+        assert hasattr(sb, n), n
+
+
 def good_layer_cfg(**kw):
     base = dict(dtype=sb.SBP_F32, batch=1, seq_len=256, chunk=64, hidden=64, n_q_heads=4, n_kv_heads=4,
                 head_dim=16, mlp_width=172)
