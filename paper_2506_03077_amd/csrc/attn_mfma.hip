@@ -115,6 +115,23 @@ __device__ __forceinline__ f32x16 zero16() {
 }
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+// A chain of N MFMAs whose A operands come from LDS: the fragment of step i+DEPTH is requested before the MFMA of
+// step i issues (ring of DEPTH+1 fragments), and scheduling barriers keep that order - left alone, the compiler
+// sinks every LDS read to just before its MFMA and the wave eats one LDS latency per MFMA.
+template <int N, int DEPTH = 3, typename LoadF, typename MmaF>
+__device__ __forceinline__ void mfma_chain(LoadF load, MmaF mma) {
+  bf16x8 f[DEPTH + 1];
+#pragma unroll
+  for (int i = 0; i < DEPTH && i < N; ++i) f[i] = load(i);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i + DEPTH < N) f[(i + DEPTH) % (DEPTH + 1)] = load(i + DEPTH);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(i, f[i % (DEPTH + 1)]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
 #define WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0f70)
 
 // row index (within a 32-row accumulator block) held in register r of a lane in half h
@@ -162,12 +179,10 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __re
     const int k0 = kt * TK;
     if (qw0 >= c || k0 > wave_last_key) return;           // nothing visible to this wave in the tile
     f32x16 s[2];
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      s[b] = zero16();
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) s[b] = MFMA(frag_rows(sK, b * 32, ks), bq[ks], s[b]);
-    }
+    s[0] = zero16();
+    s[1] = zero16();
+    mfma_chain<16>([&](int i) { return frag_rows(sK, (i >> 3) * 32, i & 7); },
+                   [&](int i, const bf16x8& f) { s[i >> 3] = MFMA(f, bq[i & 7], s[i >> 3]); });
     const bool diag = k0 + TK - 1 > wave_first_qpos;      // some (query, key) pair of the wave is masked
     if (diag) {                                           // wave-uniform: only tiles on the diagonal pay for the mask
 #pragma unroll
@@ -203,14 +218,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __re
         psum += p;
       }
     l_run += psum;
+    bf16x8 pb[4];     // P^T of the tile as four B operands: index = block * 2 + k16 step
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 pb = pack8(s[b], ks);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc_o[i] = MFMA(frag_cols_tr(sV, b * 32 + ks * 16, i * 32), pb, acc_o[i]);
-      }
+    for (int j = 0; j < 4; ++j) pb[j] = pack8(s[j >> 1], j & 1);
+    mfma_chain<16>([&](int i) { return frag_cols_tr(sV, (i >> 2) * 16, (i & 3) * 32); },
+                   [&](int i, const bf16x8& f) { acc_o[i & 3] = MFMA(f, pb[i >> 2], acc_o[i & 3]); });
   };
 
   auto issue = [&](int kt, char* sK, char* sV) {
@@ -296,10 +308,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) s = MFMA(frag_rows(sK, b * 32, ks), bq[ks], s);
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) dp = MFMA(frag_rows(sV, b * 32, ks), bdo[ks], dp);
+      mfma_chain<16>([&](int i) { return frag_rows(i < 8 ? sK : sV, b * 32, i & 7); },
+                     [&](int i, const bf16x8& f) { if (i < 8) s = MFMA(f, bq[i], s); else dp = MFMA(f, bdo[i - 8], dp); });
       if (diag) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -310,12 +320,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
         const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], sl, -lse2));
         s[r] = p * (dp[r] - dlt);                              // dS^T (the factor `scale` is applied at the end)
       }
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 db = pack8(s, ks);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sK, b * 32 + ks * 16, i * 32), db, acc[i]);
-      }
+      bf16x8 db[2];
+      db[0] = pack8(s, 0);
+      db[1] = pack8(s, 1);
+      mfma_chain<8>([&](int i) { return frag_cols_tr(sK, b * 32 + (i >> 2) * 16, (i & 3) * 32); },
+                    [&](int i, const bf16x8& f) { acc[i & 3] = MFMA(f, db[i >> 2], acc[i & 3]); });
     }
   };
   auto issue = [&](int kt, char* sK, char* sV) {
