@@ -363,25 +363,26 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
 // -------------------------------------------------------------------- dK/dV --
 // Workgroup = 128 keys of one KV head, 8 waves = 4 key blocks of 32 x 2 roles, so that each SIMD holds the two
 // waves of one key block:
-//   role P (waves 0-3): S = Q K^T -> P = exp2(S*sl - lse) (masked) -> hands P to its partner through LDS
-//                       -> dV^T += dO^T P
+//   role P (waves 0-3): S = Q K^T -> P = exp2(S*sl - lse) (masked), rounded to bf16 -> leaves P in LDS for its
+//                       partner -> dV^T += dO^T P
 //   role S (waves 4-7): dP = dO V^T -> takes P -> dS = P * (dP - delta) -> dK^T += Q^T dS
 // Each role keeps only its own operand fragments (K or V) and its own accumulator (dV or dK) in registers:
-// half the registers of a do-everything wave, so two waves fit per SIMD and the softmax arithmetic of one
-// overlaps the MFMAs of the other.  P is exchanged in fp32 (one 4 KiB slot per key block and query block).
+// half the registers of a do-everything wave, so two waves fit per SIMD.  Role S runs one tile behind role P:
+// in step j role P works on tile j while role S works on tile j-1, whose P is already in LDS, so inside a step
+// the two waves of a SIMD never wait for each other and the exponentials of one overlap the MFMAs of the other.
+// That takes three stages of the Q / dO tiles (tile j+1 in flight, j and j-1 in use) and two of P.
 // The loop walks the query tiles at or below the diagonal and, for each, the query heads of the group.
+constexpr int KV_STAGES = 3;
+
 __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                                   const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
                                                                   const float* __restrict__ lse, const float* __restrict__ delta,
                                                                   float* __restrict__ dk, float* __restrict__ dv, int Hq, int Hkv,
                                                                   int q_start, int c, float scale) {
-  __shared__ __attribute__((aligned(1024))) char sQ0[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sD0[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sQ1[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sD1[TILE64_BYTES];
-  __shared__ __attribute__((aligned(16))) float sP[4][2][64 * 16];   // [key block][query block][lane * 16 + r]
-  __shared__ __attribute__((aligned(16))) float sL[2][QT];           // log-sum-exp of the tile's queries
-  __shared__ __attribute__((aligned(16))) float sDl[2][QT];          // delta of the tile's queries
+  __shared__ __attribute__((aligned(1024))) char sQD[KV_STAGES][2][TILE64_BYTES];   // [stage][Q | dO]
+  __shared__ __attribute__((aligned(16))) bf16x8 sP[2][4][4][64];   // [tile parity][key block][query block * 2 + k16 step][lane]
+  __shared__ __attribute__((aligned(16))) float sL[KV_STAGES][QT];  // log-sum-exp of the tile's queries
+  __shared__ __attribute__((aligned(16))) float sDl[KV_STAGES][QT]; // delta of the tile's queries
 
   const int G = Hq / Hkv;
   const int key0 = blockIdx.x * KV_TILE, kvh = blockIdx.y;
@@ -411,104 +412,115 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
   const int n_qt = (c + QT - 1) / QT;
   const int n_iter = (n_qt - qt_first) * G;
 
-  auto issue = [&](int it, char* sQ, char* sD, int buf) {
+  auto issue = [&](int it, int stage) {
     const int qt = qt_first + it / G, hh = kvh * G + it % G;
-    dma_tile64<KV_THREADS>(q + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQ);
-    dma_tile64<KV_THREADS>(d_o + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sD);
+    dma_tile64<KV_THREADS>(q + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQD[stage][0]);
+    dma_tile64<KV_THREADS>(d_o + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQD[stage][1]);
     if (wave < 2) {   // 64 log-sum-exp values (wave 0) and 64 deltas (wave 1), 4 B per lane, also direct to LDS
       const int row = min(qt * QT + lane, c - 1);
       const float* src = (wave == 0 ? lse : delta) + (int64_t)hh * c + row;
-      __builtin_amdgcn_global_load_lds(src, LDS_AS(wave == 0 ? &sL[buf][0] : &sDl[buf][0]), 4, 0, 0);
+      __builtin_amdgcn_global_load_lds(src, LDS_AS(wave == 0 ? &sL[stage][0] : &sDl[stage][0]), 4, 0, 0);
     }
   };
-  // One 64-query tile = two 32-query blocks.  Both roles execute the same two barriers per tile.
-  auto step = [&](int it, const char* sQ, const char* sD, int buf) {
-    const int qt = qt_first + it / G;
-    const int qbase = qt * QT;
-    // nothing to do for this wave: no valid key, or every query of the tile precedes the wave's keys
-    const bool active = kw0 < n_total && q_start + min(qbase + QT, c) - 1 >= kw0;
+  // One 64-query tile = two 32-query blocks.  `active`: the wave has a valid key and some query of the tile is
+  // at or after its first key (the same answer for both waves of a key block).
+  auto tile_active = [&](int qbase) { return kw0 < n_total && q_start + min(qbase + QT, c) - 1 >= kw0; };
+
+  auto p_step = [&](int it, int stage, int par) {
+    const int qbase = (qt_first + it / G) * QT;
+    if (!tile_active(qbase)) return;
+    const char* sQ = sQD[stage][0];
+    const char* sD = sQD[stage][1];
     const bool diag = (q_start + qbase < kw0 + 31) || (qbase + QT > c);   // some pair masked, or ragged query tile
-    f32x16 t[2];   // role P: probabilities of the two blocks; role S: dP of the two blocks
-    if (active) {
+    f32x16 t[2];
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        t[b] = zero16();
-        const char* src = role_p ? sQ : sD;
+    for (int b = 0; b < 2; ++b) {
+      t[b] = zero16();
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) t[b] = MFMA(frag_rows(src, b * 32, ks), breg[ks], t[b]);
-      }
-      if (role_p) {
-        // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
+      for (int ks = 0; ks < 8; ++ks) t[b] = MFMA(frag_rows(sQ, b * 32, ks), breg[ks], t[b]);
+    }
+    // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
+    bf16x8 pb[4];
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          if (diag) {
+    for (int b = 0; b < 2; ++b) {
+      if (diag) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int qi = qbase + b * 32 + acc_row(r, half);
-              if (qi >= c || my_key > q_start + qi) t[b][r] = -INFINITY;      // exp2(-inf) = 0
-            }
-          }
-#pragma unroll
-          for (int a = 0; a < 4; ++a) {
-            const float4 l4 = *(const float4*)&sL[buf][b * 32 + 8 * a + 4 * half];
-            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-            float4 p4;
-            float* pp = (float*)&p4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(t[b][4 * a + e], sl, -lv[e] * LOG2E));
-              t[b][4 * a + e] = p;
-              pp[e] = p;
-            }
-            *(float4*)&sP[kb][b][(a * 64 + lane) * 4] = p4;     // slot layout [a][lane][e]: conflict-free
-          }
+        for (int r = 0; r < 16; ++r) {
+          const int qi = qbase + b * 32 + acc_row(r, half);
+          if (qi >= c || my_key > q_start + qi) t[b][r] = -INFINITY;      // exp2(-inf) = 0
         }
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const float4 l4 = *(const float4*)&sL[stage][b * 32 + 8 * a + 4 * half];
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          t[b][4 * a + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[b][4 * a + e], sl, -lv[e] * LOG2E));
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        pb[b * 2 + ks] = pack8(t[b], ks);
+        sP[par][kb][b * 2 + ks][lane] = pb[b * 2 + ks];
       }
     }
-    __syncthreads();   // P of both blocks is visible to the partner
-    if (active) {
-      if (role_p) {
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-          for (int ks = 0; ks < 2; ++ks) {
-            const bf16x8 pb = pack8(t[b], ks);
+      for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sD, j * 16, i * 32), pb[j], acc[i]);
+  };
+
+  auto s_step = [&](int it, int stage, int par) {
+    const int qbase = (qt_first + it / G) * QT;
+    if (!tile_active(qbase)) return;
+    const char* sQ = sQD[stage][0];
+    const char* sD = sQD[stage][1];
+    f32x16 t[2];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sD, b * 32 + ks * 16, i * 32), pb, acc[i]);
-          }
-      } else {
+    for (int b = 0; b < 2; ++b) {
+      t[b] = zero16();
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
+      for (int ks = 0; ks < 8; ++ks) t[b] = MFMA(frag_rows(sD, b * 32, ks), breg[ks], t[b]);
+    }
 #pragma unroll
-          for (int a = 0; a < 4; ++a) {
-            const float4 p4 = *(const float4*)&sP[kb][b][(a * 64 + lane) * 4];
-            const float4 d4 = *(const float4*)&sDl[buf][b * 32 + 8 * a + 4 * half];
-            const float pv[4] = {p4.x, p4.y, p4.z, p4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+    for (int b = 0; b < 2; ++b) {
+      float dl[16];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) t[b][4 * a + e] = pv[e] * (t[b][4 * a + e] - dl[e]);   // dS (scale applied at the end)
-          }
+      for (int a = 0; a < 4; ++a) {
+        const float4 d4 = *(const float4*)&sDl[stage][b * 32 + 8 * a + 4 * half];
+        dl[4 * a + 0] = d4.x; dl[4 * a + 1] = d4.y; dl[4 * a + 2] = d4.z; dl[4 * a + 3] = d4.w;
+      }
 #pragma unroll
-          for (int ks = 0; ks < 2; ++ks) {
-            const bf16x8 db = pack8(t[b], ks);
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8 p8 = sP[par][kb][b * 2 + ks][lane];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sQ, b * 32 + ks * 16, i * 32), db, acc[i]);
-          }
-        }
+        for (int j = 0; j < 8; ++j)     // dS (the softmax scale is applied once at the end)
+          t[b][8 * ks + j] = (float)p8[j] * (t[b][8 * ks + j] - dl[8 * ks + j]);
+        const bf16x8 db = pack8(t[b], ks);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sQ, b * 32 + ks * 16, i * 32), db, acc[i]);
       }
     }
   };
 
-  if (n_iter > 0) issue(0, sQ0, sD0, 0);
-  for (int it = 0; it < n_iter; it += 2) {
-    WAIT_VM0();
-    __syncthreads();    // tile `it` has landed for everyone; everyone is done with the other buffers and with sP
-    if (it + 1 < n_iter) issue(it + 1, sQ1, sD1, 1);
-    step(it, sQ0, sD0, 0);
-    if (it + 1 < n_iter) {
+  // Step j: tile j+1 goes in flight, role P takes tile j, role S takes tile j-1.  The barrier at the top says:
+  // tile j has landed for everyone, P of tile j-1 is written, and the stage and the P slot about to be
+  // overwritten (those of tile j-2) are no longer read.
+  if (n_iter > 0) {
+    issue(0, 0);
+    int st_next = 1, st_p = 0, st_s = KV_STAGES - 1;   // stages of tiles j+1, j, j-1
+    for (int j = 0; j <= n_iter; ++j) {
       WAIT_VM0();
       __syncthreads();
-      if (it + 2 < n_iter) issue(it + 2, sQ0, sD0, 0);
-      step(it + 1, sQ1, sD1, 1);
+      if (j + 1 < n_iter) issue(j + 1, st_next);
+      if (role_p) {
+        if (j < n_iter) p_step(j, st_p, j & 1);
+      } else {
+        if (j > 0) s_step(j - 1, st_s, (j - 1) & 1);
+      }
+      st_s = st_p;
+      st_p = st_next;
+      st_next = st_next + 1 == KV_STAGES ? 0 : st_next + 1;
     }
   }
 

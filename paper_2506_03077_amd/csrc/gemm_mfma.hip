@@ -13,6 +13,10 @@
 //    reduction index is the slow dimension in memory are kept in their natural
 //    [k][m|n] layout in LDS and fetched with the transposing LDS load
 //    (ds_read_b64_tr_b16), so no transposed copy ever exists in HBM.
+//  * The main loop contains no vector ALU instructions: a VALU instruction of one wave queues behind the MFMAs
+//    of the SIMD's other wave, so per-load address arithmetic would stretch the issue of a tile's loads
+//    several-fold.  Global addresses are an SGPR base (scalar adds per K step) + per-lane 32-bit offsets
+//    computed once; LDS fragment addresses are computed once per stage and reached with immediate offsets.
 //  * Both LDS layouts are XOR-swizzled (at 16-byte / 64-byte granularity) so that
 //    the fragment reads are bank-conflict free; because a direct-to-LDS load
 //    writes lane-linear, the swizzle is applied on the global-address side.
@@ -60,96 +64,59 @@ __device__ __forceinline__ int mnmaj_off(int krow, int col /*element*/) {
   return krow * (BM * 2) + (p16 << 4) + ((col & 7) << 1);
 }
 
-// 128-bit direct-to-LDS load: every lane supplies its own global address, the wave's 64 x 16 B land
-// contiguously at LDS address lds_wave_base.  Written as inline assembly so that the compiler does not
-// fold the explicit, counted vmcnt waits of the multi-stage pipeline into vmcnt(0).
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_wave_base) : "memory");
+// 128-bit direct-to-LDS load, SGPR base + per-lane 32-bit byte offset: the wave's 64 x 16 B land contiguously at
+// LDS address lds_wave_base.  Inline assembly for two reasons: the compiler must not fold the explicit, counted
+// vmcnt waits of the pipeline into vmcnt(0), and this addressing form needs no vector ALU work per load - in the
+// main loop every VALU instruction queues behind the MFMAs of the SIMD's other wave, so per-load 64-bit address
+// arithmetic (what the flat form needs) stretches the issue of a tile's loads several-fold.
+__device__ __forceinline__ void dma16(const char* base /*uniform*/, uint32_t voff, uint32_t lds_wave_base /*uniform*/) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_wave_base) : "memory");
 }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
+// Make a precomputed value opaque so that the compiler keeps it in a register instead of recomputing it in the loop.
+__device__ __forceinline__ uint32_t pin(uint32_t v) { asm volatile("" : "+v"(v)); return v; }
 
-// Issue this thread's share of one operand tile (direct-to-LDS, 16 B per lane).
-//   KMAJ : tile rows r0..r0+255 (clamped to r_max), k columns k0..k0+31
-//   MNMAJ: tile k-rows k0..k0+31 (clamped to k_max), columns r0..r0+255
+// Byte offset, relative to the tile's corner element, of load i (0..LOADS_PER_THREAD-1) of this thread's share.
+//   KMAJ : corner = (row r0, column k0); rows clamped so that r0 + row <= r_max
+//   MNMAJ: corner = (k-row k0, column r0); k-rows clamped so that k0 + krow <= k_max
 template <bool MNMAJ>
-__device__ __forceinline__ void load_tile(const bf16_t* __restrict__ g, int64_t ld, int r0, int r_max, int k0, int k_max,
-                                          const char* lds_tile) {
-  const int tid = threadIdx.x;
-  const uint32_t wave_base = __builtin_amdgcn_readfirstlane(lds_addr(lds_tile) + (uint32_t)(tid & ~63) * 16u);
-#pragma unroll
-  for (int i = 0; i < LOADS_PER_THREAD; ++i) {
-    const int id = i * NTHREADS + tid;            // 16-byte slot in the tile, lane-linear within a wave
-    const bf16_t* src;
-    if (!MNMAJ) {
-      const int row = id / CPR, pc = id % CPR;
-      const int chunk = pc ^ kmaj_swz(row);
-      src = g + (int64_t)min(r0 + row, r_max) * ld + k0 + chunk * 8;
-    } else {
-      const int krow = id >> 5, p16 = id & 31;
-      const int c16 = ((((p16 >> 2) ^ (krow & 7)) << 2) | (p16 & 3));
-      src = g + (int64_t)min(k0 + krow, k_max) * ld + r0 + c16 * 8;
-    }
-    dma16(src, wave_base + (uint32_t)(i * NTHREADS * 16));
-  }
-}
-
-// Fragment of a 32-row block for one k16 step: lane l holds row (l%32), k = 8*(l/32)+0..7.
-template <bool MNMAJ>
-__device__ __forceinline__ bf16x8 load_frag(const char* lds_tile, int row_base, int kk) {
-  const int l = threadIdx.x & 63;
+__device__ __forceinline__ uint32_t load_offset(int i, int64_t ld, int r0, int r_max, int k0, int k_max) {
+  const int id = i * NTHREADS + (int)threadIdx.x;   // 16-byte slot in the tile, lane-linear within a wave
   if (!MNMAJ) {
-    return *(const bf16x8*)(lds_tile + kmaj_off(row_base + (l & 31), kk * 2 + (l >> 5)));
+    const int row = id / CPR, pc = id % CPR;
+    const int chunk = pc ^ kmaj_swz(row);
+    return (uint32_t)(((int64_t)(min(r0 + row, r_max) - r0) * ld + chunk * 8) * 2);
   } else {
-    // transposing load: in each group of 16 lanes, lane p supplies the address of 4 consecutive columns of
-    // k-row (p/4); lane i receives the 4 k-values of column i.
-    const int p = l & 15, g = l >> 4;
-    const int col = row_base + 16 * (g & 1) + 4 * (p & 3);
-    const int krow = kk * 16 + 8 * (g >> 1) + (p >> 2);
-    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(lds_tile + mnmaj_off(krow, col)));
-    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(lds_tile + mnmaj_off(krow + 4, col)));
-    typedef short short8v __attribute__((ext_vector_type(8)));
-    short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, r);
+    const int krow = id >> 5, p16 = id & 31;
+    const int c16 = ((((p16 >> 2) ^ (krow & 7)) << 2) | (p16 & 3));
+    return (uint32_t)(((int64_t)(min(k0 + krow, k_max) - k0) * ld + c16 * 8) * 2);
   }
 }
 
-template <bool TA, bool TB>
-__device__ __forceinline__ void compute_tile(const char* sA, const char* sB, int wm0, int wn0, f32x16 (&acc)[FM][FN],
-                                             int k_valid /* reduction rows valid in this tile (TN tail) */) {
-  // Fragments are double-buffered in registers: the LDS reads of k16 step kk+1 are in flight while the
-  // MFMAs of step kk issue.
-  bf16x8 a[2][FM], b[2][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i) a[0][i] = load_frag<TA>(sA, wm0 + i * 32, 0);
-#pragma unroll
-  for (int j = 0; j < FN; ++j) b[0][j] = load_frag<TB>(sB, wn0 + j * 32, 0);
-#pragma unroll
-  for (int kk = 0; kk < BK / 16; ++kk) {
-    const int cur = kk & 1, nxt = cur ^ 1;
-    if (kk + 1 < BK / 16) {
-#pragma unroll
-      for (int i = 0; i < FM; ++i) a[nxt][i] = load_frag<TA>(sA, wm0 + i * 32, kk + 1);
-#pragma unroll
-      for (int j = 0; j < FN; ++j) b[nxt][j] = load_frag<TB>(sB, wn0 + j * 32, kk + 1);
-    }
-    __builtin_amdgcn_sched_barrier(0);   // keep the prefetch above the MFMAs (the scheduler would sink it to its use)
-    if (TA && k_valid < BK) {   // zero reduction rows past the end (A only: B rows are finite duplicates)
-      const int kbase = kk * 16 + 8 * ((threadIdx.x & 63) >> 5);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (kbase + e >= k_valid) a[cur][i][e] = (bf16_t)0.0f;
-    }
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
+// LDS byte offset (within an operand tile) of this lane's fragment read, for a 32-row block starting at row_base
+// and k16 step kk.  K-major: one 128-bit read.  Reduction-major: two transposing 64-bit reads (k-rows +0 and +4).
+__device__ __forceinline__ uint32_t frag_off_kmaj(int row_base, int kk) {
+  const int l = threadIdx.x & 63;
+  return (uint32_t)kmaj_off(row_base + (l & 31), kk * 2 + (l >> 5));
+}
+__device__ __forceinline__ uint32_t frag_off_mnmaj(int row_base, int kk, int hi) {
+  const int l = threadIdx.x & 63;
+  const int p = l & 15, g = l >> 4;
+  const int col = row_base + 16 * (g & 1) + 4 * (p & 3);
+  const int krow = kk * 16 + 8 * (g >> 1) + (p >> 2) + 4 * hi;
+  return (uint32_t)mnmaj_off(krow, col);
+}
+typedef short short8v __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
+  return *(const bf16x8*)(__attribute__((address_space(3))) const char*)(uintptr_t)addr;
+}
+__device__ __forceinline__ bf16x8 lds_read_tr(uint32_t lo_addr, uint32_t hi_addr) {
+  short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(uintptr_t)lo_addr);
+  short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(uintptr_t)hi_addr);
+  short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
 }
 
 // Tile id -> (tile_m, tile_n): walk tiles in column bands of group_m row tiles so that the workgroups resident
@@ -187,10 +154,17 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int n_tiles) {
 
 // One 256x256 output tile: K range [k_begin, k_end).
 // MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store, C already offset)
+//
+// The main loop is written so that it contains no vector ALU instructions at all: global addresses are an SGPR base
+// (advanced with scalar adds) plus per-lane offsets computed once, LDS fragment addresses are computed once per
+// stage and reached with immediate offsets, and the two LDS stages are unrolled.  Only the last K step of a ragged
+// reduction (weight-gradient form) takes a slower path with clamped addresses and zeroed fragments.
 template <bool TA, bool TB, int MODE>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ Cv,
                                           int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc, int k_begin, int k_end,
                                           int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES]) {
+  static_assert(NSTAGE == 2, "the main loop is unrolled over two LDS stages");
+  constexpr bool AMN = TA, BMN = !TB;     // operand kept reduction-major in LDS (B stored [N,K] is the K-contiguous case)
   const int m0 = tm * BM, n0 = tn * BN;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm0 = (wave / NWAVE_N) * WTM, wn0 = (wave % NWAVE_N) * WTN;
@@ -204,29 +178,109 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // A tile: !TA -> rows are m (clamp to M-1), TA -> rows are k (clamp to K-1), columns m (M % BM == 0 required)
-  auto issue = [&](int kt) {
+  // ---- global side: uniform 64-bit bases that walk along K + per-lane byte offsets (rows clamped once)
+  const char* gA = (const char*)(A + (AMN ? (int64_t)k_begin * lda + m0 : (int64_t)m0 * lda + k_begin));
+  const char* gB = (const char*)(B + (BMN ? (int64_t)k_begin * ldb + n0 : (int64_t)n0 * ldb + k_begin));
+  const int64_t stepA = (AMN ? (int64_t)BK * lda : (int64_t)BK) * 2, stepB = (BMN ? (int64_t)BK * ldb : (int64_t)BK) * 2;
+  uint32_t offA[LOADS_PER_THREAD], offB[LOADS_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < LOADS_PER_THREAD; ++i) {
+    // the unclamped k range (k_max = INT_MAX) is right for every full K step
+    offA[i] = pin(load_offset<AMN>(i, lda, m0, M - 1, 0, 0x7fffffff));
+    offB[i] = pin(load_offset<BMN>(i, ldb, n0, N - 1, 0, 0x7fffffff));
+  }
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(&smem[0][0][0]) + (uint32_t)(threadIdx.x & ~63) * 16u);
+  auto issue = [&](int kt, int st) {
+    const char* a_base = gA + (int64_t)kt * stepA;
+    const char* b_base = gB + (int64_t)kt * stepB;
+    const uint32_t la = lds_wave + (uint32_t)(st * 2 * TILE_BYTES), lb = la + TILE_BYTES;
     const int k0 = k_begin + kt * BK;
-    const int st = kt % NSTAGE;
-    load_tile<TA>(A, lda, m0, M - 1, k0, K - 1, smem[st][0]);
-    load_tile<!TB>(B, ldb, n0, N - 1, k0, K - 1, smem[st][1]);   // TB (B stored [N,K]) is the K-contiguous case
+    if ((AMN || BMN) && k0 + BK > K) {    // ragged last K step: clamp the k-rows (slow path, once per tile)
+#pragma unroll
+      for (int i = 0; i < LOADS_PER_THREAD; ++i) {
+        dma16(a_base, AMN ? load_offset<AMN>(i, lda, m0, M - 1, k0, K - 1) : offA[i], la + (uint32_t)(i * NTHREADS * 16));
+        dma16(b_base, BMN ? load_offset<BMN>(i, ldb, n0, N - 1, k0, K - 1) : offB[i], lb + (uint32_t)(i * NTHREADS * 16));
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < LOADS_PER_THREAD; ++i) {
+        dma16(a_base, offA[i], la + (uint32_t)(i * NTHREADS * 16));
+        dma16(b_base, offB[i], lb + (uint32_t)(i * NTHREADS * 16));
+      }
+    }
   };
 
-  // Ring of NSTAGE tiles, NSTAGE-1 in flight.  At step kt: wait until tile kt has landed (the loads of the
-  // up to NSTAGE-2 younger tiles may still be outstanding), barrier (all waves' shares have landed and
-  // everyone is done reading the stage of tile kt-1), refill that stage with tile kt+NSTAGE-1, compute.
+  // ---- LDS side: fragment addresses per stage, computed once
+  constexpr int NA = AMN ? 2 * FM : BK / 16, NB = BMN ? 2 * FN : BK / 16;
+  uint32_t fa[NSTAGE][NA], fb[NSTAGE][NB];
 #pragma unroll
-  for (int p = 0; p < NSTAGE - 1; ++p)
-    if (p < nk) issue(p);
-  for (int kt = 0; kt < nk; ++kt) {
-    const int younger = min(NSTAGE - 2, nk - 1 - kt);        // tiles issued after tile kt so far
-    if (NSTAGE > 3 && younger >= 2) WAIT_VMCNT(2 * LOADS_PER_TILE);
-    else if (NSTAGE > 2 && younger == 1) WAIT_VMCNT(LOADS_PER_TILE);
-    else WAIT_VMCNT(0);
+  for (int st = 0; st < NSTAGE; ++st) {
+    const uint32_t sa = lds_addr(&smem[st][0][0]), sb = lds_addr(&smem[st][1][0]);
+#pragma unroll
+    for (int x = 0; x < NA; ++x) fa[st][x] = pin(sa + (AMN ? frag_off_mnmaj(wm0 + (x >> 1) * 32, 0, x & 1) : frag_off_kmaj(wm0, x)));
+#pragma unroll
+    for (int x = 0; x < NB; ++x) fb[st][x] = pin(sb + (BMN ? frag_off_mnmaj(wn0 + (x >> 1) * 32, 0, x & 1) : frag_off_kmaj(wn0, x)));
+  }
+  // fragment (block i, k16 step kk) of stage st: K-major blocks are 32 rows = 4096 B apart (the swizzle repeats every
+  // 16 rows); reduction-major k16 steps are 16 k-rows = 8192 B apart (the swizzle repeats every 8 k-rows)
+  auto frag_a = [&](int st, int i, int kk) {
+    if (AMN) return lds_read_tr(fa[st][2 * i] + kk * 16 * BM * 2, fa[st][2 * i + 1] + kk * 16 * BM * 2);
+    else return lds_read_b128(fa[st][kk] + i * 32 * BK * 2);
+  };
+  auto frag_b = [&](int st, int j, int kk) {
+    if (BMN) return lds_read_tr(fb[st][2 * j] + kk * 16 * BN * 2, fb[st][2 * j + 1] + kk * 16 * BN * 2);
+    else return lds_read_b128(fb[st][kk] + j * 32 * BK * 2);
+  };
+
+  // One K step on stage st.  Fragments are double-buffered in registers: the LDS reads of k16 step kk+1 are in
+  // flight while the MFMAs of step kk issue.
+  auto compute = [&](int st, int k_valid) {
+    bf16x8 a[2][FM], b[2][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) a[0][i] = frag_a(st, i, 0);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) b[0][j] = frag_b(st, j, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) a[nxt][i] = frag_a(st, i, kk + 1);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) b[nxt][j] = frag_b(st, j, kk + 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the prefetch above the MFMAs (the scheduler would sink it to its use)
+      if (TA && k_valid < BK) {   // zero reduction rows past the end (A only: B rows are finite duplicates)
+        const int kbase = kk * 16 + 8 * (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (kbase + e >= k_valid) a[cur][i][e] = (bf16_t)0.0f;
+      }
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // Two stages: at step kt wait for tile kt, barrier (every wave's share has landed and everyone is done reading
+  // the other stage), refill the other stage with tile kt+1, compute.
+  if (nk > 0) issue(0, 0);
+  for (int kt = 0; kt < nk; kt += 2) {
+    WAIT_VMCNT(0);
     __syncthreads();
-    const int st = kt % NSTAGE;
-    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
-    compute_tile<TA, !TB>(smem[st][0], smem[st][1], wm0, wn0, acc, k_end - (k_begin + kt * BK));
+    if (kt + 1 < nk) issue(kt + 1, 1);
+    compute(0, k_end - (k_begin + kt * BK));
+    if (kt + 1 < nk) {
+      WAIT_VMCNT(0);
+      __syncthreads();
+      if (kt + 2 < nk) issue(kt + 2, 0);
+      compute(1, k_end - (k_begin + (kt + 1) * BK));
+    }
   }
 
   // Epilogue.  Accumulator register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32.
@@ -331,6 +385,7 @@ bool gemm_mfma_eligible(const GemmArgs& g) {
     return false;                            // TT is never needed
   }
   if (g.lda % 8 || g.ldb % 8) return false;
+  if (g.lda >= (1 << 22) || g.ldb >= (1 << 22)) return false;   // per-lane byte offsets within a tile are 32-bit
   if (((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15) || ((uintptr_t)g.C & 15)) return false;
   if (g.ldc % 4) return false;
   return true;
