@@ -31,6 +31,8 @@
 //            reproducible).
 #include "launch.h"
 
+#include <type_traits>
+
 #include <algorithm>
 
 namespace sbp {
@@ -116,6 +118,72 @@ __device__ __forceinline__ f32x16 zero16() {
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
+// ---- address work hoisted out of the tile loops --------------------------------------------------------------
+// In the tile loops every vector-ALU instruction competes with the softmax arithmetic for the SIMD's VALU issue
+// slots, so nothing there computes an address: the per-lane byte offsets of the fragment reads inside a 64-row
+// tile and of the direct-to-LDS loads are computed once per kernel, every tile / row block / stage is reached
+// with immediate offsets, and the global side is an SGPR base plus those per-lane offsets.
+struct FragPre {
+  uint32_t rows[8];   // frag_rows: k16 step ks of row block 0            (row block b: + b * 32 * ROW_BYTES)
+  uint32_t tr[8];     // frag_cols_tr: [i * 2 + hi], head_dim block i, tile rows +0 / +8, row_base 0 (+ row_base * ROW_BYTES)
+};
+__device__ __forceinline__ FragPre frag_pre(uint32_t lds_base /* LDS address of tile 0 */) {
+  const int l = threadIdx.x & 63;
+  FragPre f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) f.rows[ks] = pin(lds_base + (uint32_t)tile_off(l & 31, ks * 2 + (l >> 5)));
+  const int p = l & 15, g = l >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) {
+      const int col = i * 32 + 16 * (g & 1) + 4 * (p & 3);
+      const int row = 4 * (g >> 1) + (p >> 2) + 8 * hi;
+      f.tr[i * 2 + hi] = pin(lds_base + (uint32_t)(tile_off(row, col >> 3) + ((col & 7) << 1)));
+    }
+  return f;
+}
+__device__ __forceinline__ bf16x8 lds_b128(uint32_t addr) {
+  return *(const bf16x8*)(__attribute__((address_space(3))) const char*)(uintptr_t)addr;
+}
+__device__ __forceinline__ bf16x8 lds_tr(uint32_t lo_addr, uint32_t hi_addr) {
+  short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(uintptr_t)lo_addr);
+  short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(uintptr_t)hi_addr);
+  short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Direct-to-LDS load of a 64-row tile by NT threads: rows 0..63 of a [*, stride] bf16 matrix starting at `g`
+// (uniform pointer to the tile's first row, first of its 128 columns).  rows_valid = rows that exist from `g` on:
+// a tile that runs past the end (only the last one) clamps its row indices so that nothing out of range is read.
+template <int NT>
+struct TileLoad { uint32_t voff[1024 / NT]; };
+template <int NT>
+__device__ __forceinline__ uint32_t tile_load_offset(int i, int64_t stride, int rows_valid) {
+  const int id = i * NT + (int)threadIdx.x;
+  const int row = id >> 4, pc = id & 15;
+  const int chunk = pc ^ swz(row);
+  return (uint32_t)(((int64_t)min(row, rows_valid - 1) * stride + chunk * 8) * 2);
+}
+template <int NT>
+__device__ __forceinline__ TileLoad<NT> tile_load_pre(int64_t stride) {
+  TileLoad<NT> t;
+#pragma unroll
+  for (int i = 0; i < 1024 / NT; ++i) t.voff[i] = pin(tile_load_offset<NT>(i, stride, 64));
+  return t;
+}
+template <int NT>
+__device__ __forceinline__ void dma_tile64(const TileLoad<NT>& t, const bf16_t* g, int64_t stride, int rows_valid, uint32_t lds_tile) {
+  const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + (uint32_t)(threadIdx.x & ~63) * 16u);
+  if (rows_valid >= 64) {
+#pragma unroll
+    for (int i = 0; i < 1024 / NT; ++i) dma16((const char*)g, t.voff[i], dst + (uint32_t)(i * NT * 16));
+  } else {
+#pragma unroll
+    for (int i = 0; i < 1024 / NT; ++i) dma16((const char*)g, tile_load_offset<NT>(i, stride, rows_valid), dst + (uint32_t)(i * NT * 16));
+  }
+}
+
 // A chain of N MFMAs whose A operands come from LDS: the fragment of step i+DEPTH is requested before the MFMA of
 // step i issues (ring of DEPTH+1 fragments), and scheduling barriers keep that order - left alone, the compiler
 // sinks every LDS read to just before its MFMA and the wave eats one LDS latency per MFMA.
@@ -138,14 +206,14 @@ __device__ __forceinline__ void mfma_chain(LoadF load, MmaF mma) {
 __device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r >> 2) + 4 * h + (r & 3); }
 
 // ------------------------------------------------------------------ forward --
+// 8 waves x 32 queries; K/V tiles of 64 keys stream through two LDS stages.  The softmax denominator is taken from
+// the matrix pipe as well (one extra MFMA per k16 step against an all-ones operand sums the rounded probabilities
+// of each query), which takes 32 additions per tile off the vector ALU - the busier of the two units here.
 __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                                  const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                                  float* __restrict__ lse, int Hq, int Hkv, int q_start,
                                                                  int c, float scale) {
-  __shared__ __attribute__((aligned(1024))) char sK0[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sV0[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sK1[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sV1[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sT[4][TILE64_BYTES];   // stage st: K = sT[2 st], V = sT[2 st + 1]
 
   const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
@@ -163,25 +231,34 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __re
   const int wave_last_key = q_start + min(qw0 + 32, c) - 1;           // last key any query of this wave sees
   const int wave_first_qpos = q_start + qw0;
 
+  const uint32_t lds0 = lds_addr(&sT[0][0]);
+  const FragPre fp = frag_pre(lds0);
+  const TileLoad<AT_THREADS> tl = tile_load_pre<AT_THREADS>(kv_stride);
+
   bf16x8 bq[8];
   {
     const bf16_t* qp = q + ((int64_t)q_row * Hq + h) * DH + half * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) bq[ks] = *(const bf16x8*)(qp + ks * 16);
   }
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)1.0f;
   f32x16 acc_o[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc_o[i] = zero16();
-  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 acc_l = zero16();      // every register of a lane: sum over the keys so far of the probabilities of its query
+  float m_run = -INFINITY;
   const float sl = scale * LOG2E;
 
-  auto step = [&](int kt, const char* sK, const char* sV) {
+  auto step = [&](int kt, auto stage) {
+    constexpr uint32_t oK = decltype(stage)::value * 2 * TILE64_BYTES, oV = oK + TILE64_BYTES;
     const int k0 = kt * TK;
     if (qw0 >= c || k0 > wave_last_key) return;           // nothing visible to this wave in the tile
     f32x16 s[2];
     s[0] = zero16();
     s[1] = zero16();
-    mfma_chain<16>([&](int i) { return frag_rows(sK, (i >> 3) * 32, i & 7); },
+    mfma_chain<16>([&](int i) { return lds_b128(fp.rows[i & 7] + oK + (i >> 3) * 32 * ROW_BYTES); },
                    [&](int i, const bf16x8& f) { s[i >> 3] = MFMA(f, bq[i & 7], s[i >> 3]); });
     const bool diag = k0 + TK - 1 > wave_first_qpos;      // some (query, key) pair of the wave is masked
     if (diag) {                                           // wave-uniform: only tiles on the diagonal pay for the mask
@@ -201,50 +278,50 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __re
     if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= alpha;
       m_run = m_new;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc_l[r] *= alpha;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
     }
-    float psum = 0.f;
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], sl, -m_run));
-        s[b][r] = p;
-        psum += p;
-      }
-    l_run += psum;
+      for (int r = 0; r < 16; ++r) s[b][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], sl, -m_run));
     bf16x8 pb[4];     // P^T of the tile as four B operands: index = block * 2 + k16 step
 #pragma unroll
     for (int j = 0; j < 4; ++j) pb[j] = pack8(s[j >> 1], j & 1);
-    mfma_chain<16>([&](int i) { return frag_cols_tr(sV, (i >> 2) * 16, (i & 3) * 32); },
-                   [&](int i, const bf16x8& f) { acc_o[i & 3] = MFMA(f, pb[i >> 2], acc_o[i & 3]); });
+    mfma_chain<16>([&](int i) { return lds_tr(fp.tr[(i & 3) * 2] + oV + (i >> 2) * 16 * ROW_BYTES, fp.tr[(i & 3) * 2 + 1] + oV + (i >> 2) * 16 * ROW_BYTES); },
+                   [&](int i, const bf16x8& f) {
+                     acc_o[i & 3] = MFMA(f, pb[i >> 2], acc_o[i & 3]);
+                     if ((i & 3) == 3) acc_l = MFMA(ones, pb[i >> 2], acc_l);
+                   });
   };
-
-  auto issue = [&](int kt, char* sK, char* sV) {
-    dma_tile64(kbase, kv_stride, kt * TK, n_total - 1, sK);
-    dma_tile64(vbase, kv_stride, kt * TK, n_total - 1, sV);
+  auto issue = [&](int kt, int st) {
+    const int64_t row0 = (int64_t)kt * TK;
+    dma_tile64(tl, kbase + row0 * kv_stride, kv_stride, n_total - kt * TK, lds0 + (uint32_t)(st * 2 * TILE64_BYTES));
+    dma_tile64(tl, vbase + row0 * kv_stride, kv_stride, n_total - kt * TK, lds0 + (uint32_t)((st * 2 + 1) * TILE64_BYTES));
   };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
 
-  issue(0, sK0, sV0);
+  issue(0, 0);
   for (int kt = 0; kt < n_tiles; kt += 2) {
     WAIT_VM0();
     __syncthreads();
-    if (kt + 1 < n_tiles) issue(kt + 1, sK1, sV1);
-    step(kt, sK0, sV0);
+    if (kt + 1 < n_tiles) issue(kt + 1, 1);
+    step(kt, S0{});
     if (kt + 1 < n_tiles) {
       WAIT_VM0();
       __syncthreads();
-      if (kt + 2 < n_tiles) issue(kt + 2, sK0, sV0);
-      step(kt + 1, sK1, sV1);
+      if (kt + 2 < n_tiles) issue(kt + 2, 0);
+      step(kt + 1, S1{});
     }
   }
 
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = acc_l[0];
   if (q_valid) {
     const float inv = 1.0f / l_tot;
     bf16_t* op = o + ((int64_t)my_q * Hq + h) * DH;
@@ -267,10 +344,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
                                                                     const float* __restrict__ lse, const float* __restrict__ delta,
                                                                     bf16_t* __restrict__ dq, int Hq, int Hkv, int q_start, int c,
                                                                     float scale) {
-  __shared__ __attribute__((aligned(1024))) char sK0[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sV0[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sK1[TILE64_BYTES];
-  __shared__ __attribute__((aligned(1024))) char sV1[TILE64_BYTES];
+  __shared__ __attribute__((aligned(1024))) char sT[4][TILE64_BYTES];   // stage st: K = sT[2 st], V = sT[2 st + 1]
 
   const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
@@ -288,6 +362,10 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
   const int wave_last_key = q_start + min(qw0 + 32, c) - 1;
   const int wave_first_qpos = q_start + qw0;
 
+  const uint32_t lds0 = lds_addr(&sT[0][0]);
+  const FragPre fp = frag_pre(lds0);
+  const TileLoad<AT_THREADS> tl = tile_load_pre<AT_THREADS>(kv_stride);
+
   bf16x8 bq[8], bdo[8];
   {
     const int64_t off = ((int64_t)q_row * Hq + h) * DH + half * 8;
@@ -301,14 +379,15 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc[i] = zero16();
 
-  auto step = [&](int kt, const char* sK, const char* sV) {
+  auto step = [&](int kt, auto stage) {
+    constexpr uint32_t oK = decltype(stage)::value * 2 * TILE64_BYTES, oV = oK + TILE64_BYTES;
     const int k0 = kt * TK;
     if (qw0 >= c || k0 > wave_last_key) return;
     const bool diag = k0 + TK - 1 > wave_first_qpos;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       f32x16 s = zero16(), dp = zero16();
-      mfma_chain<16>([&](int i) { return frag_rows(i < 8 ? sK : sV, b * 32, i & 7); },
+      mfma_chain<16>([&](int i) { return lds_b128(fp.rows[i & 7] + (i < 8 ? oK : oV) + b * 32 * ROW_BYTES); },
                      [&](int i, const bf16x8& f) { if (i < 8) s = MFMA(f, bq[i], s); else dp = MFMA(f, bdo[i - 8], dp); });
       if (diag) {
 #pragma unroll
@@ -323,26 +402,29 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
       bf16x8 db[2];
       db[0] = pack8(s, 0);
       db[1] = pack8(s, 1);
-      mfma_chain<8>([&](int i) { return frag_cols_tr(sK, b * 32 + (i >> 2) * 16, (i & 3) * 32); },
+      mfma_chain<8>([&](int i) { return lds_tr(fp.tr[(i & 3) * 2] + oK + (b * 32 + (i >> 2) * 16) * ROW_BYTES, fp.tr[(i & 3) * 2 + 1] + oK + (b * 32 + (i >> 2) * 16) * ROW_BYTES); },
                     [&](int i, const bf16x8& f) { acc[i & 3] = MFMA(f, db[i >> 2], acc[i & 3]); });
     }
   };
-  auto issue = [&](int kt, char* sK, char* sV) {
-    dma_tile64(kbase, kv_stride, kt * TK, n_total - 1, sK);
-    dma_tile64(vbase, kv_stride, kt * TK, n_total - 1, sV);
+  auto issue = [&](int kt, int st) {
+    const int64_t row0 = (int64_t)kt * TK;
+    dma_tile64(tl, kbase + row0 * kv_stride, kv_stride, n_total - kt * TK, lds0 + (uint32_t)(st * 2 * TILE64_BYTES));
+    dma_tile64(tl, vbase + row0 * kv_stride, kv_stride, n_total - kt * TK, lds0 + (uint32_t)((st * 2 + 1) * TILE64_BYTES));
   };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
 
-  issue(0, sK0, sV0);
+  issue(0, 0);
   for (int kt = 0; kt < n_tiles; kt += 2) {
     WAIT_VM0();
     __syncthreads();
-    if (kt + 1 < n_tiles) issue(kt + 1, sK1, sV1);
-    step(kt, sK0, sV0);
+    if (kt + 1 < n_tiles) issue(kt + 1, 1);
+    step(kt, S0{});
     if (kt + 1 < n_tiles) {
       WAIT_VM0();
       __syncthreads();
-      if (kt + 2 < n_tiles) issue(kt + 2, sK0, sV0);
-      step(kt + 1, sK1, sV1);
+      if (kt + 2 < n_tiles) issue(kt + 2, 0);
+      step(kt + 1, S1{});
     }
   }
 

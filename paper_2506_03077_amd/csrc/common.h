@@ -52,6 +52,20 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return t;
 }
 
+// 128-bit direct-to-LDS load, SGPR base + per-lane 32-bit byte offset: the wave's 64 x 16 B land contiguously at
+// LDS address lds_wave_base.  Inline assembly for two reasons: the compiler must not fold the explicit, counted
+// vmcnt waits of a pipeline into vmcnt(0), and this addressing form needs no vector ALU work per load - in an
+// MFMA loop every VALU instruction queues behind the MFMAs of the SIMD's other wave, so per-load 64-bit address
+// arithmetic (what the flat form needs) stretches the issue of a tile's loads several-fold.
+__device__ __forceinline__ void dma16(const char* base /*uniform*/, uint32_t voff, uint32_t lds_wave_base /*uniform*/) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_wave_base) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+// Make a precomputed value opaque so that the compiler keeps it in a register instead of recomputing it in a loop.
+__device__ __forceinline__ uint32_t pin(uint32_t v) { asm volatile("" : "+v"(v)); return v; }
+
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -64,20 +64,6 @@ __device__ __forceinline__ int mnmaj_off(int krow, int col /*element*/) {
   return krow * (BM * 2) + (p16 << 4) + ((col & 7) << 1);
 }
 
-// 128-bit direct-to-LDS load, SGPR base + per-lane 32-bit byte offset: the wave's 64 x 16 B land contiguously at
-// LDS address lds_wave_base.  Inline assembly for two reasons: the compiler must not fold the explicit, counted
-// vmcnt waits of the pipeline into vmcnt(0), and this addressing form needs no vector ALU work per load - in the
-// main loop every VALU instruction queues behind the MFMAs of the SIMD's other wave, so per-load 64-bit address
-// arithmetic (what the flat form needs) stretches the issue of a tile's loads several-fold.
-__device__ __forceinline__ void dma16(const char* base /*uniform*/, uint32_t voff, uint32_t lds_wave_base /*uniform*/) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_wave_base) : "memory");
-}
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
-}
-// Make a precomputed value opaque so that the compiler keeps it in a register instead of recomputing it in the loop.
-__device__ __forceinline__ uint32_t pin(uint32_t v) { asm volatile("" : "+v"(v)); return v; }
-
 // Byte offset, relative to the tile's corner element, of load i (0..LOADS_PER_THREAD-1) of this thread's share.
 //   KMAJ : corner = (row r0, column k0); rows clamped so that r0 + row <= r_max
 //   MNMAJ: corner = (k-row k0, column r0); k-rows clamped so that k0 + krow <= k_max
