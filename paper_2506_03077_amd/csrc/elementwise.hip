@@ -133,6 +133,95 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_k(const DN* __restrict__ dnor
   }
 }
 
+// Vectorised form for d % 8 == 0, d <= 4096: one wave per row, 8 elements (128 or 256 bits) per lane per access;
+// a workgroup of 4 waves takes RB rows (2 per wave), each wave keeps its share of dg in registers across its rows
+// and the four waves' shares meet in LDS in a fixed order.  Same arithmetic and the same partial-sum layout as the
+// plain kernel above.
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
+  typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
+  const bf16x8_t a = *(const bf16x8_t*)p;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+  *(float4*)(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
+  typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
+  bf16x8_t a;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a[e] = (bf16_t)v[e];
+  *(bf16x8_t*)p = a;
+}
+constexpr int RV_MAX_IT = 8;    // 64 lanes x 8 elements x 8 = 4096 columns (4 x d floats of LDS stay under 64 KiB)
+template <typename T, typename XT, typename RT, typename DN>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_vec_k(const DN* __restrict__ dnorm, const XT* __restrict__ xin,
+                                                         const T* __restrict__ g, const float* __restrict__ rstd,
+                                                         const RT* __restrict__ res, float* __restrict__ out_f32,
+                                                         T* __restrict__ out_t, float* __restrict__ partial,
+                                                         int rows, int d) {
+  extern __shared__ float sdg[];   // [4][d]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row0 = (int64_t)blockIdx.x * RB;
+  const int n_it = (d + 511) / 512;
+  float dg[RV_MAX_IT][8];
+#pragma unroll
+  for (int it = 0; it < RV_MAX_IT; ++it)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dg[it][e] = 0.f;
+  for (int r = wave; r < RB; r += 4) {
+    const int64_t row = row0 + r;
+    if (row >= rows) break;
+    const float rs = rstd[row];
+    float dot = 0.f;
+#pragma unroll
+    for (int it = 0; it < RV_MAX_IT; ++it) {
+      const int j = it * 512 + lane * 8;
+      if (it < n_it && j < d) {
+        float dn[8], gv[8], xv[8];
+        load8(dnorm + row * d + j, dn); load8(g + j, gv); load8(xin + row * d + j, xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dot += dn[e] * gv[e] * xv[e];
+      }
+    }
+    dot = wave_sum(dot);
+    const float coef = rs * rs * rs * dot / (float)d;
+#pragma unroll
+    for (int it = 0; it < RV_MAX_IT; ++it) {
+      const int j = it * 512 + lane * 8;
+      if (it < n_it && j < d) {
+        float dn[8], gv[8], xv[8], rv[8], o[8];
+        load8(dnorm + row * d + j, dn); load8(g + j, gv); load8(xin + row * d + j, xv);
+        if (res) load8(res + row * d + j, rv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          dg[it][e] += dn[e] * xv[e] * rs;
+          o[e] = (res ? rv[e] : 0.f) + dn[e] * gv[e] * rs - xv[e] * coef;
+        }
+        if (out_f32) store8(out_f32 + row * d + j, o);
+        if (out_t) store8(out_t + row * d + j, o);
+      }
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < RV_MAX_IT; ++it) {
+    const int j = it * 512 + lane * 8;
+    if (it < n_it && j < d) store8(sdg + (int64_t)wave * d + j, dg[it]);
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < d; j += blockDim.x)
+    partial[(int64_t)blockIdx.x * d + j] = (sdg[j] + sdg[d + j]) + (sdg[2 * d + j] + sdg[3 * d + j]);
+}
+static bool rmsnorm_bwd_vec_ok(int d, const void* a, const void* b, const void* c, const void* e, const void* f, const void* h) {
+  auto al = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  return d % 8 == 0 && d <= 512 * RV_MAX_IT && al(a) && al(b) && al(c) && al(e) && al(f) && al(h);
+}
+
 // dg[j] += sum_b partial[b][j]: 64 columns per workgroup, the partial rows dealt to 4 waves, fixed summation order.
 __global__ __launch_bounds__(256) void colsum_accum_k(const float* __restrict__ partial, float* __restrict__ dg, int nblk, int d) {
   __shared__ float red[4][64];
@@ -152,9 +241,17 @@ hipError_t rmsnorm_bwd(int dt, const float* dnorm, const void* xin, bool x_is_f3
                        float* dg, float* partial, int rows, int d, hipStream_t st) {
   if (rows == 0) return hipSuccess;
   const int nblk = (int)cdiv(rows, RB);
-#define RB_LAUNCH(T, XT, RT)                                                                             \
-  rmsnorm_bwd_k<T, XT, RT><<<nblk, 256, 0, st>>>(dnorm, (const XT*)xin, (const T*)g, rstd, (const RT*)res, \
-                                                 out_f32, (T*)out_t, partial, rows, d)
+  const bool vec = rmsnorm_bwd_vec_ok(d, dnorm, xin, g, res, out_f32, out_t);
+  const size_t shm = (size_t)4 * d * sizeof(float);
+#define RB_LAUNCH(T, XT, RT)                                                                                     \
+  do {                                                                                                           \
+    if (vec)                                                                                                     \
+      rmsnorm_bwd_vec_k<T, XT, RT, float><<<nblk, 256, shm, st>>>(dnorm, (const XT*)xin, (const T*)g, rstd,      \
+                                                                  (const RT*)res, out_f32, (T*)out_t, partial, rows, d); \
+    else                                                                                                         \
+      rmsnorm_bwd_k<T, XT, RT><<<nblk, 256, 0, st>>>(dnorm, (const XT*)xin, (const T*)g, rstd, (const RT*)res,   \
+                                                     out_f32, (T*)out_t, partial, rows, d);                      \
+  } while (0)
   DISPATCH_DT(dt, T, {
     if (x_is_f32 && res_is_f32) RB_LAUNCH(T, float, float);
     else if (x_is_f32) RB_LAUNCH(T, float, T);
@@ -174,8 +271,16 @@ hipError_t rmsnorm_bwd_plain(int dt, const void* dy, const void* x, const void* 
                              float* dg, float* partial, int rows, int d, hipStream_t st) {
   if (rows == 0) return hipSuccess;
   const int nblk = (int)cdiv(rows, RB);
-  DISPATCH_DT(dt, T, (rmsnorm_bwd_k<T, T, T, T><<<nblk, 256, 0, st>>>((const T*)dy, (const T*)x, (const T*)g, rstd,
-                                                                     (const T*)nullptr, nullptr, (T*)dx, partial, rows, d)));
+  const bool vec = rmsnorm_bwd_vec_ok(d, dy, x, g, nullptr, nullptr, dx);
+  const size_t shm = (size_t)4 * d * sizeof(float);
+  DISPATCH_DT(dt, T, {
+    if (vec)
+      rmsnorm_bwd_vec_k<T, T, T, T><<<nblk, 256, shm, st>>>((const T*)dy, (const T*)x, (const T*)g, rstd, (const T*)nullptr,
+                                                            nullptr, (T*)dx, partial, rows, d);
+    else
+      rmsnorm_bwd_k<T, T, T, T><<<nblk, 256, 0, st>>>((const T*)dy, (const T*)x, (const T*)g, rstd, (const T*)nullptr,
+                                                      nullptr, (T*)dx, partial, rows, d);
+  });
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   colsum_accum_k<<<(unsigned)cdiv(d, 64), 256, 0, st>>>(partial, dg, nblk, d);
