@@ -101,7 +101,7 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   w.rstd1 = cv.take<float>(cm);
   w.rstd2 = cv.take<float>(cm);
   w.lse = cv.take<float>(cm * c->n_q_heads);
-  w.delta = cv.take<float>(cm * c->n_q_heads);
+  w.delta = cv.take<float>(2 * cm * c->n_q_heads);
   w.partial = cv.take<float>(rmsnorm_bwd_partial_floats((int)cm, (int)d));
   w.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, (int)std::max(d, qd)) : 0;
   w.gemm_scratch = (float*)cv.take_bytes(w.gemm_scratch_bytes);
@@ -417,7 +417,7 @@ static int32_t check_attn_cfg(const sbp_attn_cfg* c) {
 
 size_t streambp_attn_workspace_bytes(const sbp_attn_cfg* cfg) {
   if (check_attn_cfg(cfg) != SBP_OK) return 0;
-  return align_up((size_t)std::max(cfg->q_len, 1) * cfg->n_q_heads * sizeof(float), 256);
+  return align_up((size_t)2 * std::max(cfg->q_len, 1) * cfg->n_q_heads * sizeof(float), 256);
 }
 
 int32_t streambp_attn_chunk_forward(const sbp_attn_cfg* c, const void* q, const void* k, const void* v, void* o,

@@ -458,12 +458,12 @@ constexpr int KV_STAGES = 3;
 
 __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                                   const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
-                                                                  const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                  const float* __restrict__ lse2, const float* __restrict__ delta,
                                                                   float* __restrict__ dk, float* __restrict__ dv, int Hq, int Hkv,
                                                                   int q_start, int c, float scale) {
   __shared__ __attribute__((aligned(1024))) char sQD[KV_STAGES][2][TILE64_BYTES];   // [stage][Q | dO]
   __shared__ __attribute__((aligned(16))) bf16x8 sP[2][4][4][64];   // [tile parity][key block][query block * 2 + k16 step][lane]
-  __shared__ __attribute__((aligned(16))) float sL[KV_STAGES][QT];  // log-sum-exp of the tile's queries
+  __shared__ __attribute__((aligned(16))) float sL[KV_STAGES][QT];  // log2-domain log-sum-exp of the tile's queries
   __shared__ __attribute__((aligned(16))) float sDl[KV_STAGES][QT]; // delta of the tile's queries
 
   const int G = Hq / Hkv;
@@ -477,6 +477,17 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
   const int key_row = min(my_key, n_total - 1);
   const int64_t kv_stride = (int64_t)Hkv * DH;
   const int64_t q_stride = (int64_t)Hq * DH;
+
+  // Fragment addresses: one set reaches 64 KiB (stages 0 and 1), a second one stage 2.  Role P reads Q row-wise and
+  // dO transposed, role S the other way round; only the half of each set that the role uses stays live.
+  const uint32_t lds0 = lds_addr(&sQD[0][0][0]);
+  const FragPre f0 = frag_pre(lds0 + (role_p ? 0 : TILE64_BYTES));                 // row-wise operand: Q (P) / dO (S)
+  const FragPre g0 = frag_pre(lds0 + (role_p ? TILE64_BYTES : 0));                 // transposed operand: dO (P) / Q (S)
+  const FragPre f2 = frag_pre(lds0 + 2 * 2 * TILE64_BYTES + (role_p ? 0 : TILE64_BYTES));
+  const FragPre g2 = frag_pre(lds0 + 2 * 2 * TILE64_BYTES + (role_p ? TILE64_BYTES : 0));
+  const TileLoad<KV_THREADS> tl = tile_load_pre<KV_THREADS>(q_stride);
+  const uint32_t sp_lane = pin(lds_addr(&sP[0][kb][0][lane]));                      // + parity * 8192 + (b * 2 + ks) * 1024
+  const uint32_t stat_lane = pin(lds_addr(role_p ? &sL[0][4 * half] : &sDl[0][4 * half]));   // + stage * 256 + (b * 32 + 8 a) * 4
 
   bf16x8 breg[8];   // B operand of the first product: K rows (role P) or V rows (role S) of my key
   {
@@ -496,113 +507,117 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
 
   auto issue = [&](int it, int stage) {
     const int qt = qt_first + it / G, hh = kvh * G + it % G;
-    dma_tile64<KV_THREADS>(q + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQD[stage][0]);
-    dma_tile64<KV_THREADS>(d_o + (int64_t)hh * DH, q_stride, qt * QT, c - 1, sQD[stage][1]);
+    const int64_t corner = (int64_t)qt * QT * q_stride + (int64_t)hh * DH;
+    dma_tile64(tl, q + corner, q_stride, c - qt * QT, lds0 + (uint32_t)(stage * 2 * TILE64_BYTES));
+    dma_tile64(tl, d_o + corner, q_stride, c - qt * QT, lds0 + (uint32_t)((stage * 2 + 1) * TILE64_BYTES));
     if (wave < 2) {   // 64 log-sum-exp values (wave 0) and 64 deltas (wave 1), 4 B per lane, also direct to LDS
       const int row = min(qt * QT + lane, c - 1);
-      const float* src = (wave == 0 ? lse : delta) + (int64_t)hh * c + row;
+      const float* src = (wave == 0 ? lse2 : delta) + (int64_t)hh * c + row;
       __builtin_amdgcn_global_load_lds(src, LDS_AS(wave == 0 ? &sL[stage][0] : &sDl[stage][0]), 4, 0, 0);
     }
   };
   // One 64-query tile = two 32-query blocks.  `active`: the wave has a valid key and some query of the tile is
   // at or after its first key (the same answer for both waves of a key block).
   auto tile_active = [&](int qbase) { return kw0 < n_total && q_start + min(qbase + QT, c) - 1 >= kw0; };
+  auto lds_f4 = [](uint32_t addr) { return *(const float4*)(__attribute__((address_space(3))) const char*)(uintptr_t)addr; };
 
-  auto p_step = [&](int it, int stage, int par) {
+  auto p_step = [&](int it, auto stage_c, int par) {
+    constexpr int stage = decltype(stage_c)::value;
+    constexpr uint32_t so = (stage & 1) * 2 * TILE64_BYTES;        // offset of the stage from its address set
+    const FragPre& fr = stage < 2 ? f0 : f2;
+    const FragPre& gt = stage < 2 ? g0 : g2;
     const int qbase = (qt_first + it / G) * QT;
     if (!tile_active(qbase)) return;
-    const char* sQ = sQD[stage][0];
-    const char* sD = sQD[stage][1];
     const bool diag = (q_start + qbase < kw0 + 31) || (qbase + QT > c);   // some pair masked, or ragged query tile
-    f32x16 t[2];
+    const uint32_t sp = sp_lane + (uint32_t)par * (uint32_t)sizeof(sP[0]);
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      t[b] = zero16();
+    for (int b = 0; b < 2; ++b) {      // one 32-query block at a time: fewer live registers
+      f32x16 t = zero16();
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) t[b] = MFMA(frag_rows(sQ, b * 32, ks), breg[ks], t[b]);
-    }
-    // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
-    bf16x8 pb[4];
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
+      for (int ks = 0; ks < 8; ++ks) t = MFMA(lds_b128(fr.rows[ks] + so + b * 32 * ROW_BYTES), breg[ks], t);
+      // accumulator: column = my key, rows = queries qbase + b*32 + acc_row(r, half)
       if (diag) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int qi = qbase + b * 32 + acc_row(r, half);
-          if (qi >= c || my_key > q_start + qi) t[b][r] = -INFINITY;      // exp2(-inf) = 0
+          if (qi >= c || my_key > q_start + qi) t[r] = -INFINITY;      // exp2(-inf) = 0
         }
       }
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
-        const float4 l4 = *(const float4*)&sL[stage][b * 32 + 8 * a + 4 * half];
+        const float4 l4 = lds_f4(stat_lane + stage * QT * 4 + (b * 32 + 8 * a) * 4);
         const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          t[b][4 * a + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[b][4 * a + e], sl, -lv[e] * LOG2E));
+        for (int e = 0; e < 4; ++e) t[4 * a + e] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[4 * a + e], sl, -lv[e]));
       }
+      bf16x8 pb[2];
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        pb[b * 2 + ks] = pack8(t[b], ks);
-        sP[par][kb][b * 2 + ks][lane] = pb[b * 2 + ks];
+        pb[ks] = pack8(t, ks);
+        *(bf16x8*)(__attribute__((address_space(3))) char*)(uintptr_t)(sp + (b * 2 + ks) * 1024) = pb[ks];
       }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[i] = MFMA(lds_tr(gt.tr[i * 2] + so + (b * 32 + ks * 16) * ROW_BYTES, gt.tr[i * 2 + 1] + so + (b * 32 + ks * 16) * ROW_BYTES),
+                        pb[ks], acc[i]);
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sD, j * 16, i * 32), pb[j], acc[i]);
   };
 
-  auto s_step = [&](int it, int stage, int par) {
+  auto s_step = [&](int it, auto stage_c, int par) {
+    constexpr int stage = decltype(stage_c)::value;
+    constexpr uint32_t so = (stage & 1) * 2 * TILE64_BYTES;
+    const FragPre& fr = stage < 2 ? f0 : f2;
+    const FragPre& gt = stage < 2 ? g0 : g2;
     const int qbase = (qt_first + it / G) * QT;
     if (!tile_active(qbase)) return;
-    const char* sQ = sQD[stage][0];
-    const char* sD = sQD[stage][1];
-    f32x16 t[2];
+    const uint32_t sp = sp_lane + (uint32_t)par * (uint32_t)sizeof(sP[0]);
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      t[b] = zero16();
+      f32x16 t = zero16();
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) t[b] = MFMA(frag_rows(sD, b * 32, ks), breg[ks], t[b]);
-    }
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      float dl[16];
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const float4 d4 = *(const float4*)&sDl[stage][b * 32 + 8 * a + 4 * half];
-        dl[4 * a + 0] = d4.x; dl[4 * a + 1] = d4.y; dl[4 * a + 2] = d4.z; dl[4 * a + 3] = d4.w;
-      }
+      for (int ks = 0; ks < 8; ++ks) t = MFMA(lds_b128(fr.rows[ks] + so + b * 32 * ROW_BYTES), breg[ks], t);
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8 p8 = sP[par][kb][b * 2 + ks][lane];
+        const float4 d0 = lds_f4(stat_lane + stage * QT * 4 + (b * 32 + 16 * ks) * 4);
+        const float4 d1 = lds_f4(stat_lane + stage * QT * 4 + (b * 32 + 16 * ks + 8) * 4);
+        const float dl[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+        const bf16x8 p8 = lds_b128(sp + (b * 2 + ks) * 1024);
 #pragma unroll
         for (int j = 0; j < 8; ++j)     // dS (the softmax scale is applied once at the end)
-          t[b][8 * ks + j] = (float)p8[j] * (t[b][8 * ks + j] - dl[8 * ks + j]);
-        const bf16x8 db = pack8(t[b], ks);
+          t[8 * ks + j] = (float)p8[j] * (t[8 * ks + j] - dl[j]);
+        const bf16x8 db = pack8(t, ks);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = MFMA(frag_cols_tr(sQ, b * 32 + ks * 16, i * 32), db, acc[i]);
+        for (int i = 0; i < 4; ++i)
+          acc[i] = MFMA(lds_tr(gt.tr[i * 2] + so + (b * 32 + ks * 16) * ROW_BYTES, gt.tr[i * 2 + 1] + so + (b * 32 + ks * 16) * ROW_BYTES), db, acc[i]);
       }
     }
   };
 
   // Step j: tile j+1 goes in flight, role P takes tile j, role S takes tile j-1.  The barrier at the top says:
   // tile j has landed for everyone, P of tile j-1 is written, and the stage and the P slot about to be
-  // overwritten (those of tile j-2) are no longer read.
+  // overwritten (those of tile j-2) are no longer read.  Tile j lives in stage j % 3; the loop is unrolled by three
+  // so that every stage offset is an immediate.
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  using S2 = std::integral_constant<int, 2>;
+  auto body = [&](int j, auto st_p, auto st_s, int st_next) {
+    WAIT_VM0();
+    __syncthreads();
+    if (j + 1 < n_iter) issue(j + 1, st_next);
+    if (role_p) {
+      if (j < n_iter) p_step(j, st_p, j & 1);
+    } else {
+      if (j > 0) s_step(j - 1, st_s, (j - 1) & 1);
+    }
+  };
   if (n_iter > 0) {
     issue(0, 0);
-    int st_next = 1, st_p = 0, st_s = KV_STAGES - 1;   // stages of tiles j+1, j, j-1
-    for (int j = 0; j <= n_iter; ++j) {
-      WAIT_VM0();
-      __syncthreads();
-      if (j + 1 < n_iter) issue(j + 1, st_next);
-      if (role_p) {
-        if (j < n_iter) p_step(j, st_p, j & 1);
-      } else {
-        if (j > 0) s_step(j - 1, st_s, (j - 1) & 1);
-      }
-      st_s = st_p;
-      st_p = st_next;
-      st_next = st_next + 1 == KV_STAGES ? 0 : st_next + 1;
+    for (int j = 0; j <= n_iter; j += 3) {
+      body(j, S0{}, S2{}, 1);
+      if (j + 1 <= n_iter) body(j + 1, S1{}, S0{}, 2);
+      if (j + 2 <= n_iter) body(j + 2, S2{}, S1{}, 0);
     }
   }
 
@@ -622,8 +637,11 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
 }
 
 // delta[h, t] = sum_j d_o[t,h,j] * o[t,h,j]  (one wave per (t, h))
+// also lse2[h, t] = lse[h, t] * log2(e), the form the dK/dV kernel's exp2 wants (one multiply per (t, h) here
+// instead of one per score there)
 __global__ __launch_bounds__(256) void attn_delta_mfma_k(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
-                                                         float* __restrict__ delta, int Hq, int c) {
+                                                         const float* __restrict__ lse, float* __restrict__ delta,
+                                                         float* __restrict__ lse2, int Hq, int c) {
   const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);      // t * Hq + h
   if (pair >= (int64_t)c * Hq) return;
   const int lane = threadIdx.x & 63;
@@ -631,7 +649,10 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_k(const bf16_t* __restric
   const int64_t base = pair * DH + lane * 2;
   float s = (float)o[base] * (float)d_o[base] + (float)o[base + 1] * (float)d_o[base + 1];
   s = wave_sum(s);
-  if (lane == 0) delta[(int64_t)h * c + t] = s;
+  if (lane == 0) {
+    delta[(int64_t)h * c + t] = s;
+    lse2[(int64_t)h * c + t] = lse[(int64_t)h * c + t] * LOG2E;
+  }
 }
 
 bool attn_mfma_eligible(int dt, int dh, int Hq, int Hkv) { return dt == DT_BF16 && dh == DH && Hq % Hkv == 0; }
@@ -656,13 +677,15 @@ hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st) {
       !aligned16(a.dk) || !aligned16(a.dv))
     return attn_backward_generic(a, st);
   const int64_t pairs = (int64_t)a.q_len * a.Hq;
-  attn_delta_mfma_k<<<(unsigned)cdiv(pairs, 4), 256, 0, st>>>((const bf16_t*)a.o, (const bf16_t*)a.d_o, a.delta, a.Hq, a.q_len);
+  float* lse2 = a.delta + pairs;   // second half of the [2, Hq, c] scratch
+  attn_delta_mfma_k<<<(unsigned)cdiv(pairs, 4), 256, 0, st>>>((const bf16_t*)a.o, (const bf16_t*)a.d_o, a.lse, a.delta, lse2, a.Hq,
+                                                              a.q_len);
   dim3 gq((unsigned)cdiv(a.q_len, TQ), a.Hq);
   attn_bwd_dq_mfma_k<<<gq, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
                                                 a.lse, a.delta, (bf16_t*)a.dq, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
   dim3 gk((unsigned)cdiv(a.q_start + a.q_len, KV_TILE), a.Hkv);
   attn_bwd_dkv_mfma_k<<<gk, KV_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
-                                                 a.lse, a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
+                                                 lse2, a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
   return hipGetLastError();
 }
 

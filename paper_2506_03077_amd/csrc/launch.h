@@ -88,7 +88,7 @@ struct AttnArgs {
   const void *q, *k, *v;   // q [c,Hq,dh]; k,v [>=s+c,Hkv,dh]
   void* o; float* lse;     // o [c,Hq,dh]; lse [Hq,c]
   const void* d_o; void* dq; float *dk, *dv;
-  float* delta;            // [Hq,c] scratch (backward)
+  float* delta;            // [2,Hq,c] scratch (backward): delta, then the log2-domain log-sum-exp
 };
 hipError_t attn_forward(const AttnArgs& a, hipStream_t st);
 hipError_t attn_backward(const AttnArgs& a, hipStream_t st);
