@@ -312,9 +312,14 @@ static int32_t check_head_cfg(const sbp_head_cfg* c) {
   return SBP_OK;
 }
 
+// The weight gradient of the head is accumulated once per HEAD_DW_GROUP chunks: dz and the gathered h rows of that
+// many chunks stay alive and one GEMM with a segmented reduction adds them into dW, so the 8 bytes per element of
+// read-modify-write traffic on dW (the largest tensor of the path) are paid once per group instead of once per
+// chunk.  The fp32 logits - the dominant term - still exist for one chunk only.
+constexpr int HEAD_DW_GROUP = 2;
 struct HeadWs {
-  float* z; void* dz; float *row_loss, *seq_weight, *ell;
-  int32_t *index, *chunk_rows; void *hc, *dhc;   // active-row compaction: row list, rows per chunk, gathered h / dh rows
+  float* z; void* dz[HEAD_DW_GROUP]; float *row_loss, *seq_weight, *ell;
+  int32_t *index, *chunk_rows; void *hc[HEAD_DW_GROUP], *dhc;   // active-row compaction: row list, rows per chunk, gathered h / dh rows
   float* gemm_scratch; size_t gemm_scratch_bytes; size_t bytes;
 };
 static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
@@ -323,13 +328,13 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   Carver cv(ws);
   HeadWs h;
   h.z = cv.take<float>(cm * c->vocab);
-  h.dz = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
+  for (int g = 0; g < HEAD_DW_GROUP; ++g) h.dz[g] = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
   h.row_loss = cv.take<float>(cm);
   h.seq_weight = cv.take<float>(c->batch);
   h.ell = cv.take<float>(1);
   h.index = cv.take<int32_t>((size_t)rows);
   h.chunk_rows = cv.take<int32_t>((size_t)cdiv(rows, (int64_t)cm));
-  h.hc = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
+  for (int g = 0; g < HEAD_DW_GROUP; ++g) h.hc[g] = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
   h.dhc = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
   h.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, c->hidden) : 0;
   h.gemm_scratch = (float*)cv.take_bytes(h.gemm_scratch_bytes);
@@ -373,16 +378,20 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
   const int n_chunks = (int)cdiv(rows, (int64_t)cm);
   HIPCHK(compact_active(targets, rows, cm, s.index, s.chunk_rows, n_chunks, st));
   HIPCHK(fill_zero(dh, (size_t)rows * d * es, st));          // ignored rows of dh: exact zeros
+  GemmArgs pending[HEAD_DW_GROUP];
+  int n_pending = 0;
   for (int ci = 0; ci < n_chunks; ++ci) {
     const int32_t* idx = s.index + (size_t)ci * cm;
     const int* n_dev = s.chunk_rows + ci;
     const int n = (int)std::min<int64_t>(cm, rows - (int64_t)ci * cm);      // upper bound of the chunk's rows
-    HIPCHK(gather_rows(dt, h, idx, n_dev, s.hc, n, d, st));
-    GemmArgs gz = fwd_gemm(s.hc, w, s.z, n, V, d, dt, DT_F32);
+    void* hc = s.hc[n_pending];
+    void* dz = s.dz[n_pending];
+    HIPCHK(gather_rows(dt, h, idx, n_dev, hc, n, d, st));
+    GemmArgs gz = fwd_gemm(hc, w, s.z, n, V, d, dt, DT_F32);
     gz.rows_dev = n_dev;
     HIPCHK(gemm(gz, st));
     HeadRowArgs a{};
-    a.dt = dt; a.objective = c->objective; a.z = s.z; a.dz = s.dz; a.targets = targets;
+    a.dt = dt; a.objective = c->objective; a.z = s.z; a.dz = dz; a.targets = targets;
     a.old_logp = old_logp; a.ref_logp = ref_logp;
     a.advantages = advantages; a.seq_weight = s.seq_weight; a.row0 = 0; a.row_index = idx; a.rows_dev = n_dev;
     a.rows = n; a.V = V; a.T = c->seq_len;
@@ -390,13 +399,16 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
     a.row_loss = s.row_loss;
     HIPCHK(head_rows(a, st));
     HIPCHK(reduce_add(s.row_loss, n, c->objective == SBP_OBJ_DPO ? s.ell : loss, st, n_dev));
-    GemmArgs gh = dx_gemm(s.dz, w, s.dhc, n, V, d, dt, dt, false);
+    GemmArgs gh = dx_gemm(dz, w, s.dhc, n, V, d, dt, dt, false);
     gh.rows_dev = n_dev;
     HIPCHK(gemm(gh, st));
     HIPCHK(scatter_rows(dt, s.dhc, idx, n_dev, dh, n, d, st));
-    GemmArgs gw = dw_gemm(s.dz, s.hc, dw, n, V, d, dt);
-    gw.rows_dev = n_dev;
-    HIPCHK(gemm(gw, st));
+    pending[n_pending] = dw_gemm(dz, hc, dw, n, V, d, dt);
+    pending[n_pending].rows_dev = n_dev;
+    if (++n_pending == HEAD_DW_GROUP || ci + 1 == n_chunks) {
+      HIPCHK(gemm_batch(pending, n_pending, st));
+      n_pending = 0;
+    }
   }
   if (c->objective == SBP_OBJ_DPO)
     HIPCHK(dpo_finish(dt, s.ell, c->kl_beta, dh, rows * d, dw, (int64_t)V * d, loss, st));

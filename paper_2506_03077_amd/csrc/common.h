@@ -63,6 +63,12 @@ __device__ __forceinline__ void dma16(const char* base /*uniform*/, uint32_t vof
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
+// A pointer the compiler cannot prove wave-uniform (e.g. picked from an array by a loop index), moved to SGPRs.
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+  const uint64_t v = (uint64_t)(uintptr_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
 // Make a precomputed value opaque so that the compiler keeps it in a register instead of recomputing it in a loop.
 __device__ __forceinline__ uint32_t pin(uint32_t v) { asm volatile("" : "+v"(v)); return v; }
 

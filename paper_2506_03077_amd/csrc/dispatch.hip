@@ -11,6 +11,8 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st);
 bool gemm_mfma_eligible(const GemmArgs& g);
 bool gemm_mfma_group_eligible(const GemmArgs* gs, int n);
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st);
+bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n);
+hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st);
 hipError_t attn_forward_generic(const AttnArgs& a, hipStream_t st);
 hipError_t attn_backward_generic(const AttnArgs& a, hipStream_t st);
 hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st);
@@ -56,6 +58,7 @@ hipError_t gemm(const GemmArgs& g, hipStream_t st) {
   return gemm_generic(g, st);
 }
 hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st) {
+  if (!g_force_generic_gemm && gemm_mfma_seg_eligible(gs, n)) return gemm_mfma_seg(gs, n, st);   // same C: one pass over it
   if (!g_force_generic_gemm && gemm_mfma_group_eligible(gs, n)) {
     return gemm_mfma_group(gs, n, st);
   }

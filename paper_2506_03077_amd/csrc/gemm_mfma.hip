@@ -145,16 +145,26 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int n_tiles) {
 // (advanced with scalar adds) plus per-lane offsets computed once, LDS fragment addresses are computed once per
 // stage and reached with immediate offsets, and the two LDS stages are unrolled.  Only the last K step of a ragged
 // reduction (weight-gradient form) takes a slower path with clamped addresses and zeroed fragments.
+// The reduction may come in several segments (operand pairs of the same shape and leading dimensions whose products
+// are summed into the same output tile): one accumulator, one epilogue.
+constexpr int MAX_SEG = 4;
+struct KSegments {
+  const bf16_t* A[MAX_SEG];
+  const bf16_t* B[MAX_SEG];
+  int K[MAX_SEG];         // reduction length of the segment (clamp for the loads)
+  int k_begin[MAX_SEG];   // range of the segment this tile works on
+  int k_end[MAX_SEG];
+  int n;
+};
+
 template <bool TA, bool TB, int MODE>
-__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* __restrict__ Cv,
-                                          int M, int N, int K, int64_t lda, int64_t ldb, int64_t ldc, int k_begin, int k_end,
-                                          int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES]) {
+__device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restrict__ Cv, int M, int N, int64_t lda,
+                                          int64_t ldb, int64_t ldc, int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES]) {
   static_assert(NSTAGE == 2, "the main loop is unrolled over two LDS stages");
   constexpr bool AMN = TA, BMN = !TB;     // operand kept reduction-major in LDS (B stored [N,K] is the K-contiguous case)
   const int m0 = tm * BM, n0 = tn * BN;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm0 = (wave / NWAVE_N) * WTM, wn0 = (wave % NWAVE_N) * WTN;
-  const int nk = (k_end - k_begin + BK - 1) / BK;
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -164,9 +174,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // ---- global side: uniform 64-bit bases that walk along K + per-lane byte offsets (rows clamped once)
-  const char* gA = (const char*)(A + (AMN ? (int64_t)k_begin * lda + m0 : (int64_t)m0 * lda + k_begin));
-  const char* gB = (const char*)(B + (BMN ? (int64_t)k_begin * ldb + n0 : (int64_t)n0 * ldb + k_begin));
+  // ---- global side: per-lane byte offsets (rows clamped once); the uniform 64-bit bases walk along K
   const int64_t stepA = (AMN ? (int64_t)BK * lda : (int64_t)BK) * 2, stepB = (BMN ? (int64_t)BK * ldb : (int64_t)BK) * 2;
   uint32_t offA[LOADS_PER_THREAD], offB[LOADS_PER_THREAD];
 #pragma unroll
@@ -176,25 +184,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
     offB[i] = pin(load_offset<BMN>(i, ldb, n0, N - 1, 0, 0x7fffffff));
   }
   const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_addr(&smem[0][0][0]) + (uint32_t)(threadIdx.x & ~63) * 16u);
-  auto issue = [&](int kt, int st) {
-    const char* a_base = gA + (int64_t)kt * stepA;
-    const char* b_base = gB + (int64_t)kt * stepB;
-    const uint32_t la = lds_wave + (uint32_t)(st * 2 * TILE_BYTES), lb = la + TILE_BYTES;
-    const int k0 = k_begin + kt * BK;
-    if ((AMN || BMN) && k0 + BK > K) {    // ragged last K step: clamp the k-rows (slow path, once per tile)
-#pragma unroll
-      for (int i = 0; i < LOADS_PER_THREAD; ++i) {
-        dma16(a_base, AMN ? load_offset<AMN>(i, lda, m0, M - 1, k0, K - 1) : offA[i], la + (uint32_t)(i * NTHREADS * 16));
-        dma16(b_base, BMN ? load_offset<BMN>(i, ldb, n0, N - 1, k0, K - 1) : offB[i], lb + (uint32_t)(i * NTHREADS * 16));
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < LOADS_PER_THREAD; ++i) {
-        dma16(a_base, offA[i], la + (uint32_t)(i * NTHREADS * 16));
-        dma16(b_base, offB[i], lb + (uint32_t)(i * NTHREADS * 16));
-      }
-    }
-  };
 
   // ---- LDS side: fragment addresses per stage, computed once
   constexpr int NA = AMN ? 2 * FM : BK / 16, NB = BMN ? 2 * FN : BK / 16;
@@ -255,17 +244,46 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, const bf
 
   // Two stages: at step kt wait for tile kt, barrier (every wave's share has landed and everyone is done reading
   // the other stage), refill the other stage with tile kt+1, compute.
-  if (nk > 0) issue(0, 0);
-  for (int kt = 0; kt < nk; kt += 2) {
-    WAIT_VMCNT(0);
-    __syncthreads();
-    if (kt + 1 < nk) issue(kt + 1, 1);
-    compute(0, k_end - (k_begin + kt * BK));
-    if (kt + 1 < nk) {
+#pragma unroll      // constant segment indices: the segment table stays in scalar registers
+  for (int sg = 0; sg < MAX_SEG; ++sg) {
+    if (sg >= segs.n) break;
+    const int K = segs.K[sg], k_begin = segs.k_begin[sg], k_end = segs.k_end[sg];
+    const int nk = (k_end - k_begin + BK - 1) / BK;
+    if (nk <= 0) continue;
+    const char* gA = uniform_ptr(segs.A[sg] + (AMN ? (int64_t)k_begin * lda + m0 : (int64_t)m0 * lda + k_begin));
+    const char* gB = uniform_ptr(segs.B[sg] + (BMN ? (int64_t)k_begin * ldb + n0 : (int64_t)n0 * ldb + k_begin));
+    auto issue = [&](int kt, int st) {
+      const char* a_base = gA + (int64_t)kt * stepA;
+      const char* b_base = gB + (int64_t)kt * stepB;
+      const uint32_t la = lds_wave + (uint32_t)(st * 2 * TILE_BYTES), lb = la + TILE_BYTES;
+      const int k0 = k_begin + kt * BK;
+      if ((AMN || BMN) && k0 + BK > K) {    // ragged last K step: clamp the k-rows (slow path, once per tile)
+#pragma unroll
+        for (int i = 0; i < LOADS_PER_THREAD; ++i) {
+          dma16(a_base, AMN ? load_offset<AMN>(i, lda, m0, M - 1, k0, K - 1) : offA[i], la + (uint32_t)(i * NTHREADS * 16));
+          dma16(b_base, BMN ? load_offset<BMN>(i, ldb, n0, N - 1, k0, K - 1) : offB[i], lb + (uint32_t)(i * NTHREADS * 16));
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < LOADS_PER_THREAD; ++i) {
+          dma16(a_base, offA[i], la + (uint32_t)(i * NTHREADS * 16));
+          dma16(b_base, offB[i], lb + (uint32_t)(i * NTHREADS * 16));
+        }
+      }
+    };
+    if (sg > 0) __syncthreads();     // everyone is done reading the stages of the previous segment
+    issue(0, 0);
+    for (int kt = 0; kt < nk; kt += 2) {
       WAIT_VMCNT(0);
       __syncthreads();
-      if (kt + 2 < nk) issue(kt + 2, 0);
-      compute(1, k_end - (k_begin + (kt + 1) * BK));
+      if (kt + 1 < nk) issue(kt + 1, 1);
+      compute(0, k_end - (k_begin + kt * BK));
+      if (kt + 1 < nk) {
+        WAIT_VMCNT(0);
+        __syncthreads();
+        if (kt + 2 < nk) issue(kt + 2, 0);
+        compute(1, k_end - (k_begin + (kt + 1) * BK));
+      }
     }
   }
 
@@ -310,7 +328,32 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
   const int k_begin = blockIdx.z * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
   if (k_end <= k_begin && MODE == 2) return;   // nothing to add
-  gemm_tile<TA, TB, MODE>(A, B, Cv, M, N, K, lda, ldb, ldc, k_begin, k_end, tm, tn, smem);
+  KSegments segs;
+  segs.n = 1; segs.A[0] = A; segs.B[0] = B; segs.K[0] = K; segs.k_begin[0] = k_begin; segs.k_end[0] = k_end;
+  gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem);
+}
+
+// Weight-gradient form with a segmented reduction: C += sum_s A_s^T B_s, every segment with its own run-time row
+// count.  One pass over C (one atomic add per element) for several chunks' worth of rows.
+struct SegLaunch { const bf16_t* A[MAX_SEG]; const bf16_t* B[MAX_SEG]; const int* rows_dev[MAX_SEG]; int K[MAX_SEG]; int n; };
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_seg_k(const SegLaunch sl, float* __restrict__ C, int M, int N, int64_t lda,
+                                                            int64_t ldb, int64_t ldc) {
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  int tm, tn;
+  band_coords((int)blockIdx.x, tiles_m, tiles_n, band_height(tiles_m, tiles_m * tiles_n, false), tm, tn);
+  KSegments segs;
+  segs.n = sl.n;
+  int total = 0;
+#pragma unroll
+  for (int s = 0; s < MAX_SEG; ++s) {
+    int K = 0;
+    if (s < sl.n) { K = sl.K[s]; if (sl.rows_dev[s]) K = min(K, max(0, *sl.rows_dev[s])); }
+    segs.A[s] = sl.A[s]; segs.B[s] = sl.B[s]; segs.K[s] = K; segs.k_begin[s] = 0; segs.k_end[s] = K;
+    total += K;
+  }
+  if (total == 0) return;   // nothing to add
+  gemm_tile<true, false, 2>(segs, C, M, N, lda, ldb, ldc, tm, tn, smem);
 }
 
 // Several independent GEMMs of one layout / output mode in a single launch: the tiles of all problems form one
@@ -335,7 +378,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_group_k(const GroupArgs ga
   const GroupProblem& g = ga.p[pi];
   int tm, tn;
   band_coords(id - g.tile_begin, g.tiles_m, g.tiles_n, band_height(g.tiles_m, g.tiles_m * g.tiles_n, MODE != 2), tm, tn);
-  gemm_tile<TA, TB, MODE>(g.A, g.B, g.C, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, 0, g.K, tm, tn, smem);
+  KSegments segs;
+  segs.n = 1; segs.A[0] = g.A; segs.B[0] = g.B; segs.K[0] = g.K; segs.k_begin[0] = 0; segs.k_end[0] = g.K;
+  gemm_tile<TA, TB, MODE>(segs, g.C, g.M, g.N, g.lda, g.ldb, g.ldc, tm, tn, smem);
 }
 
 // C (=|+=) sum_z partial[z] in a fixed order; OUT_BF16 rounds once at the end.
@@ -480,6 +525,34 @@ hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
   else GLAUNCH_LAYOUT(0);
 #undef GLAUNCH_LAYOUT
 #undef GLAUNCH
+  return hipGetLastError();
+}
+
+// Segmented weight-gradient launch: gs[0..n) are accumulate-form (TN, fp32 C +=) problems that share C, M, N and the
+// leading dimensions and differ in A, B, K and rows_dev.
+bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n) {
+  if (n < 2 || n > MAX_SEG) return false;
+  for (int i = 0; i < n; ++i) {
+    const GemmArgs& g = gs[i];
+    if (!gemm_mfma_eligible(g) || !g.ta || g.tb || !g.acc || g.out_dt != DT_F32) return false;
+    if (g.C != gs[0].C || g.M != gs[0].M || g.N != gs[0].N || g.lda != gs[0].lda || g.ldb != gs[0].ldb || g.ldc != gs[0].ldc) return false;
+  }
+  return true;
+}
+hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st) {
+  SegLaunch sl{};
+  sl.n = n;
+  double work = 0.0;
+  bool bounded = false;
+  for (int i = 0; i < n; ++i) {
+    sl.A[i] = (const bf16_t*)gs[i].A; sl.B[i] = (const bf16_t*)gs[i].B; sl.rows_dev[i] = gs[i].rows_dev; sl.K[i] = gs[i].K;
+    work += 2.0 * gs[i].M * gs[i].N * gs[i].K;
+    bounded = bounded || gs[i].rows_dev != nullptr;
+  }
+  const GemmArgs& g = gs[0];
+  const int tiles = (int)cdiv(g.M, BM) * (g.N / BN);
+  prof::Scope sc(prof::GEMM_SINGLE + 2 * 4 + 2, work, bounded, st);   // same kind as the single accumulate-form launch
+  gemm_mfma_seg_k<<<tiles, NTHREADS, 0, st>>>(sl, (float*)g.C, g.M, g.N, g.lda, g.ldb, g.ldc);
   return hipGetLastError();
 }
 
