@@ -103,7 +103,7 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   w.lse = cv.take<float>(cm * c->n_q_heads);
   w.delta = cv.take<float>(2 * cm * c->n_q_heads);
   w.partial = cv.take<float>(rmsnorm_bwd_partial_floats((int)cm, (int)d));
-  w.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, (int)std::max(d, qd)) : 0;
+  w.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, (int)std::max(d, qd), 4) : 0;
   w.gemm_scratch = (float*)cv.take_bytes(w.gemm_scratch_bytes);
   w.bytes = cv.off;
   return w;
@@ -336,7 +336,7 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   h.chunk_rows = cv.take<int32_t>((size_t)cdiv(rows, (int64_t)cm));
   for (int g = 0; g < HEAD_DW_GROUP; ++g) h.hc[g] = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
   h.dhc = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
-  h.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, c->hidden) : 0;
+  h.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, c->hidden, 4) : 0;
   h.gemm_scratch = (float*)cv.take_bytes(h.gemm_scratch_bytes);
   h.bytes = cv.off;
   return h;

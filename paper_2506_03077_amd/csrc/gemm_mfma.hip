@@ -120,11 +120,13 @@ __device__ __forceinline__ void band_coords(int id, int tiles_m, int tiles_n, in
 // group_m rows x run/group_m columns of tiles; the fabric traffic of that XCD is proportional to rows + columns,
 // so the block is made as square as the problem allows.  (Interleaved ids, used by the accumulate form, give
 // every XCD one row of each band and all columns; 8 rows per band suit that.)
+__device__ __forceinline__ int band_height_for_run(int tiles_m, int run) {
+  int h = (int)(sqrtf((float)max(1, run)) + 0.5f);
+  return max(1, min(h, min(tiles_m, 8)));
+}
 __device__ __forceinline__ int band_height(int tiles_m, int n_tiles, bool xcd_contiguous) {
   if (!xcd_contiguous) return 8;
-  const int run = max(1, n_tiles / 8);
-  int h = (int)(sqrtf((float)run) + 0.5f);
-  return max(1, min(h, min(tiles_m, 8)));
+  return band_height_for_run(tiles_m, n_tiles / 8);
 }
 // Hardware deals consecutive workgroups round-robin to the 8 XCDs (each with its own L2); undo that so each
 // XCD gets a contiguous run of tile ids.  Measured: +3-4% for the store-only forms; the accumulate form (atomic adds
@@ -313,19 +315,33 @@ template <bool TA, bool TB, int MODE>
 __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                         void* __restrict__ Cv, int M, int N, int K, int64_t lda,
                                                         int64_t ldb, int64_t ldc, int k_per_split,
-                                                        const int* __restrict__ rows_dev) {
+                                                        const int* __restrict__ rows_dev, int xcds_per_split) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
-  int tm, tn;
-  band_coords(MODE == 2 ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n), tiles_m, tiles_n,
-              band_height(tiles_m, tiles_m * tiles_n, MODE != 2), tm, tn);
-  if (MODE == 3) Cv = (float*)Cv + (int64_t)blockIdx.z * M * ldc;   // partial slices are laid out for the host-side M
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN, n_tiles = tiles_m * tiles_n;
+  int tm, tn, split = 0;
+  if (MODE == 3 && xcds_per_split > 0) {
+    // Split-K with each slice of the reduction pinned to its own group of XCDs (the grid is 1-D: n_tiles x splits
+    // workgroups, dealt round-robin to the 8 XCDs by the hardware).  Inside a group every XCD takes a contiguous
+    // run of the tile ids, so it touches only its slice of K of the operand panels of that run (measured: 12% less
+    // fabric traffic than with every XCD working on all slices of its tiles).
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int run = n_tiles / xcds_per_split;
+    split = xcd / xcds_per_split;
+    band_coords((xcd % xcds_per_split) * run + q, tiles_m, tiles_n, band_height_for_run(tiles_m, run), tm, tn);
+  } else if (MODE == 3) {
+    split = blockIdx.x / n_tiles;
+    band_coords(xcd_contiguous_id(blockIdx.x % n_tiles, n_tiles), tiles_m, tiles_n, band_height(tiles_m, n_tiles, true), tm, tn);
+  } else {
+    band_coords(MODE == 2 ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, n_tiles), tiles_m, tiles_n,
+                band_height(tiles_m, n_tiles, MODE != 2), tm, tn);
+  }
+  if (MODE == 3) Cv = (float*)Cv + (int64_t)split * M * ldc;   // partial slices are laid out for the host-side M
   if (rows_dev) {                     // run-time row count: rows are M (NT / NN) or the reduction K (dW form)
     const int rows = max(0, *rows_dev);
     if (TA) K = min(K, rows); else M = min(M, rows);
     if (!TA && tm * BM >= M) return;  // no valid row in this tile
   }
-  const int k_begin = blockIdx.z * k_per_split;
+  const int k_begin = split * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
   if (k_end <= k_begin && MODE == 2) return;   // nothing to add
   KSegments segs;
@@ -422,33 +438,42 @@ bool gemm_mfma_eligible(const GemmArgs& g) {
   return true;
 }
 
-constexpr int MAX_SPLITS = 4;
-// Split-K factor: fill the 256 CUs when the output has few tiles and K is long.
+constexpr int MAX_SPLITS = 8;
+// Split-K factor (a power of two <= 8) for outputs with too few tiles to fill the chip: the largest split that
+// still fits one round of 256 CUs and leaves every slice at least 8 K steps.  Splitting further does not reduce
+// the fabric traffic: an XCD runs 32 tiles at a time whatever the split, and those pull (rows + columns) operand
+// panels per K step.
 int gemm_mfma_splits(const GemmArgs& g) {
   const int64_t tiles = cdiv(g.M, BM) * (g.N / BN);
   const int k_tiles = (int)cdiv(g.K, BK);
   if (tiles >= 200 || k_tiles < 16 || (g.ta && g.rows_dev)) return 1;
-  int s = (int)std::min<int64_t>(256 / tiles, k_tiles / 8);   // largest split that still fits one round of 256 CUs
-  return std::max(1, std::min(s, MAX_SPLITS));
+  int s = 1;
+  while (s * 2 <= MAX_SPLITS && s * 2 * tiles <= 256 && k_tiles / (s * 2) >= 8) s *= 2;
+  return s;
 }
 
-size_t gemm_scratch_bytes(int max_m, int max_n) { return (size_t)MAX_SPLITS * max_m * max_n * sizeof(float); }
+size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits) {
+  return (size_t)std::min(max_splits, MAX_SPLITS) * max_m * max_n * sizeof(float);
+}
 
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const int tiles_m = (int)cdiv(g.M, BM), tiles_n = g.N / BN;
   int splits = gemm_mfma_splits(g);
-  if (splits > 1 && (g.scratch == nullptr || g.scratch_bytes < (size_t)splits * g.M * g.ldc * sizeof(float) || g.ldc != g.N))
-    splits = 1;
+  if (g.scratch == nullptr || g.ldc != g.N) splits = 1;
+  while (splits > 1 && g.scratch_bytes < (size_t)splits * g.M * g.ldc * sizeof(float)) splits /= 2;   // what the scratch holds
   int k_per_split = g.K;
+  int xcds_per_split = 0;
   if (splits > 1) {
     k_per_split = (int)(cdiv(cdiv(g.K, BK), splits) * BK);
-    splits = (int)cdiv(g.K, k_per_split);
+    if ((int)cdiv(g.K, k_per_split) != splits) splits = (int)cdiv(g.K, k_per_split);
+    if (8 % splits == 0 && (tiles_m * tiles_n) % (8 / splits) == 0) xcds_per_split = 8 / splits;
   }
-  dim3 grid(tiles_m * tiles_n, 1, splits);
+  dim3 grid(tiles_m * tiles_n * splits, 1, 1);
   const bf16_t* A = (const bf16_t*)g.A;
   const bf16_t* B = (const bf16_t*)g.B;
 #define LAUNCH(TA, TB, MODE, CPTR) \
-  gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split, g.rows_dev)
+  gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split, g.rows_dev, \
+                                                       xcds_per_split)
 #define LAUNCH_LAYOUT(MODE, CPTR)                       \
   do {                                                  \
     if (!g.ta && g.tb) LAUNCH(false, true, MODE, CPTR); \

@@ -25,7 +25,7 @@ struct GemmArgs {
   const int* rows_dev = nullptr;
 };
 // upper bound of the scratch a GEMM with M <= max_m rows and N <= max_n columns may use
-size_t gemm_scratch_bytes(int max_m, int max_n);
+size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits);
 hipError_t gemm(const GemmArgs& g, hipStream_t st);
 // n independent GEMMs (distinct outputs); one grouped launch when the MFMA kernel can take them all
 hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st);
