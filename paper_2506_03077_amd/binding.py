@@ -110,6 +110,9 @@ def lib():
         L.streambp_stack_backward.restype = i32
         L.streambp_stack_backward.argtypes = [C.POINTER(StackCfg), C.POINTER(LayerWeights), vp, vp, C.POINTER(vp), vp, vp, vp, vp,
                                               vp, C.POINTER(LayerGrads), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.streambp_debug_gemm_dw_segments.restype = C.c_int
+        L.streambp_debug_gemm_dw_segments.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(vp), C.POINTER(vp),
+                                                      C.POINTER(vp), vp, C.c_longlong, C.c_longlong, C.c_longlong, C.c_int, vp]
         L.streambp_debug_profile_begin.restype = C.c_int
         L.streambp_debug_profile_begin.argtypes = [C.c_int]
         L.streambp_debug_profile_end.restype = C.c_int
@@ -339,11 +342,26 @@ def debug_gemm(A, B, C_out, M, N, K, ta, tb, acc=False, scratch=None, stream=Non
     return rc
 
 
+def debug_gemm_dw_segments(As, Bs, C_out, M, N, Ks, rows_dev=None, stream=None):
+    """C[M,N] += sum_s As[s]^T Bs[s] (As[s] [K_s, M], Bs[s] [K_s, N]) through the library's batched dispatcher; rows_dev: optional
+    list of int32 device scalars (or None) limiting each segment's row count.  Returns 1 if one segmented MFMA launch did it."""
+    n = len(As)
+    Ka = (C.c_int * n)(*Ks)
+    Aa = (C.c_void_p * n)(*[_ptr(a) for a in As])
+    Ba = (C.c_void_p * n)(*[_ptr(b) for b in Bs])
+    Ra = (C.c_void_p * n)(*[(_ptr(r) if r is not None else None) for r in (rows_dev or [None] * n)])
+    rc = lib().streambp_debug_gemm_dw_segments(n, M, N, Ka, Aa, Ba, Ra, _ptr(C_out), As[0].stride(0), Bs[0].stride(0),
+                                               C_out.stride(0), _dt_code(As[0]), _stream(stream))
+    if rc < 0:
+        raise StreamBPError(rc, "debug_gemm_dw_segments launch failed")
+    return rc
+
+
 def _profile_kind_names():
     lay = (("false, true", "NT"), ("false, false", "NN"), ("true, false", "TN"))
     names = [f"gemm_mfma_k<{t}, {m}>" for t, _ in lay for m in range(4)]
     names += [f"gemm_mfma_group_k<{t}, {m}>" for t, _ in lay for m in range(4)]
-    names += ["gemm_generic_k", "attn_fwd (launch sequence)", "attn_bwd (delta + dq + dkv launch sequence)"]
+    names += ["gemm_generic_k", "attn_fwd (launch sequence)", "attn_bwd (delta + dq + dkv launch sequence)", "gemm_mfma_seg_k"]
     return tuple(names)
 
 

@@ -95,6 +95,23 @@ extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_d
   return e == hipSuccess ? (sbp::gemm_uses_mfma(g) ? 1 : 0) : -5;
 }
 
+// Weight-gradient form over several reduction segments through gemm_batch: C[M,N] += sum_s A_s^T B_s with
+// A_s [K_s, M], B_s [K_s, N] (row counts optionally limited by device integers).  Returns 1 if the segmented MFMA
+// kernel took it, 0 if it ran as separate launches.
+extern "C" int streambp_debug_gemm_dw_segments(int n, int M, int N, const int* K, const void* const* A, const void* const* B,
+                                               const int* const* rows_dev, float* C, long long lda, long long ldb,
+                                               long long ldc, int in_dt, void* stream) {
+  if (n < 1 || n > 8) return -2;
+  sbp::GemmArgs gs[8];
+  for (int i = 0; i < n; ++i) {
+    gs[i] = sbp::GemmArgs{A[i], B[i], C, M, N, K[i], lda, ldb, ldc, true, false, in_dt, sbp::DT_F32, true};
+    gs[i].rows_dev = rows_dev ? rows_dev[i] : nullptr;
+  }
+  const bool seg = !sbp::g_force_generic_gemm && sbp::gemm_mfma_seg_eligible(gs, n);
+  hipError_t e = sbp::gemm_batch(gs, n, (hipStream_t)stream);
+  return e == hipSuccess ? (seg ? 1 : 0) : -5;
+}
+
 // Per-launch timing with HIP events recorded on the launch stream around each GEMM kernel / attention launch
 // sequence.  begin: creates 2*max_records events and switches recording on.  end: synchronises the events and
 // returns per kind (see prof:: in launch.h; N_KIND entries) the launch count, the summed duration in ms, the

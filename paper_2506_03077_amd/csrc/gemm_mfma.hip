@@ -576,7 +576,7 @@ hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st) {
   }
   const GemmArgs& g = gs[0];
   const int tiles = (int)cdiv(g.M, BM) * (g.N / BN);
-  prof::Scope sc(prof::GEMM_SINGLE + 2 * 4 + 2, work, bounded, st);   // same kind as the single accumulate-form launch
+  prof::Scope sc(prof::GEMM_SEG, work, bounded, st);
   gemm_mfma_seg_k<<<tiles, NTHREADS, 0, st>>>(sl, (float*)g.C, g.M, g.N, g.lda, g.ldb, g.ldc);
   return hipGetLastError();
 }

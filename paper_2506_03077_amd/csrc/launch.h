@@ -38,7 +38,7 @@ void gemm_set_force_generic(bool on);
 namespace prof {
 // kinds 0..11: gemm_mfma_k<layout, mode> with layout NT=0, NN=1, TN=2 and mode 0..3; 12..23: the grouped kernel;
 // then the shape-agnostic GEMM and the attention forward / backward launch sequences
-enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, N_KIND = 27 };
+enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, GEMM_SEG = 27, N_KIND = 28 };
 struct Scope {
   hipStream_t st; bool active = false; int kind = 0; double work = 0; bool bounded = false; hipEvent_t e0{}, e1{};
   // bounded: `work` was computed from a host-side upper bound of a run-time row count

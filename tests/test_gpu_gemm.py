@@ -24,7 +24,7 @@ def run(M, N, K, ta, tb, out="f32", acc=False, seed=0, expect_mfma=None, dtype="
     want = opA @ opB + C0
     Cd = dev(C0, out) if acc else torch.full((M, N), float("nan"), device="cuda",
                                             dtype=torch.bfloat16 if out == "bf16" else torch.float32)
-    scratch = torch.empty(4 * M * N, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(8 * M * N, dtype=torch.float32, device="cuda")
     used = sb.debug_gemm(dev(A, dtype), dev(B, dtype), Cd, M, N, K, ta, tb, acc, scratch)
     torch.cuda.synchronize()
     if expect_mfma is not None:
@@ -63,6 +63,38 @@ def test_mfma_split_k_paths():
     run(300, 512, 4096, False, False, out="bf16", expect_mfma=True)
     run(512, 256, 4096, False, False, acc=True, expect_mfma=True)
     run(256, 256, 4000, True, False, acc=True, expect_mfma=True)     # ragged split
+
+
+def test_mfma_split_k_eight_ways_and_unaligned_groups():
+    run(256, 512, 8192, False, True, expect_mfma=True)                # 2 tiles, 128 K steps: 8 slices, one per XCD
+    run(256, 768, 8192, False, False, out="bf16", expect_mfma=True)   # 3 tiles x 8 slices
+    run(256, 768, 3072, False, False, expect_mfma=True, seed=3)       # 4 slices, 3 tiles: not a multiple of the XCD group
+    run(200, 1280, 2048, False, True, acc=True, expect_mfma=True, seed=4)   # ragged rows, 5 tiles x 4 slices
+
+
+def test_mfma_segmented_weight_gradient():
+    # C += sum_s A_s^T B_s in one launch; segments of different length, two of them cut short by a device row count
+    rng = np.random.default_rng(5)
+    M, N, Ks, limits = 512, 256, (300, 1000, 64, 128), (250, None, 0, None)
+    As = [synth.to_storage(rng.normal(size=(K, M)), "bf16") for K in Ks]
+    Bs = [synth.to_storage(rng.normal(size=(K, N)), "bf16") for K in Ks]
+    C0 = rng.normal(size=(M, N)).astype(np.float32)
+    want = C0.astype(np.float64)
+    for A, B, K, lim in zip(As, Bs, Ks, limits):
+        k = K if lim is None else lim
+        want = want + A[:k].T.astype(np.float64) @ B[:k].astype(np.float64)
+    for n in (2, 4):
+        Cd = dev(C0, "f32")
+        rows = [None if lim is None else torch.tensor([lim], dtype=torch.int32, device="cuda") for lim in limits[:n]]
+        used = sb.debug_gemm_dw_segments([dev(a, "bf16") for a in As[:n]], [dev(b, "bf16") for b in Bs[:n]], Cd, M, N, Ks[:n], rows)
+        torch.cuda.synchronize()
+        assert used == 1
+        part = C0.astype(np.float64)
+        for A, B, K, lim in list(zip(As, Bs, Ks, limits))[:n]:
+            k = K if lim is None else lim
+            part = part + A[:k].T.astype(np.float64) @ B[:k].astype(np.float64)
+        assert_close(host(Cd), part, 2e-5, f"segmented dW, {n} segments")
+    assert part.shape == want.shape
 
 
 def test_mfma_bigger_square():
