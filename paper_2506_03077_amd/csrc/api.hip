@@ -53,8 +53,21 @@ struct LayerWs {
   float *h1, *dm, *dh1, *da, *proj;                                       // per chunk, fp32 [c, d]
   float *rstd1, *rstd2, *lse, *delta, *partial;
   float* gemm_scratch; size_t gemm_scratch_bytes;
+  // Second copy of the operands of the chunk's weight-gradient GEMMs (a, o, m, gate, up, act, dh1_t, dq, dkc, dvc):
+  // the weight gradients of two consecutive chunks are added in one launch, so one chunk's operands stay alive
+  // while the next chunk is processed.
+  void* alt[10];
   size_t bytes;
 };
+// The workspace view a chunk uses: even chunks the primary operand buffers, odd chunks the second copy.
+LayerWs chunk_view(const LayerWs& s, int parity) {
+  LayerWs v = s;
+  if (parity) {
+    void** ptrs[10] = {&v.a, &v.o, &v.m, &v.gate, &v.up, &v.act, &v.dh1_t, &v.dq, &v.dkc, &v.dvc};
+    for (int i = 0; i < 10; ++i) *ptrs[i] = s.alt[i];
+  }
+  return v;
+}
 
 int32_t check_layer_cfg(const sbp_layer_cfg* c) {
   if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
@@ -105,6 +118,11 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   w.partial = cv.take<float>(rmsnorm_bwd_partial_floats((int)cm, (int)d));
   w.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, (int)std::max(d, qd), 4) : 0;
   w.gemm_scratch = (float*)cv.take_bytes(w.gemm_scratch_bytes);
+  {
+    const size_t sizes[10] = {cm * d * es, cm * qd * es, cm * d * es, cm * F * es, cm * F * es, cm * F * es,
+                              cm * d * es, cm * qd * es, cm * kd * es, cm * kd * es};   // a, o, m, gate, up, act, dh1_t, dq, dkc, dvc
+    for (int i = 0; i < 10; ++i) w.alt[i] = cv.take_bytes(sizes[i]);
+  }
   w.bytes = cv.off;
   return w;
 }
@@ -210,30 +228,33 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
   }
   if (dx == x || dx == dy) return fail(SBP_ERR_SHAPE, "dx may not alias x or dy");
   if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-  const LayerWs s = carve_layer(c, workspace);
-  if (workspace_bytes < s.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s.bytes);
+  const LayerWs s_all = carve_layer(c, workspace);
+  if (workspace_bytes < s_all.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s_all.bytes);
 
   hipStream_t st = (hipStream_t)hip_stream;
-  t_gemm_scratch = s.gemm_scratch; t_gemm_scratch_bytes = s.gemm_scratch_bytes;
+  t_gemm_scratch = s_all.gemm_scratch; t_gemm_scratch_bytes = s_all.gemm_scratch_bytes;
   const int dt = c->dtype;
   const size_t es = dtype_size(dt);
   const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden, F = c->mlp_width;
   const int qd = c->n_q_heads * c->head_dim, kd = c->n_kv_heads * c->head_dim, half = c->head_dim / 2;
 
-  HIPCHK(rope_table(s.rope, T, c->head_dim, c->rope_theta, c->pos_offset, st));
+  HIPCHK(rope_table(s_all.rope, T, c->head_dim, c->rope_theta, c->pos_offset, st));
   for (int b = 0; b < c->batch; ++b) {
     const char* xb = at(x, (size_t)b * T, d, es);
     const char* dyb = at(dy, (size_t)b * T, d, es);
     char* dxb = at(dx, (size_t)b * T, d, es);
-    if ((rc = kv_prepass(c, w, s, xb, st))) return rc;
-    HIPCHK(fill_zero(s.dK, (size_t)T * kd * sizeof(float), st));
-    HIPCHK(fill_zero(s.dV, (size_t)T * kd * sizeof(float), st));
+    if ((rc = kv_prepass(c, w, s_all, xb, st))) return rc;
+    HIPCHK(fill_zero(s_all.dK, (size_t)T * kd * sizeof(float), st));
+    HIPCHK(fill_zero(s_all.dV, (size_t)T * kd * sizeof(float), st));
     // Chunks run last to first: rows of dK/dV belonging to chunk i are final once
     // chunks >= i are done (later queries are the only other readers of those
     // keys), so the K/V-side gradient and dx of the chunk can be finished at once.
     const int n_chunks = (int)cdiv(T, cm);
+    GemmArgs dws[14];          // weight-gradient GEMMs waiting for their launch (two chunks' worth)
+    int n_dws = 0;
     for (int ci = n_chunks - 1; ci >= 0; --ci) {
       const int r0 = ci * cm, n = std::min(cm, T - r0);
+      const LayerWs s = chunk_view(s_all, ci & 1);
       if ((rc = chunk_reforward(c, w, s, xb, r0, n, st))) return rc;
       const char* dyc = at(dyb, r0, d, es);
       // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
@@ -257,13 +278,18 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
                             n, c->n_kv_heads, c->head_dim, st));
       HIPCHK(gemm(dx_gemm(s.dkc, w->wk, s.da, n, kd, d, dt, DT_F32, true), st));
       HIPCHK(gemm(dx_gemm(s.dvc, w->wv, s.da, n, kd, d, dt, DT_F32, true), st));
-      // ---- all seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand), one launch
+      // ---- the seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand): queued, and launched together
+      //      with those of the next chunk (one pass over every dW for two chunks' rows)
       {
-        const GemmArgs dws[7] = {dw_gemm(dyc, s.act, g->wdown, n, d, F, dt),   dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt),
-                                 dw_gemm(s.up, s.m, g->wup, n, F, d, dt),     dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt),
-                                 dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt),     dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt),
-                                 dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt)};
-        HIPCHK(gemm_batch(dws, 7, st));
+        const GemmArgs mine[7] = {dw_gemm(dyc, s.act, g->wdown, n, d, F, dt),  dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt),
+                                  dw_gemm(s.up, s.m, g->wup, n, F, d, dt),    dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt),
+                                  dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt),    dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt),
+                                  dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt)};
+        for (int i = 0; i < 7; ++i) dws[n_dws++] = mine[i];
+        if (n_dws == 14 || ci == 0) {
+          HIPCHK(gemm_batch(dws, n_dws, st));
+          n_dws = 0;
+        }
       }
       HIPCHK(rmsnorm_bwd(dt, s.da, at(xb, r0, d, es), false, w->g1, s.rstd1, s.dh1, true, nullptr, at(dxb, r0, d, es),
                          g->g1, s.partial, n, d, st));

@@ -375,9 +375,10 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_seg_k(const SegLaunch sl, 
 // Several independent GEMMs of one layout / output mode in a single launch: the tiles of all problems form one
 // grid, so small problems fill the tail of large ones instead of each paying its own partial last round.
 constexpr int MAX_GROUP = 8;
+constexpr int MAX_GSEG = 2;      // reduction segments per grouped problem (accumulate form: two chunks' operands)
 struct GroupProblem {
-  const bf16_t* A; const bf16_t* B; void* C;
-  int M, N, K;
+  const bf16_t* A[MAX_GSEG]; const bf16_t* B[MAX_GSEG]; void* C;
+  int M, N, K[MAX_GSEG], nseg;
   int64_t lda, ldb, ldc;
   int tile_begin, tiles_m, tiles_n;
 };
@@ -395,7 +396,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_group_k(const GroupArgs ga
   int tm, tn;
   band_coords(id - g.tile_begin, g.tiles_m, g.tiles_n, band_height(g.tiles_m, g.tiles_m * g.tiles_n, MODE != 2), tm, tn);
   KSegments segs;
-  segs.n = 1; segs.A[0] = g.A; segs.B[0] = g.B; segs.K[0] = g.K; segs.k_begin[0] = 0; segs.k_end[0] = g.K;
+  segs.n = g.nseg;
+#pragma unroll
+  for (int sg = 0; sg < MAX_GSEG; ++sg) {
+    segs.A[sg] = g.A[sg]; segs.B[sg] = g.B[sg]; segs.K[sg] = g.K[sg]; segs.k_begin[sg] = 0; segs.k_end[sg] = g.K[sg];
+  }
   gemm_tile<TA, TB, MODE>(segs, g.C, g.M, g.N, g.lda, g.ldb, g.ldc, tm, tn, smem);
 }
 
@@ -509,28 +514,56 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
 
 
 // Grouped launch.  Requires every problem to be eligible, of the same layout / output type / accumulate mode.
+// Accumulate-form problems that write the same C (same shape and leading dimensions) are folded into one grouped
+// problem with several reduction segments: one pass over that C.
+static bool same_output(const GemmArgs& a, const GemmArgs& b) {
+  return a.C == b.C && a.M == b.M && a.N == b.N && a.lda == b.lda && a.ldb == b.ldb && a.ldc == b.ldc;
+}
+static int group_fold(const GemmArgs* gs, int n, int* owner /* [n]: index of the first problem with the same output */) {
+  int n_out = 0;
+  for (int i = 0; i < n; ++i) {
+    owner[i] = i;
+    if (gs[i].acc)
+      for (int j = 0; j < i; ++j)
+        if (owner[j] == j && same_output(gs[j], gs[i])) { owner[i] = j; break; }
+    if (owner[i] == i) ++n_out;
+  }
+  return n_out;
+}
+constexpr int MAX_BATCH = MAX_GROUP * MAX_GSEG;
 bool gemm_mfma_group_eligible(const GemmArgs* gs, int n) {
-  if (n < 2 || n > MAX_GROUP) return false;
+  if (n < 2 || n > MAX_BATCH) return false;
   int64_t tiles = 0;
+  int owner[MAX_BATCH], nseg[MAX_BATCH] = {0};
+  if (group_fold(gs, n, owner) > MAX_GROUP) return false;
   for (int i = 0; i < n; ++i) {
     if (!gemm_mfma_eligible(gs[i]) || gs[i].rows_dev) return false;
     if (gs[i].ta != gs[0].ta || gs[i].tb != gs[0].tb || gs[i].out_dt != gs[0].out_dt || gs[i].acc != gs[0].acc) return false;
-    tiles += cdiv(gs[i].M, BM) * (gs[i].N / BN);
+    if (++nseg[owner[i]] > MAX_GSEG) return false;
+    if (owner[i] == i) tiles += cdiv(gs[i].M, BM) * (gs[i].N / BN);
   }
   return tiles >= 200 && tiles < (1 << 30);   // otherwise per-problem launches with split-K fill the chip better
 }
 
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
   GroupArgs ga{};
-  ga.n = n;
-  int tiles = 0;
+  int owner[MAX_BATCH], slot[MAX_BATCH];
+  group_fold(gs, n, owner);
+  int tiles = 0, np = 0;
   for (int i = 0; i < n; ++i) {
-    GroupProblem& p = ga.p[i];
-    p.A = (const bf16_t*)gs[i].A; p.B = (const bf16_t*)gs[i].B; p.C = gs[i].C;
-    p.M = gs[i].M; p.N = gs[i].N; p.K = gs[i].K; p.lda = gs[i].lda; p.ldb = gs[i].ldb; p.ldc = gs[i].ldc;
-    p.tiles_m = (int)cdiv(gs[i].M, BM); p.tiles_n = gs[i].N / BN; p.tile_begin = tiles;
-    tiles += p.tiles_m * p.tiles_n;
+    if (owner[i] == i) {
+      slot[i] = np;
+      GroupProblem& p = ga.p[np++];
+      p.C = gs[i].C; p.M = gs[i].M; p.N = gs[i].N; p.lda = gs[i].lda; p.ldb = gs[i].ldb; p.ldc = gs[i].ldc;
+      p.nseg = 0;
+      p.tiles_m = (int)cdiv(gs[i].M, BM); p.tiles_n = gs[i].N / BN; p.tile_begin = tiles;
+      tiles += p.tiles_m * p.tiles_n;
+    }
+    GroupProblem& p = ga.p[slot[owner[i]]];
+    p.A[p.nseg] = (const bf16_t*)gs[i].A; p.B[p.nseg] = (const bf16_t*)gs[i].B; p.K[p.nseg] = gs[i].K;
+    ++p.nseg;
   }
+  ga.n = np;
   ga.total_tiles = tiles;
   const GemmArgs& g = gs[0];
   double work = 0.0;
