@@ -59,6 +59,74 @@ hipError_t rope_apply(int dt, void* x, const float2* tab, int rows, int H, int d
 }
 
 // --------------------------------------------------------------- RMSNorm --
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
+  typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
+  const bf16x8_t a = *(const bf16x8_t*)p;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+  *(float4*)(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
+  typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
+  bf16x8_t a;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a[e] = (bf16_t)v[e];
+  *(bf16x8_t*)p = a;
+}
+constexpr int RV_MAX_IT = 8;    // 64 lanes x 8 elements x 8 = 4096 columns (the backward's 4 x d floats of LDS stay under 64 KiB)
+// Vectorised form for d % 8 == 0, d <= 4096: one wave per row, 8 elements per lane per access, the row stays in
+// registers between the sum of squares and the scaling (one read of x instead of two).
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_vec_k(const T* __restrict__ x, const float* __restrict__ add,
+                                                         const T* __restrict__ g, T* __restrict__ out,
+                                                         float* __restrict__ sum_out, float* __restrict__ rstd,
+                                                         int rows, int d, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int n_it = (d + 511) / 512;
+  float v[RV_MAX_IT][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < RV_MAX_IT; ++it) {
+    const int j = it * 512 + lane * 8;
+    if (it < n_it && j < d) {
+      load8(x + row * d + j, v[it]);
+      if (add) {
+        float a[8];
+        load8(add + row * d + j, a);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[it][e] += a[e];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += v[it][e] * v[it][e];
+    }
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  if (lane == 0 && rstd) rstd[row] = r;
+  if (!out) return;
+#pragma unroll
+  for (int it = 0; it < RV_MAX_IT; ++it) {
+    const int j = it * 512 + lane * 8;
+    if (it < n_it && j < d) {
+      float gv[8], o[8];
+      load8(g + j, gv);
+      if (sum_out) store8(sum_out + row * d + j, v[it]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = gv[e] * v[it][e] * r;
+      store8(out + row * d + j, o);
+    }
+  }
+}
+
 // One workgroup per row.  r = 1/sqrt(mean(v^2) + eps) with v = x (+ add).
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_fwd_k(const T* __restrict__ x, const float* __restrict__ add,
@@ -88,7 +156,12 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_k(const T* __restrict__ x, co
 hipError_t rmsnorm_fwd(int dt, const void* x, const float* add, const void* g, void* out, float* sum_out,
                        float* rstd, int rows, int d, float eps, hipStream_t st) {
   if (rows == 0) return hipSuccess;
-  DISPATCH_DT(dt, T, (rmsnorm_fwd_k<T><<<rows, 256, 0, st>>>((const T*)x, add, (const T*)g, (T*)out, sum_out, rstd, d, eps)));
+  auto al = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  const bool vec = d % 8 == 0 && d <= 512 * RV_MAX_IT && al(x) && al(add) && al(g) && al(out) && al(sum_out);
+  DISPATCH_DT(dt, T, {
+    if (vec) rmsnorm_fwd_vec_k<T><<<(unsigned)cdiv(rows, 4), 256, 0, st>>>((const T*)x, add, (const T*)g, (T*)out, sum_out, rstd, rows, d, eps);
+    else rmsnorm_fwd_k<T><<<rows, 256, 0, st>>>((const T*)x, add, (const T*)g, (T*)out, sum_out, rstd, d, eps);
+  });
   return hipGetLastError();
 }
 
@@ -137,28 +210,6 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_k(const DN* __restrict__ dnor
 // a workgroup of 4 waves takes RB rows (2 per wave), each wave keeps its share of dg in registers across its rows
 // and the four waves' shares meet in LDS in a fixed order.  Same arithmetic and the same partial-sum layout as the
 // plain kernel above.
-__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
-  const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-__device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
-  typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
-  const bf16x8_t a = *(const bf16x8_t*)p;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = (float)a[e];
-}
-__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
-  *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
-  *(float4*)(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
-}
-__device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
-  typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
-  bf16x8_t a;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) a[e] = (bf16_t)v[e];
-  *(bf16x8_t*)p = a;
-}
-constexpr int RV_MAX_IT = 8;    // 64 lanes x 8 elements x 8 = 4096 columns (4 x d floats of LDS stay under 64 KiB)
 template <typename T, typename XT, typename RT, typename DN>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_vec_k(const DN* __restrict__ dnorm, const XT* __restrict__ xin,
                                                          const T* __restrict__ g, const float* __restrict__ rstd,
