@@ -161,17 +161,27 @@ int32_t check_layer_ptrs(const sbp_layer_weights* w) {
   return SBP_OK;
 }
 
-// K and V of the whole sequence, once (cached for all chunks of the layer).
+// K and V of the whole sequence, once (cached for all chunks of the layer).  The pass runs in row blocks as large as
+// the chunk buffers that are idle at this point allow (gate, up, act, dact are contiguous: 4 c F elements hold the
+// normalised rows of 4 c F / d positions), so that the two projections are GEMMs with enough output tiles to fill
+// the chip on their own; nothing proportional to T is added to the workspace.
 int32_t kv_prepass(const sbp_layer_cfg* c, const sbp_layer_weights* w, const LayerWs& s, const char* xb, hipStream_t st) {
   const int dt = c->dtype;
   const size_t es = dtype_size(dt);
   const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden;
   const int kd = c->n_kv_heads * c->head_dim;
-  for (int r0 = 0; r0 < T; r0 += cm) {
-    const int n = std::min(cm, T - r0);
-    HIPCHK(rmsnorm_fwd(dt, at(xb, r0, d, es), nullptr, w->g1, s.a, nullptr, s.rstd1, n, d, c->rms_eps, st));
-    const GemmArgs kv[2] = {fwd_gemm(s.a, w->wk, at(s.K, r0, kd, es), n, kd, d, dt, dt),
-                            fwd_gemm(s.a, w->wv, at(s.V, r0, kd, es), n, kd, d, dt, dt)};
+  void* a_rows = s.a;
+  int block = cm;
+  const size_t idle_rows = (size_t)((const char*)s.dh1_t - (const char*)s.gate) / ((size_t)d * es);
+  if (idle_rows > (size_t)cm) {
+    a_rows = s.gate;
+    block = (int)std::min<size_t>((size_t)T, idle_rows);
+  }
+  for (int r0 = 0; r0 < T; r0 += block) {
+    const int n = std::min(block, T - r0);
+    HIPCHK(rmsnorm_fwd(dt, at(xb, r0, d, es), nullptr, w->g1, a_rows, nullptr, nullptr, n, d, c->rms_eps, st));
+    const GemmArgs kv[2] = {fwd_gemm(a_rows, w->wk, at(s.K, r0, kd, es), n, kd, d, dt, dt),
+                            fwd_gemm(a_rows, w->wv, at(s.V, r0, kd, es), n, kd, d, dt, dt)};
     HIPCHK(gemm_batch(kv, 2, st));
     HIPCHK(rope_apply(dt, at(s.K, r0, kd, es), s.rope + (size_t)r0 * (c->head_dim / 2), n, c->n_kv_heads, c->head_dim, false, st));
   }
