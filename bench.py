@@ -1,5 +1,6 @@
 #!/usr/bin/env python3
-"""StreamBP backward benchmark: one 7B-shaped decoder layer + LM head at 32k tokens.
+"""StreamBP backward benchmark: one 7B-shaped decoder layer + LM head at 32k tokens (the headline workload; the
+other workloads of the paper's shape list can be timed with --workload).
 
 A step = one pass of the whole hot path over one synthetic sequence:
 LM-head + cross-entropy StreamBP (chunk 2048 rows of logits at a time) followed
@@ -7,8 +8,8 @@ by the layer-wise StreamBP of one decoder layer (K/V pre-pass, then per chunk:
 reforward, MLP / attention backward, dW accumulation), with all inputs already
 resident in HBM.  Prints ONE JSON line (see README for the fields).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--seq-len T] [--chunk C]
-                    [--no-cpu-baseline] [--no-profile]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|llama_layer|lmhead|grpo] [--seq-len T]
+                    [--chunk C] [--no-cpu-baseline] [--no-profile]
 """
 from __future__ import annotations
 
@@ -29,15 +30,21 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC = {"gemm_mfma_k<false, false, 3>": 0.904e9}
 
 
-def algorithmic_flops(cfg, T, active_rows):
+def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=True):
     """Work the method must do (Sec. 3.2): 6*P per token for the linear maps (reforward, dX, dW), 14*dh per
-    visible causal (query, key) pair per query head (4 forward + 10 backward), 6*d*V per row of the head."""
-    d, Hq, Hkv, dh, F, V = (cfg[k] for k in ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "mlp_width", "vocab"))
-    p_lin = d * Hq * dh + 2 * d * Hkv * dh + Hq * dh * d + 3 * d * F
-    linear = 6.0 * p_lin * T
-    attn = 14.0 * dh * Hq * (T * (T + 1) / 2.0)
-    head_all = 6.0 * d * V * T
-    head_active = 6.0 * d * V * active_rows
+    visible causal (query, key) pair per query head (4 forward + 10 backward), 6*d*V per row of the head.
+    T = tokens per sequence, batch sequences (no attention across sequences), active_rows over the whole batch."""
+    d = cfg["hidden"]
+    linear = attn = head_all = head_active = 0.0
+    if has_layer:
+        Hq, Hkv, dh, F = (cfg[k] for k in ("n_q_heads", "n_kv_heads", "head_dim", "mlp_width"))
+        p_lin = d * Hq * dh + 2 * d * Hkv * dh + Hq * dh * d + 3 * d * F
+        linear = 6.0 * p_lin * T * batch
+        attn = 14.0 * dh * Hq * (T * (T + 1) / 2.0) * batch
+    if has_head:
+        V = cfg["vocab"]
+        head_all = 6.0 * d * V * T * batch
+        head_active = 6.0 * d * V * active_rows
     # Rows whose target is ignored (prompt positions) need no head work at all (their dz is zero) and the
     # library skips them, so only the active rows are credited; the all-rows figure is kept for reference.
     return dict(linear=linear, attention=attn, head_all_rows=head_all, head_active_rows=head_active,
@@ -81,6 +88,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", choices=("7b", "llama_layer", "lmhead", "grpo"), default="7b",
+                    help="7b (default, the workload the metric is quoted on): 7B-shaped layer + LM head, 32k tokens, SFT; "
+                         "llama_layer: one Llama-style layer, 8k tokens; lmhead: LM head + cross-entropy only, 32k rows; "
+                         "grpo: 7B-shaped layer + LM head, 8 sequences x 16k tokens, GRPO objective")
     ap.add_argument("--seq-len", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=None)
     ap.add_argument("--head-chunk", type=int, default=None)
@@ -107,49 +118,72 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    cfg = dict(synth.CONFIGS["7b"])
+    wl = args.workload
+    cfg = dict(synth.CONFIGS[wl])
+    has_layer, has_head = wl != "lmhead", wl != "llama_layer"
+    grpo = wl == "grpo"
+    B = cfg["batch"]
     T = args.seq_len or cfg["seq_len"]
     c = args.chunk or cfg["chunk"]
     hc_rows = args.head_chunk or c
-    d, V = cfg["hidden"], cfg["vocab"]
+    default_shape = wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c   # what the profiles cover
+    d = cfg["hidden"]
     bf = torch.bfloat16
 
     # ---- synthetic inputs, generated on the device (seeded): weights N(0, 0.02), hidden states N(0, 1),
-    # gains 1 + N(0, 0.02), target ids uniform in [0, V) with the first 25% of positions ignored (prompt).
+    # gains 1 + N(0, 0.02), upstream gradients N(0, 1e-3), target ids uniform in [0, V) with the first 25% of the
+    # positions of every sequence ignored (prompt); GRPO: advantages N(0, 1) per sequence, reference log-probs
+    # N(-2, 0.5), on-policy (no old log-probs).
     gen = torch.Generator(device=dev)
     gen.manual_seed(0)
 
     def normal(shape, std, mean=0.0):
         return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(bf)
 
-    Hq, Hkv, dh, F = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"]
-    w = dict(wq=normal((Hq * dh, d), 0.02), wk=normal((Hkv * dh, d), 0.02), wv=normal((Hkv * dh, d), 0.02),
-             wo=normal((d, Hq * dh), 0.02), wgate=normal((F, d), 0.02), wup=normal((F, d), 0.02),
-             wdown=normal((d, F), 0.02), g1=normal((d,), 0.02, 1.0), g2=normal((d,), 0.02, 1.0))
-    w_head = normal((V, d), 0.02)
-    x = normal((1, T, d), 1.0)          # layer input (the checkpoint)
-    h = normal((1, T, d), 1.0)          # hidden states entering the head
-    targets = torch.randint(0, V, (1, T), generator=gen, device=dev, dtype=torch.int32)
     n_prompt = T // 4
-    targets[:, :n_prompt] = -1
-    n_act = T - n_prompt
-
-    lcfg = sb.layer_cfg(sb.SBP_BF16, 1, T, c, d, Hq, Hkv, dh, F)
-    hcfg = sb.head_cfg(sb.SBP_BF16, 1, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act)
-    ws_layer = torch.empty(sb.streambp_layer_workspace_bytes(lcfg), dtype=torch.uint8, device=dev)
-    ws_head = torch.empty(sb.streambp_lmhead_workspace_bytes(hcfg), dtype=torch.uint8, device=dev)
-    dw = sb.new_layer_grads(w)
-    dw_head = torch.zeros((V, d), dtype=torch.float32, device=dev)
-    dh_out = torch.empty_like(h)
-    dx = torch.empty_like(x)
-    loss = torch.zeros(1, dtype=torch.float32, device=dev)
-    n_active = torch.zeros(1, dtype=torch.int64, device=dev)
+    n_act = B * (T - n_prompt)
+    ws_bytes = {}
+    if has_layer:
+        Hq, Hkv, dh, F = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"]
+        w = dict(wq=normal((Hq * dh, d), 0.02), wk=normal((Hkv * dh, d), 0.02), wv=normal((Hkv * dh, d), 0.02),
+                 wo=normal((d, Hq * dh), 0.02), wgate=normal((F, d), 0.02), wup=normal((F, d), 0.02),
+                 wdown=normal((d, F), 0.02), g1=normal((d,), 0.02, 1.0), g2=normal((d,), 0.02, 1.0))
+        x = normal((B, T, d), 1.0)          # layer input (the checkpoint)
+        lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F)
+        ws_layer = torch.empty(sb.streambp_layer_workspace_bytes(lcfg), dtype=torch.uint8, device=dev)
+        ws_bytes["layer_workspace"] = ws_layer.numel()
+        dw = sb.new_layer_grads(w)
+        dx = torch.empty_like(x)
+    if has_head:
+        V = cfg["vocab"]
+        w_head = normal((V, d), 0.02)
+        h = normal((B, T, d), 1.0)          # hidden states entering the head
+        targets = torch.randint(0, V, (B, T), generator=gen, device=dev, dtype=torch.int32)
+        targets[:, :n_prompt] = -1
+        adv = ref_logp = None
+        if grpo:
+            adv = torch.randn((B,), generator=gen, device=dev, dtype=torch.float32)
+            ref_logp = torch.randn((B, T), generator=gen, device=dev, dtype=torch.float32) * 0.5 - 2.0
+            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_GRPO)
+        else:
+            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act)
+        ws_head = torch.empty(sb.streambp_lmhead_workspace_bytes(hcfg), dtype=torch.uint8, device=dev)
+        ws_bytes["head_workspace"] = ws_head.numel()
+        ws_bytes["full_sequence_logits_fp32_would_be"] = B * T * V * 4
+        dw_head = torch.zeros((V, d), dtype=torch.float32, device=dev)
+        dh_out = torch.empty_like(h)
+        loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        n_active = torch.zeros(1, dtype=torch.int64, device=dev)
+    else:
+        dh_out = normal((B, T, d), 1e-3)    # upstream gradient of the layer
 
     def step():
-        sb.streambp_lmhead_ce_backward(hcfg, w_head, h, targets, dh=dh_out, dw=dw_head, loss=loss, n_active=n_active,
-                                       workspace=ws_head)
-        # the head's dH is the upstream gradient of the layer (the final norm is left out of the timed step)
-        sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
+        if has_head:
+            sb.streambp_lmhead_ce_backward(hcfg, w_head, h, targets, ref_logp=ref_logp, advantages=adv, dh=dh_out, dw=dw_head,
+                                           loss=loss, n_active=n_active, workspace=ws_head)
+        if has_layer:
+            # the head's dH is the upstream gradient of the layer (the final norm is left out of the timed step)
+            sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
 
     if args.pmc_calibrate:   # 2^28 fp32 elements: the add kernel fetches 1 GiB and writes 1 GiB
         ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -167,23 +201,29 @@ def main():
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / max(args.steps, 1)
 
-    assert int(n_active.item()) == n_act
-    assert bool(torch.isfinite(dx.float()).all()) and bool(torch.isfinite(loss).all())
+    if has_head:
+        assert int(n_active.item()) == n_act
+        assert bool(torch.isfinite(loss).all()) and bool(torch.isfinite(dh_out.float()).all())
+    if has_layer:
+        assert bool(torch.isfinite(dx.float()).all())
 
-    fl = algorithmic_flops(cfg, T, n_act)
+    fl = algorithmic_flops(cfg, T, n_act, B, has_layer, has_head)
+    names = {"7b": "7B-shaped decoder layer (d=3584, 28q/4kv x128, F=18944) + LM head (V=152064)",
+             "llama_layer": "Llama-style decoder layer (d=4096, 32q/8kv x128, F=14336), upstream gradient N(0,1e-3)",
+             "lmhead": "LM head + cross-entropy (d=3584, V=152064)",
+             "grpo": "7B-shaped decoder layer + LM head (V=152064), GRPO objective (on-policy, reference log-probs)"}
     out = {
         "metric": "backward tokens/s per layer+LM head at 32k seq",
-        "value": T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": B * T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"7B-shaped decoder layer (d=3584, 28q/4kv x128, F=18944) + LM head (V=152064), "
-                               f"T={T}, chunk={c}, head chunk={hc_rows}, batch 1, SFT loss on last 75% of positions",
+        "config": {"workload": f"{names[wl]}, T={T}, chunk={c}, head chunk={hc_rows}, batch {B}, "
+                               f"loss on the last 75% of the positions of every sequence",
                    "algorithmic_tflop_per_step": fl["total"] / 1e12,
                    "algorithmic_tflop_per_step_if_ignored_rows_were_counted": fl["total_all_rows"] / 1e12,
                    "achieved_tflops": fl["total"] / dt / 1e12,
                    "frac_of_bf16_mfma_peak": fl["total"] / dt / 1e12 / PEAK_BF16_TFLOPS,
-                   "peak_activation_bytes": {"layer_workspace": ws_layer.numel(), "head_workspace": ws_head.numel(),
-                                             "full_sequence_logits_fp32_would_be": T * V * 4},
+                   "peak_activation_bytes": ws_bytes,
                    "torch_max_memory_allocated": int(torch.cuda.max_memory_allocated())},
     }
 
@@ -197,7 +237,7 @@ def main():
         # Flops per kernel: 2MNK summed over its launches.  For the LM-head GEMMs the row count of a chunk lives
         # on the device (ignored rows are compacted away), so the library reports their work from the host-side
         # upper bound separately; the real row total is n_active of B*T rows, hence the factor below.
-        active_frac = n_act / float(T)
+        active_frac = n_act / float(B * T)
         per_kernel = {}
         for kname, v in prof.items():
             if not v["count"]:
@@ -211,10 +251,11 @@ def main():
                            "avg_launch_ms": pk["avg_launch_ms"], "avg_launch_tflop": pk["tflop"] / pk["launches"],
                            "achieved": pk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": pk["tflops"] / PEAK_BF16_TFLOPS,
-                           "traffic": args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC.get(dom)}
+                           "traffic": args.traffic_bytes if args.traffic_bytes is not None else
+                           (MEASURED_TRAFFIC.get(dom) if default_shape else None)}
         out["config"]["per_kernel"] = per_kernel
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg)
+        out["cpu_baseline"] = cpu_baseline(dict(synth.CONFIGS["7b"]))
     print(json.dumps(out))
 
 
