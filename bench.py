@@ -92,6 +92,9 @@ def main():
                     help="7b (default, the workload the metric is quoted on): 7B-shaped layer + LM head, 32k tokens, SFT; "
                          "llama_layer: one Llama-style layer, 8k tokens; lmhead: LM head + cross-entropy only, 32k rows; "
                          "grpo: 7B-shaped layer + LM head, 8 sequences x 16k tokens, GRPO objective")
+    ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
+                    help="element type of the weight-gradient accumulators (default fp32; bf16 is the paper's own training "
+                         "setting, App. B.1, and halves the read-modify-write traffic on dW)")
     ap.add_argument("--seq-len", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=None)
     ap.add_argument("--head-chunk", type=int, default=None)
@@ -126,7 +129,9 @@ def main():
     T = args.seq_len or cfg["seq_len"]
     c = args.chunk or cfg["chunk"]
     hc_rows = args.head_chunk or c
-    default_shape = wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c   # what the profiles cover
+    gdt = sb.SBP_BF16 if args.grad_dtype == "bf16" else sb.SBP_F32
+    default_shape = (wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c
+                     and gdt == sb.SBP_F32)                                       # what the profiles cover
     d = cfg["hidden"]
     bf = torch.bfloat16
 
@@ -149,10 +154,10 @@ def main():
                  wo=normal((d, Hq * dh), 0.02), wgate=normal((F, d), 0.02), wup=normal((F, d), 0.02),
                  wdown=normal((d, F), 0.02), g1=normal((d,), 0.02, 1.0), g2=normal((d,), 0.02, 1.0))
         x = normal((B, T, d), 1.0)          # layer input (the checkpoint)
-        lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F)
+        lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F, grad_dtype=gdt)
         ws_layer = torch.empty(sb.streambp_layer_workspace_bytes(lcfg), dtype=torch.uint8, device=dev)
         ws_bytes["layer_workspace"] = ws_layer.numel()
-        dw = sb.new_layer_grads(w)
+        dw = sb.new_layer_grads(w, gdt)
         dx = torch.empty_like(x)
     if has_head:
         V = cfg["vocab"]
@@ -164,13 +169,13 @@ def main():
         if grpo:
             adv = torch.randn((B,), generator=gen, device=dev, dtype=torch.float32)
             ref_logp = torch.randn((B, T), generator=gen, device=dev, dtype=torch.float32) * 0.5 - 2.0
-            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_GRPO)
+            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_GRPO, grad_dtype=gdt)
         else:
-            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act)
+            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act, grad_dtype=gdt)
         ws_head = torch.empty(sb.streambp_lmhead_workspace_bytes(hcfg), dtype=torch.uint8, device=dev)
         ws_bytes["head_workspace"] = ws_head.numel()
         ws_bytes["full_sequence_logits_fp32_would_be"] = B * T * V * 4
-        dw_head = torch.zeros((V, d), dtype=torch.float32, device=dev)
+        dw_head = torch.zeros((V, d), dtype=torch.bfloat16 if gdt == sb.SBP_BF16 else torch.float32, device=dev)
         dh_out = torch.empty_like(h)
         loss = torch.zeros(1, dtype=torch.float32, device=dev)
         n_active = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -218,7 +223,8 @@ def main():
         "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{names[wl]}, T={T}, chunk={c}, head chunk={hc_rows}, batch {B}, "
-                               f"loss on the last 75% of the positions of every sequence",
+                               f"loss on the last 75% of the positions of every sequence, "
+                               f"{args.grad_dtype} weight-gradient accumulators",
                    "algorithmic_tflop_per_step": fl["total"] / 1e12,
                    "algorithmic_tflop_per_step_if_ignored_rows_were_counted": fl["total_all_rows"] / 1e12,
                    "achieved_tflops": fl["total"] / dt / 1e12,

@@ -75,6 +75,11 @@ typedef struct {
   float rms_eps;        /* e.g. 1e-6                                          */
   float rope_theta;     /* e.g. 1e4                                           */
   int32_t pos_offset;   /* RoPE position of row 0                             */
+  int32_t grad_dtype;   /* element type of the weight-gradient matrices:
+                           SBP_F32 (0, default) or SBP_BF16 (needs dtype ==
+                           SBP_BF16; App. B.1 of the paper trains with bf16
+                           weights and gradients).  A bf16 gradient is read,
+                           added to in fp32 and rounded once per pass over it. */
 } sbp_layer_cfg;
 
 /* wq [Hq*dh, d]; wk, wv [Hkv*dh, d]; wo [d, Hq*dh]; wgate, wup [F, d];
@@ -83,9 +88,11 @@ typedef struct {
   const void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown, *g1, *g2;
 } sbp_layer_weights;
 
-/* Same shapes, fp32, accumulated into. */
+/* Same shapes, accumulated into.  The seven matrices have element type
+ * cfg.grad_dtype; the gradients of the two norm gains are always fp32. */
 typedef struct {
-  float *wq, *wk, *wv, *wo, *wgate, *wup, *wdown, *g1, *g2;
+  void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown;
+  float *g1, *g2;
 } sbp_layer_grads;
 
 /* Bytes of workspace streambp_layer_backward / streambp_layer_forward need for
@@ -132,6 +139,8 @@ typedef struct {
   float kl_beta;        /* GRPO: weight of the KL term; DPO: beta              */
   int32_t kl_mode;      /* GRPO: 0 = log(pi/pi_ref) (the paper's compact form),
                            1 = exp(ref-logp) - (ref-logp) - 1                  */
+  int32_t grad_dtype;   /* element type of dw: SBP_F32 (0, default) or SBP_BF16
+                           (needs dtype == SBP_BF16)                            */
 } sbp_head_cfg;
 
 size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg *cfg);
@@ -145,7 +154,7 @@ size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg *cfg);
  *   old_logp [B, T] fp32 or NULL (GRPO; NULL = on-policy, ratio 1)
  *   ref_logp [B, T] fp32 (GRPO, DPO; NULL for SFT)
  *   advantages [B] fp32 (GRPO; NULL otherwise)
- *   dh [B, T, d] out (cfg.dtype);  dw [V, d] fp32 +=
+ *   dh [B, T, d] out (cfg.dtype);  dw [V, d] (cfg.grad_dtype) +=
  *   loss: device fp32 scalar, +=.   n_active: device int64 scalar, out.
  * GRPO: L = -(1/B) sum_j (1/T_o,j) sum_{t active in j} f(j,t) with T_o,j the
  * number of active rows of sequence j.
@@ -156,7 +165,7 @@ size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg *cfg);
 int32_t streambp_lmhead_ce_backward(const sbp_head_cfg *cfg, const void *w, const void *h,
                                     const int32_t *targets, const float *old_logp,
                                     const float *ref_logp, const float *advantages,
-                                    void *dh, float *dw, float *loss, int64_t *n_active,
+                                    void *dh, void *dw, float *loss, int64_t *n_active,
                                     void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* ------------------------------------------------------- chunk attention -- */
@@ -236,14 +245,15 @@ int32_t streambp_stack_forward(const sbp_stack_cfg *cfg, const sbp_layer_weights
 
 /* Backward: LM head + objective on RMSNorm(ckpt[L]), final norm, then layers
  * L-1 .. 0, each by streambp_layer_backward on its checkpoint.
- *   dlayers [L] (+=), dg_final [d] fp32 (+=), dw_head [V, d] fp32 (+=; DPO: zero on entry),
+ *   dlayers [L] (+=; matrices in layer.grad_dtype), dg_final [d] fp32 (+=),
+ *   dw_head [V, d] in layer.grad_dtype (+=; DPO: zero on entry),
  *   demb [V, d] fp32 (+=, may be NULL together with ids), loss (+=), n_active (out);
  *   dx0 [B, T, d] out (may be NULL): gradient wrt the stack input. */
 int32_t streambp_stack_backward(const sbp_stack_cfg *cfg, const sbp_layer_weights *layers,
                                 const void *g_final, const void *w_head, void *const *ckpt,
                                 const int32_t *ids, const int32_t *targets, const float *old_logp,
                                 const float *ref_logp, const float *advantages,
-                                const sbp_layer_grads *dlayers, float *dg_final, float *dw_head,
+                                const sbp_layer_grads *dlayers, float *dg_final, void *dw_head,
                                 float *demb, void *dx0, float *loss, int64_t *n_active,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 

@@ -27,7 +27,8 @@ class StreamBPError(RuntimeError):
 class LayerCfg(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
                 ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
-                ("mlp_width", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("pos_offset", C.c_int32)]
+                ("mlp_width", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("pos_offset", C.c_int32),
+                ("grad_dtype", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -41,7 +42,7 @@ class LayerGrads(C.Structure):
 class HeadCfg(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
                 ("hidden", C.c_int32), ("vocab", C.c_int32), ("objective", C.c_int32), ("loss_scale", C.c_float),
-                ("clip_eps", C.c_float), ("kl_beta", C.c_float), ("kl_mode", C.c_int32)]
+                ("clip_eps", C.c_float), ("kl_beta", C.c_float), ("kl_mode", C.c_int32), ("grad_dtype", C.c_int32)]
 
 
 class AttnCfg(C.Structure):
@@ -112,7 +113,7 @@ def lib():
                                               vp, C.POINTER(LayerGrads), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.streambp_debug_gemm_dw_segments.restype = C.c_int
         L.streambp_debug_gemm_dw_segments.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(vp), C.POINTER(vp),
-                                                      C.POINTER(vp), vp, C.c_longlong, C.c_longlong, C.c_longlong, C.c_int, vp]
+                                                      C.POINTER(vp), vp, C.c_longlong, C.c_longlong, C.c_longlong, C.c_int, C.c_int, vp]
         L.streambp_debug_profile_begin.restype = C.c_int
         L.streambp_debug_profile_begin.argtypes = [C.c_int]
         L.streambp_debug_profile_end.restype = C.c_int
@@ -165,9 +166,9 @@ def streambp_version():
 
 
 def layer_cfg(dtype, batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
-              rms_eps=1e-6, rope_theta=1e4, pos_offset=0):
+              rms_eps=1e-6, rope_theta=1e4, pos_offset=0, grad_dtype=SBP_F32):
     return LayerCfg(int(dtype), batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
-                    rms_eps, rope_theta, pos_offset)
+                    rms_eps, rope_theta, pos_offset, int(grad_dtype))
 
 
 def streambp_layer_workspace_bytes(cfg: LayerCfg) -> int:
@@ -178,10 +179,17 @@ def _weights_struct(w):
     return LayerWeights(*[_ptr(w[n]) for n in WEIGHT_NAMES])
 
 
-def new_layer_grads(w):
-    """Zero fp32 accumulators shaped like the weights."""
+def _grad_torch_dtype(grad_dtype):
     torch = _torch()
-    return {n: torch.zeros(w[n].shape, dtype=torch.float32, device=w[n].device) for n in WEIGHT_NAMES}
+    return torch.bfloat16 if int(grad_dtype) == SBP_BF16 else torch.float32
+
+
+def new_layer_grads(w, grad_dtype=SBP_F32):
+    """Zero accumulators shaped like the weights: matrices in grad_dtype, the two norm gains always fp32."""
+    torch = _torch()
+    mat = _grad_torch_dtype(grad_dtype)
+    return {n: torch.zeros(w[n].shape, dtype=(torch.float32 if n in ("g1", "g2") else mat), device=w[n].device)
+            for n in WEIGHT_NAMES}
 
 
 def streambp_layer_backward(cfg: LayerCfg, w, x, dy, dx=None, dw=None, workspace=None, stream=None):
@@ -190,7 +198,10 @@ def streambp_layer_backward(cfg: LayerCfg, w, x, dy, dx=None, dw=None, workspace
     if dx is None:
         dx = torch.empty_like(x)
     if dw is None:
-        dw = new_layer_grads(w)
+        dw = new_layer_grads(w, cfg.grad_dtype)
+    for n in WEIGHT_NAMES:
+        want = torch.float32 if n in ("g1", "g2") else _grad_torch_dtype(cfg.grad_dtype)
+        assert dw[n].dtype == want, f"dw[{n}] must be {want} for this cfg"
     if workspace is None:
         workspace = _workspace(streambp_layer_workspace_bytes(cfg), x.device)
     ws, gs = _weights_struct(w), LayerGrads(*[_ptr(dw[n]) for n in WEIGHT_NAMES])
@@ -212,8 +223,9 @@ def streambp_layer_forward(cfg: LayerCfg, w, x, y=None, workspace=None, stream=N
 
 
 def head_cfg(dtype, batch, seq_len, chunk, hidden, vocab, objective=SBP_OBJ_SFT, loss_scale=1.0,
-             clip_eps=0.2, kl_beta=0.04, kl_mode=0):
-    return HeadCfg(int(dtype), batch, seq_len, chunk, hidden, vocab, objective, loss_scale, clip_eps, kl_beta, kl_mode)
+             clip_eps=0.2, kl_beta=0.04, kl_mode=0, grad_dtype=SBP_F32):
+    return HeadCfg(int(dtype), batch, seq_len, chunk, hidden, vocab, objective, loss_scale, clip_eps, kl_beta, kl_mode,
+                   int(grad_dtype))
 
 
 def streambp_lmhead_workspace_bytes(cfg: HeadCfg) -> int:
@@ -228,7 +240,8 @@ def streambp_lmhead_ce_backward(cfg: HeadCfg, w, h, targets, old_logp=None, ref_
     if dh is None:
         dh = torch.empty_like(h)
     if dw is None:
-        dw = torch.zeros(w.shape, dtype=torch.float32, device=dev)
+        dw = torch.zeros(w.shape, dtype=_grad_torch_dtype(cfg.grad_dtype), device=dev)
+    assert dw.dtype == _grad_torch_dtype(cfg.grad_dtype), "dw must have the element type cfg.grad_dtype names"
     if loss is None:
         loss = torch.zeros(1, dtype=torch.float32, device=dev)
     if n_active is None:
@@ -351,7 +364,7 @@ def debug_gemm_dw_segments(As, Bs, C_out, M, N, Ks, rows_dev=None, stream=None):
     Ba = (C.c_void_p * n)(*[_ptr(b) for b in Bs])
     Ra = (C.c_void_p * n)(*[(_ptr(r) if r is not None else None) for r in (rows_dev or [None] * n)])
     rc = lib().streambp_debug_gemm_dw_segments(n, M, N, Ka, Aa, Ba, Ra, _ptr(C_out), As[0].stride(0), Bs[0].stride(0),
-                                               C_out.stride(0), _dt_code(As[0]), _stream(stream))
+                                               C_out.stride(0), _dt_code(As[0]), _dt_code(C_out), _stream(stream))
     if rc < 0:
         raise StreamBPError(rc, "debug_gemm_dw_segments launch failed")
     return rc
@@ -419,11 +432,11 @@ def streambp_stack_backward(cfg: StackCfg, layers, g_final, w_head, ckpt, target
     torch = _torch()
     dev = ckpt[0].device
     if dlayers is None:
-        dlayers = [new_layer_grads(w) for w in layers]
+        dlayers = [new_layer_grads(w, cfg.layer.grad_dtype) for w in layers]
     if dg_final is None:
         dg_final = torch.zeros(g_final.shape, dtype=torch.float32, device=dev)
     if dw_head is None:
-        dw_head = torch.zeros(w_head.shape, dtype=torch.float32, device=dev)
+        dw_head = torch.zeros(w_head.shape, dtype=_grad_torch_dtype(cfg.layer.grad_dtype), device=dev)
     if ids is not None and demb is None:
         demb = torch.zeros(w_head.shape, dtype=torch.float32, device=dev)
     if dx0 is None:

@@ -43,6 +43,12 @@ struct Carver {
 };
 
 bool valid_dtype(int32_t dt) { return dt == SBP_F32 || dt == SBP_BF16; }
+// weight gradients: fp32, or bf16 next to bf16 weights
+int32_t check_grad_dtype(int32_t dt, int32_t grad_dt) {
+  if (!valid_dtype(grad_dt)) return fail(SBP_ERR_UNSUPPORTED, "grad_dtype %d not supported", grad_dt);
+  if (grad_dt == SBP_BF16 && dt != SBP_BF16) return fail(SBP_ERR_UNSUPPORTED, "bf16 gradients need dtype == SBP_BF16");
+  return SBP_OK;
+}
 
 // ------------------------------------------------------------- layer ------
 struct LayerWs {
@@ -72,6 +78,7 @@ LayerWs chunk_view(const LayerWs& s, int parity) {
 int32_t check_layer_cfg(const sbp_layer_cfg* c) {
   if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
   if (!valid_dtype(c->dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", c->dtype);
+  if (int32_t rc = check_grad_dtype(c->dtype, c->grad_dtype)) return rc;
   if (c->batch < 1 || c->seq_len < 1 || c->chunk < 1) return fail(SBP_ERR_SHAPE, "batch, seq_len and chunk must be >= 1");
   if (c->hidden < 1 || c->mlp_width < 1) return fail(SBP_ERR_SHAPE, "hidden and mlp_width must be >= 1");
   if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads != 0)
@@ -147,8 +154,8 @@ GemmArgs dx_gemm(const void* dY, const void* W, void* dX, int M, int N, int K, i
   return mk(dY, W, dX, M, K, N, N, K, K, false, false, dt, out_dt, acc);
 }
 // dW[N,K] += dY[M,N]^T X[M,K]
-GemmArgs dw_gemm(const void* dY, const void* X, float* dW, int M, int N, int K, int dt) {
-  return mk(dY, X, dW, N, K, M, N, K, K, true, false, dt, DT_F32, true);
+GemmArgs dw_gemm(const void* dY, const void* X, void* dW, int M, int N, int K, int dt, int grad_dt) {
+  return mk(dY, X, dW, N, K, M, N, K, K, true, false, dt, grad_dt, true);
 }
 
 const char* at(const void* p, size_t row, size_t width, size_t es) { return (const char*)p + row * width * es; }
@@ -233,8 +240,8 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
   if ((rc = check_layer_ptrs(w))) return rc;
   if (!x || !dy || !dx || !g || !workspace) return fail(SBP_ERR_NULL, "x, dy, dx, dw and workspace must be non-NULL");
   {
-    const float* ps[] = {g->wq, g->wk, g->wv, g->wo, g->wgate, g->wup, g->wdown, g->g1, g->g2};
-    for (const float* p : ps) if (!p) return fail(SBP_ERR_NULL, "a gradient pointer is NULL");
+    const void* ps[] = {g->wq, g->wk, g->wv, g->wo, g->wgate, g->wup, g->wdown, g->g1, g->g2};
+    for (const void* p : ps) if (!p) return fail(SBP_ERR_NULL, "a gradient pointer is NULL");
   }
   if (dx == x || dx == dy) return fail(SBP_ERR_SHAPE, "dx may not alias x or dy");
   if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
@@ -243,7 +250,7 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
 
   hipStream_t st = (hipStream_t)hip_stream;
   t_gemm_scratch = s_all.gemm_scratch; t_gemm_scratch_bytes = s_all.gemm_scratch_bytes;
-  const int dt = c->dtype;
+  const int dt = c->dtype, gdt = c->grad_dtype;
   const size_t es = dtype_size(dt);
   const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden, F = c->mlp_width;
   const int qd = c->n_q_heads * c->head_dim, kd = c->n_kv_heads * c->head_dim, half = c->head_dim / 2;
@@ -291,10 +298,10 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       // ---- the seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand): queued, and launched together
       //      with those of the next chunk (one pass over every dW for two chunks' rows)
       {
-        const GemmArgs mine[7] = {dw_gemm(dyc, s.act, g->wdown, n, d, F, dt),  dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt),
-                                  dw_gemm(s.up, s.m, g->wup, n, F, d, dt),    dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt),
-                                  dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt),    dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt),
-                                  dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt)};
+        const GemmArgs mine[7] = {dw_gemm(dyc, s.act, g->wdown, n, d, F, dt, gdt),  dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt, gdt),
+                                  dw_gemm(s.up, s.m, g->wup, n, F, d, dt, gdt),    dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt, gdt),
+                                  dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt, gdt),    dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt, gdt),
+                                  dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt, gdt)};
         for (int i = 0; i < 7; ++i) dws[n_dws++] = mine[i];
         if (n_dws == 14 || ci == 0) {
           HIPCHK(gemm_batch(dws, n_dws, st));
@@ -341,6 +348,7 @@ int32_t streambp_layer_forward(const sbp_layer_cfg* c, const sbp_layer_weights* 
 static int32_t check_head_cfg(const sbp_head_cfg* c) {
   if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
   if (!valid_dtype(c->dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", c->dtype);
+  if (int32_t rc = check_grad_dtype(c->dtype, c->grad_dtype)) return rc;
   if (c->batch < 1 || c->seq_len < 1 || c->chunk < 1 || c->hidden < 1 || c->vocab < 1)
     return fail(SBP_ERR_SHAPE, "batch, seq_len, chunk, hidden and vocab must be >= 1");
   if (c->objective < SBP_OBJ_SFT || c->objective > SBP_OBJ_DPO) return fail(SBP_ERR_UNSUPPORTED, "objective %d not supported", c->objective);
@@ -385,7 +393,7 @@ size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg* cfg) {
 
 int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const void* h, const int32_t* targets,
                                     const float* old_logp, const float* ref_logp, const float* advantages, void* dh,
-                                    float* dw, float* loss, int64_t* n_active, void* workspace, size_t workspace_bytes,
+                                    void* dw, float* loss, int64_t* n_active, void* workspace, size_t workspace_bytes,
                                     void* hip_stream) {
   int32_t rc = check_head_cfg(c);
   if (rc) return rc;
@@ -439,7 +447,7 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
     gh.rows_dev = n_dev;
     HIPCHK(gemm(gh, st));
     HIPCHK(scatter_rows(dt, s.dhc, idx, n_dev, dh, n, d, st));
-    pending[n_pending] = dw_gemm(dz, hc, dw, n, V, d, dt);
+    pending[n_pending] = dw_gemm(dz, hc, dw, n, V, d, dt, c->grad_dtype);
     pending[n_pending].rows_dev = n_dev;
     if (++n_pending == HEAD_DW_GROUP || ci + 1 == n_chunks) {
       HIPCHK(gemm_batch(pending, n_pending, st));
@@ -447,7 +455,7 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
     }
   }
   if (c->objective == SBP_OBJ_DPO)
-    HIPCHK(dpo_finish(dt, s.ell, c->kl_beta, dh, rows * d, dw, (int64_t)V * d, loss, st));
+    HIPCHK(dpo_finish(dt, s.ell, c->kl_beta, dh, rows * d, dw, c->grad_dtype, (int64_t)V * d, loss, st));
   return SBP_OK;
 }
 
@@ -521,7 +529,7 @@ sbp_head_cfg stack_head_cfg(const sbp_stack_cfg* c) {
   sbp_head_cfg h{};
   h.dtype = c->layer.dtype; h.batch = c->layer.batch; h.seq_len = c->layer.seq_len; h.chunk = c->head_chunk;
   h.hidden = c->layer.hidden; h.vocab = c->vocab; h.objective = c->objective; h.loss_scale = c->loss_scale;
-  h.clip_eps = c->clip_eps; h.kl_beta = c->kl_beta; h.kl_mode = c->kl_mode;
+  h.clip_eps = c->clip_eps; h.kl_beta = c->kl_beta; h.kl_mode = c->kl_mode; h.grad_dtype = c->layer.grad_dtype;
   return h;
 }
 int32_t check_stack_cfg(const sbp_stack_cfg* c) {
@@ -576,7 +584,7 @@ extern "C" int32_t streambp_stack_forward(const sbp_stack_cfg* c, const sbp_laye
 extern "C" int32_t streambp_stack_backward(const sbp_stack_cfg* c, const sbp_layer_weights* layers, const void* g_final,
                                            const void* w_head, void* const* ckpt, const int32_t* ids, const int32_t* targets,
                                            const float* old_logp, const float* ref_logp, const float* advantages,
-                                           const sbp_layer_grads* dlayers, float* dg_final, float* dw_head, float* demb,
+                                           const sbp_layer_grads* dlayers, float* dg_final, void* dw_head, float* demb,
                                            void* dx0, float* loss, int64_t* n_active, void* workspace,
                                            size_t workspace_bytes, void* hip_stream) {
   int32_t rc = check_stack_cfg(c);

@@ -96,15 +96,15 @@ extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_d
 }
 
 // Weight-gradient form over several reduction segments through gemm_batch: C[M,N] += sum_s A_s^T B_s with
-// A_s [K_s, M], B_s [K_s, N] (row counts optionally limited by device integers).  Returns 1 if the segmented MFMA
-// kernel took it, 0 if it ran as separate launches.
+// A_s [K_s, M], B_s [K_s, N] (row counts optionally limited by device integers), C fp32 or bf16 (out_dt).  Returns 1 if
+// the segmented MFMA kernel took it, 0 if it ran as separate launches.
 extern "C" int streambp_debug_gemm_dw_segments(int n, int M, int N, const int* K, const void* const* A, const void* const* B,
-                                               const int* const* rows_dev, float* C, long long lda, long long ldb,
-                                               long long ldc, int in_dt, void* stream) {
+                                               const int* const* rows_dev, void* C, long long lda, long long ldb,
+                                               long long ldc, int in_dt, int out_dt, void* stream) {
   if (n < 1 || n > 8) return -2;
   sbp::GemmArgs gs[8];
   for (int i = 0; i < n; ++i) {
-    gs[i] = sbp::GemmArgs{A[i], B[i], C, M, N, K[i], lda, ldb, ldc, true, false, in_dt, sbp::DT_F32, true};
+    gs[i] = sbp::GemmArgs{A[i], B[i], C, M, N, K[i], lda, ldb, ldc, true, false, in_dt, out_dt, true};
     gs[i].rows_dev = rows_dev ? rows_dev[i] : nullptr;
   }
   const bool seg = !sbp::g_force_generic_gemm && sbp::gemm_mfma_seg_eligible(gs, n);
@@ -142,7 +142,7 @@ extern "C" int streambp_debug_profile_end(long long* count, double* ms, double* 
     count[r.kind] += 1; ms[r.kind] += t;
     (r.bounded ? work_bounded : work)[r.kind] += r.work;
   }
-  for (auto& e : g_pool) hipEventDestroy(e);
+  for (auto& e : g_pool) (void)hipEventDestroy(e);
   g_pool.clear();
   g_recs.clear();
   return rc;

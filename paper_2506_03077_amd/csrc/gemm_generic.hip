@@ -75,7 +75,8 @@ hipError_t gemm_generic(const GemmArgs& g, hipStream_t st) {
   gemm_generic_k<TI, TO, ACC><<<grid, 256, 0, st>>>((const TI*)g.A, (const TI*)g.B, (TO*)g.C, g.M, g.N, g.K, \
                                                     g.lda, g.ldb, g.ldc, g.ta ? 1 : 0, g.tb ? 1 : 0, g.rows_dev)
   if (g.in_dt == DT_BF16) {
-    if (g.out_dt == DT_BF16) GG(bf16_t, bf16_t, false);
+    if (g.out_dt == DT_BF16 && g.acc) GG(bf16_t, bf16_t, true);
+    else if (g.out_dt == DT_BF16) GG(bf16_t, bf16_t, false);
     else if (g.acc) GG(bf16_t, float, true);
     else GG(bf16_t, float, false);
   } else {

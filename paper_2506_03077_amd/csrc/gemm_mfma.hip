@@ -141,7 +141,9 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int n_tiles) {
 #define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
 
 // One 256x256 output tile: K range [k_begin, k_end).
-// MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store, C already offset)
+// MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store, C already offset),
+//       4 = accumulate into a bf16 C (read, add in fp32, round once; weight-gradient form only)
+constexpr bool mode_accumulates(int mode) { return mode == 2 || mode == 4; }
 //
 // The main loop is written so that it contains no vector ALU instructions at all: global addresses are an SGPR base
 // (advanced with scalar adds) plus per-lane offsets computed once, LDS fragment addresses are computed once per
@@ -292,6 +294,51 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
   // Epilogue.  Accumulator register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32.
   float* Cf = (float*)Cv;
   bf16_t* Cb = (bf16_t*)Cv;
+  if constexpr (MODE == 4) {
+    // bf16 C += acc, two columns (4 bytes) per lane and access: neighbouring lanes hold neighbouring columns, so for each
+    // register pair (r, r+1) the even lane takes row r of both columns and the odd lane row r+1 of both (one lane
+    // swap).  Every element has exactly one owner per launch: plain loads and stores, the sum is formed in fp32 and
+    // rounded once.  All loads of a 32-row block are issued before the first store so that the wave waits for C once
+    // per block, not once per element.
+    typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+    const bool odd = lane & 1;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      float lo[8][FN], hi[8][FN];
+      bf16x2 old[8][FN];
+#pragma unroll
+      for (int rp = 0; rp < 8; ++rp) {
+        const int r = 2 * rp;
+        const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) + (odd ? 1 : 0);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          float a0 = acc[i][j][r], a1 = acc[i][j][r + 1];
+          asm volatile("" : "+v"(a0), "+v"(a1));     // two plain registers: the select below stays a single v_cndmask
+          const float keep = odd ? a1 : a0;
+          const float send = odd ? a0 : a1;
+          const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, false));
+          lo[rp][j] = odd ? got : keep;
+          hi[rp][j] = odd ? keep : got;
+          const int64_t idx = (int64_t)row * ldc + n0 + wn0 + j * 32 + (lane & 31) - (odd ? 1 : 0);
+          if (row < M) old[rp][j] = *(const bf16x2*)(Cb + idx);
+        }
+      }
+#pragma unroll
+      for (int rp = 0; rp < 8; ++rp) {
+        const int r = 2 * rp;
+        const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) + (odd ? 1 : 0);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const int64_t idx = (int64_t)row * ldc + n0 + wn0 + j * 32 + (lane & 31) - (odd ? 1 : 0);
+          bf16x2 v;
+          v[0] = (bf16_t)((float)old[rp][j][0] + lo[rp][j]);
+          v[1] = (bf16_t)((float)old[rp][j][1] + hi[rp][j]);
+          if (row < M) *(bf16x2*)(Cb + idx) = v;
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -332,8 +379,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
     split = blockIdx.x / n_tiles;
     band_coords(xcd_contiguous_id(blockIdx.x % n_tiles, n_tiles), tiles_m, tiles_n, band_height(tiles_m, n_tiles, true), tm, tn);
   } else {
-    band_coords(MODE == 2 ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, n_tiles), tiles_m, tiles_n,
-                band_height(tiles_m, n_tiles, MODE != 2), tm, tn);
+    band_coords(mode_accumulates(MODE) ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, n_tiles), tiles_m, tiles_n,
+                band_height(tiles_m, n_tiles, !mode_accumulates(MODE)), tm, tn);
   }
   if (MODE == 3) Cv = (float*)Cv + (int64_t)split * M * ldc;   // partial slices are laid out for the host-side M
   if (rows_dev) {                     // run-time row count: rows are M (NT / NN) or the reduction K (dW form)
@@ -343,7 +390,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
   }
   const int k_begin = split * k_per_split;
   const int k_end = min(K, k_begin + k_per_split);
-  if (k_end <= k_begin && MODE == 2) return;   // nothing to add
+  if (k_end <= k_begin && mode_accumulates(MODE)) return;   // nothing to add
   KSegments segs;
   segs.n = 1; segs.A[0] = A; segs.B[0] = B; segs.K[0] = K; segs.k_begin[0] = k_begin; segs.k_end[0] = k_end;
   gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem);
@@ -352,7 +399,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
 // Weight-gradient form with a segmented reduction: C += sum_s A_s^T B_s, every segment with its own run-time row
 // count.  One pass over C (one atomic add per element) for several chunks' worth of rows.
 struct SegLaunch { const bf16_t* A[MAX_SEG]; const bf16_t* B[MAX_SEG]; const int* rows_dev[MAX_SEG]; int K[MAX_SEG]; int n; };
-__global__ __launch_bounds__(NTHREADS) void gemm_mfma_seg_k(const SegLaunch sl, float* __restrict__ C, int M, int N, int64_t lda,
+template <bool C_BF16>
+__global__ __launch_bounds__(NTHREADS) void gemm_mfma_seg_k(const SegLaunch sl, void* __restrict__ C, int M, int N, int64_t lda,
                                                             int64_t ldb, int64_t ldc) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
@@ -369,7 +417,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_seg_k(const SegLaunch sl, 
     total += K;
   }
   if (total == 0) return;   // nothing to add
-  gemm_tile<true, false, 2>(segs, C, M, N, lda, ldb, ldc, tm, tn, smem);
+  gemm_tile<true, false, C_BF16 ? 4 : 2>(segs, C, M, N, lda, ldb, ldc, tm, tn, smem);
 }
 
 // Several independent GEMMs of one layout / output mode in a single launch: the tiles of all problems form one
@@ -387,14 +435,14 @@ struct GroupArgs { GroupProblem p[MAX_GROUP]; int n; int total_tiles; };
 template <bool TA, bool TB, int MODE>
 __global__ __launch_bounds__(NTHREADS) void gemm_mfma_group_k(const GroupArgs ga) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];
-  const int id = MODE == 2 ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, ga.total_tiles);
+  const int id = mode_accumulates(MODE) ? (int)blockIdx.x : xcd_contiguous_id(blockIdx.x, ga.total_tiles);
   int pi = 0;
 #pragma unroll
   for (int i = 1; i < MAX_GROUP; ++i)
     if (i < ga.n && id >= ga.p[i].tile_begin) pi = i;
   const GroupProblem& g = ga.p[pi];
   int tm, tn;
-  band_coords(id - g.tile_begin, g.tiles_m, g.tiles_n, band_height(g.tiles_m, g.tiles_m * g.tiles_n, MODE != 2), tm, tn);
+  band_coords(id - g.tile_begin, g.tiles_m, g.tiles_n, band_height(g.tiles_m, g.tiles_m * g.tiles_n, !mode_accumulates(MODE)), tm, tn);
   KSegments segs;
   segs.n = g.nseg;
 #pragma unroll
@@ -415,8 +463,10 @@ __global__ void splitk_reduce_k(const float* __restrict__ part, void* __restrict
     s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
   }
   if (OUT_BF16) {
+    bf16x4* c = (bf16x4*)((bf16_t*)C + i);
+    if (ACC) { const bf16x4 t = *c; s.x += (float)t[0]; s.y += (float)t[1]; s.z += (float)t[2]; s.w += (float)t[3]; }
     bf16x4 o; o[0] = (bf16_t)s.x; o[1] = (bf16_t)s.y; o[2] = (bf16_t)s.z; o[3] = (bf16_t)s.w;
-    *(bf16x4*)((bf16_t*)C + i) = o;
+    *c = o;
   } else {
     float4* c = (float4*)((float*)C + i);
     if (ACC) { float4 t = *c; s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w; }
@@ -426,7 +476,7 @@ __global__ void splitk_reduce_k(const float* __restrict__ part, void* __restrict
 
 bool gemm_mfma_eligible(const GemmArgs& g) {
   if (g.in_dt != DT_BF16) return false;
-  if (g.acc && g.out_dt != DT_F32) return false;
+  if (g.acc && g.out_dt != DT_F32 && !(g.out_dt == DT_BF16 && g.ta && !g.tb)) return false;   // bf16 C += : dW form only
   if (g.M < 1 || g.N < BN || g.K < 1) return false;
   if (g.N % BN != 0) return false;
   if (g.ta && !g.tb) {                       // TN: both operands reduction-major; ragged K allowed
@@ -486,7 +536,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
     else LAUNCH(true, false, MODE, CPTR);               \
   } while (0)
   const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
-  const int mode = splits > 1 ? 3 : (g.out_dt == DT_BF16 ? 1 : (g.acc ? 2 : 0));
+  const int mode = splits > 1 ? 3 : (g.acc ? 2 : (g.out_dt == DT_BF16 ? 1 : 0));   // (both accumulate forms are timed as one kind)
   const int kind = prof::GEMM_SINGLE + layout * 4 + mode;
   const double work = 2.0 * g.M * g.N * g.K;
   if (splits > 1) {
@@ -498,13 +548,15 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
     if (e != hipSuccess) return e;
     const int64_t n = (int64_t)g.M * g.N;
     const unsigned blocks = (unsigned)cdiv(n / 4, 256);
-    if (g.out_dt == DT_BF16) splitk_reduce_k<true, false><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
+    if (g.out_dt == DT_BF16 && g.acc) splitk_reduce_k<true, true><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
+    else if (g.out_dt == DT_BF16) splitk_reduce_k<true, false><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
     else if (g.acc) splitk_reduce_k<false, true><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
     else splitk_reduce_k<false, false><<<blocks, 256, 0, st>>>(g.scratch, g.C, n, splits);
     return hipGetLastError();
   }
   prof::Scope sc(kind, work, g.rows_dev != nullptr, st);
-  if (g.out_dt == DT_BF16) LAUNCH_LAYOUT(1, g.C);
+  if (g.out_dt == DT_BF16 && g.acc) LAUNCH(true, false, 4, g.C);
+  else if (g.out_dt == DT_BF16) LAUNCH_LAYOUT(1, g.C);
   else if (g.acc) LAUNCH_LAYOUT(2, g.C);
   else LAUNCH_LAYOUT(0, g.C);
 #undef LAUNCH_LAYOUT
@@ -569,7 +621,7 @@ hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
   double work = 0.0;
   for (int i = 0; i < n; ++i) work += 2.0 * gs[i].M * gs[i].N * gs[i].K;
   const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
-  const int mode = g.out_dt == DT_BF16 ? 1 : (g.acc ? 2 : 0);
+  const int mode = g.acc ? 2 : (g.out_dt == DT_BF16 ? 1 : 0);
   prof::Scope sc(prof::GEMM_GROUP + layout * 4 + mode, work, false, st);
 #define GLAUNCH(TA, TB, MODE) gemm_mfma_group_k<TA, TB, MODE><<<tiles, NTHREADS, 0, st>>>(ga)
 #define GLAUNCH_LAYOUT(MODE)                     \
@@ -578,7 +630,8 @@ hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
     else if (!g.ta && !g.tb) GLAUNCH(false, false, MODE); \
     else GLAUNCH(true, false, MODE);             \
   } while (0)
-  if (g.out_dt == DT_BF16) GLAUNCH_LAYOUT(1);
+  if (g.out_dt == DT_BF16 && g.acc) GLAUNCH(true, false, 4);
+  else if (g.out_dt == DT_BF16) GLAUNCH_LAYOUT(1);
   else if (g.acc) GLAUNCH_LAYOUT(2);
   else GLAUNCH_LAYOUT(0);
 #undef GLAUNCH_LAYOUT
@@ -586,13 +639,13 @@ hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
   return hipGetLastError();
 }
 
-// Segmented weight-gradient launch: gs[0..n) are accumulate-form (TN, fp32 C +=) problems that share C, M, N and the
+// Segmented weight-gradient launch: gs[0..n) are accumulate-form (TN, fp32 or bf16 C +=) problems that share C, M, N and the
 // leading dimensions and differ in A, B, K and rows_dev.
 bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n) {
   if (n < 2 || n > MAX_SEG) return false;
   for (int i = 0; i < n; ++i) {
     const GemmArgs& g = gs[i];
-    if (!gemm_mfma_eligible(g) || !g.ta || g.tb || !g.acc || g.out_dt != DT_F32) return false;
+    if (!gemm_mfma_eligible(g) || !g.ta || g.tb || !g.acc || g.out_dt != gs[0].out_dt) return false;
     if (g.C != gs[0].C || g.M != gs[0].M || g.N != gs[0].N || g.lda != gs[0].lda || g.ldb != gs[0].ldb || g.ldc != gs[0].ldc) return false;
   }
   return true;
@@ -610,7 +663,8 @@ hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st) {
   const GemmArgs& g = gs[0];
   const int tiles = (int)cdiv(g.M, BM) * (g.N / BN);
   prof::Scope sc(prof::GEMM_SEG, work, bounded, st);
-  gemm_mfma_seg_k<<<tiles, NTHREADS, 0, st>>>(sl, (float*)g.C, g.M, g.N, g.lda, g.ldb, g.ldc);
+  if (g.out_dt == DT_BF16) gemm_mfma_seg_k<true><<<tiles, NTHREADS, 0, st>>>(sl, g.C, g.M, g.N, g.lda, g.ldb, g.ldc);
+  else gemm_mfma_seg_k<false><<<tiles, NTHREADS, 0, st>>>(sl, g.C, g.M, g.N, g.lda, g.ldb, g.ldc);
   return hipGetLastError();
 }
 

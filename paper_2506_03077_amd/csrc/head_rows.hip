@@ -210,9 +210,9 @@ hipError_t count_active(const int32_t* targets, int B, int T, float* seq_weight,
   return hipGetLastError();
 }
 
-template <typename T>
+template <typename T, typename TW>
 __global__ void dpo_finish_k(const float* __restrict__ ell, float beta, T* __restrict__ dh, int64_t n_dh,
-                             float* __restrict__ dw, int64_t n_dw, float* __restrict__ loss) {
+                             TW* __restrict__ dw, int64_t n_dw, float* __restrict__ loss) {
   const float x = beta * (*ell);
   const float sig = 1.0f / (1.0f + expf(-x));
   const float factor = sig - 1.0f;
@@ -221,14 +221,15 @@ __global__ void dpo_finish_k(const float* __restrict__ ell, float beta, T* __res
   if (i == 0) *loss += (x > -30.f) ? log1pf(expf(-x)) : -x;
   for (; i < n_dh + n_dw; i += stride) {
     if (i < n_dh) stf(dh + i, ldf(dh + i) * factor);
-    else dw[i - n_dh] *= factor;
+    else stf(dw + (i - n_dh), ldf(dw + (i - n_dh)) * factor);
   }
 }
-hipError_t dpo_finish(int dt, const float* ell, float beta, void* dh, int64_t n_dh, float* dw, int64_t n_dw,
+hipError_t dpo_finish(int dt, const float* ell, float beta, void* dh, int64_t n_dh, void* dw, int dw_dt, int64_t n_dw,
                       float* loss, hipStream_t st) {
   unsigned grid = (unsigned)std::min<int64_t>(cdiv(n_dh + n_dw, 256), 256 * 16);
-  if (dt == DT_BF16) dpo_finish_k<bf16_t><<<grid, 256, 0, st>>>(ell, beta, (bf16_t*)dh, n_dh, dw, n_dw, loss);
-  else dpo_finish_k<float><<<grid, 256, 0, st>>>(ell, beta, (float*)dh, n_dh, dw, n_dw, loss);
+  if (dt == DT_BF16 && dw_dt == DT_BF16) dpo_finish_k<bf16_t, bf16_t><<<grid, 256, 0, st>>>(ell, beta, (bf16_t*)dh, n_dh, (bf16_t*)dw, n_dw, loss);
+  else if (dt == DT_BF16) dpo_finish_k<bf16_t, float><<<grid, 256, 0, st>>>(ell, beta, (bf16_t*)dh, n_dh, (float*)dw, n_dw, loss);
+  else dpo_finish_k<float, float><<<grid, 256, 0, st>>>(ell, beta, (float*)dh, n_dh, (float*)dw, n_dw, loss);
   return hipGetLastError();
 }
 

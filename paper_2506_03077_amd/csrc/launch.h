@@ -129,7 +129,7 @@ hipError_t compact_active(const int32_t* targets, int64_t rows, int chunk, int32
 hipError_t gather_rows(int dt, const void* src, const int32_t* index, const int* rows_dev, void* dst, int max_rows, int d, hipStream_t st);
 hipError_t scatter_rows(int dt, const void* src, const int32_t* index, const int* rows_dev, void* dst, int max_rows, int d, hipStream_t st);
 // DPO fix-up: factor = sigmoid(beta*ell)-1 ; scales dh (dt) and dw (fp32) in place, loss += -log sigmoid(beta*ell)
-hipError_t dpo_finish(int dt, const float* ell, float beta, void* dh, int64_t n_dh, float* dw, int64_t n_dw,
+hipError_t dpo_finish(int dt, const float* ell, float beta, void* dh, int64_t n_dh, void* dw, int dw_dt, int64_t n_dw,
                       float* loss, hipStream_t st);
 
 }  // namespace sbp

@@ -75,6 +75,7 @@ def test_head_workspace_is_per_chunk():
 @pytest.mark.parametrize("kw,code", [
     (dict(n_q_heads=4, n_kv_heads=3), -2), (dict(head_dim=15), -2), (dict(chunk=0), -2), (dict(seq_len=0), -2),
     (dict(dtype=7), -3), (dict(head_dim=512), -2),
+    (dict(grad_dtype=7), -3), (dict(grad_dtype=sb.SBP_BF16), -3),      # bf16 gradients only next to bf16 weights
 ])
 def test_layer_bad_config_codes(kw, code):
     cfg = good_layer_cfg(**kw)
@@ -104,6 +105,8 @@ def test_head_and_attn_codes():
     L = sb.lib()
     hc = sb.head_cfg(sb.SBP_F32, 1, 8, 4, 8, 16, objective=5)
     assert sb.streambp_lmhead_workspace_bytes(hc) == 0
+    assert sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_F32, 1, 8, 4, 8, 16, grad_dtype=sb.SBP_BF16)) == 0
+    assert sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_BF16, 1, 8, 4, 8, 16, grad_dtype=sb.SBP_BF16)) > 0
     hc = sb.head_cfg(sb.SBP_F32, 1, 8, 4, 8, 16, objective=sb.SBP_OBJ_GRPO)
     need = sb.streambp_lmhead_workspace_bytes(hc)
     args = [256] * 4

@@ -18,7 +18,7 @@ def run(M, N, K, ta, tb, out="f32", acc=False, seed=0, expect_mfma=None, dtype="
     rng = np.random.default_rng(seed)
     A = synth.to_storage(rng.normal(size=(K, M) if ta else (M, K)), dtype)
     B = synth.to_storage(rng.normal(size=(N, K) if tb else (K, N)), dtype)
-    C0 = rng.normal(size=(M, N)).astype(np.float32) if acc else np.zeros((M, N), np.float32)
+    C0 = synth.to_storage(rng.normal(size=(M, N)), out) if acc else np.zeros((M, N), np.float32)
     opA = A.T.astype(np.float64) if ta else A.astype(np.float64)
     opB = B.T.astype(np.float64) if tb else B.astype(np.float64)
     want = opA @ opB + C0
@@ -95,6 +95,24 @@ def test_mfma_segmented_weight_gradient():
             part = part + A[:k].T.astype(np.float64) @ B[:k].astype(np.float64)
         assert_close(host(Cd), part, 2e-5, f"segmented dW, {n} segments")
     assert part.shape == want.shape
+
+
+def test_weight_gradient_into_bf16_accumulator():
+    # C (bf16) += A^T B: read, add in fp32, round once
+    run(512, 768, 320, True, False, out="bf16", acc=True, expect_mfma=True, seed=6)     # one launch, ragged reduction
+    run(512, 256, 2048, True, False, out="bf16", acc=True, expect_mfma=True, seed=7)    # split-K, reduced into the bf16 C
+    run(130, 172, 64, True, False, out="bf16", acc=True, expect_mfma=False, seed=8)     # shape-agnostic kernel
+    rng = np.random.default_rng(9)
+    M, N, Ks = 512, 256, (300, 200)
+    As = [synth.to_storage(rng.normal(size=(K, M)), "bf16") for K in Ks]
+    Bs = [synth.to_storage(rng.normal(size=(K, N)), "bf16") for K in Ks]
+    C0 = synth.to_storage(rng.normal(size=(M, N)), "bf16")
+    want = C0.astype(np.float64) + sum(A.T.astype(np.float64) @ B.astype(np.float64) for A, B in zip(As, Bs))
+    Cd = dev(C0, "bf16")
+    used = sb.debug_gemm_dw_segments([dev(a, "bf16") for a in As], [dev(b, "bf16") for b in Bs], Cd, M, N, Ks)
+    torch.cuda.synchronize()
+    assert used == 1
+    assert_close(host(Cd), want, 4e-3, "segmented dW into bf16")
 
 
 def test_mfma_bigger_square():

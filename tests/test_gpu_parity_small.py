@@ -25,15 +25,16 @@ MID32 = dict(MID16, dtype="f32")
 ODD16 = dict(dtype="bf16", hidden=72, n_q_heads=6, n_kv_heads=2, head_dim=24, mlp_width=172, vocab=333)
 
 
-def run_layer_case(cfg, T, chunk, batch=1, seed=0, pos_offset=0):
+def run_layer_case(cfg, T, chunk, batch=1, seed=0, pos_offset=0, grad_dtype="f32"):
     cfg = dict(cfg, pos_offset=pos_offset)
     inp = synth.layer_inputs(cfg, seed=seed, seq_len=T, batch=batch)
     _, dx_ref, g_ref = o_layer.layer_forward_backward(inp["x"], inp["w"], oracle_cfg(cfg), inp["dy"])
     dt = cfg["dtype"]
     w = {k: dev(v, dt) for k, v in inp["w"].items()}
     x, dy = dev(inp["x"], dt), dev(inp["dy"], dt)
-    dx, dw = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, chunk, batch), w, x, dy)
+    dx, dw = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, chunk, batch, grad_dtype), w, x, dy)
     torch.cuda.synchronize()
+    assert all(dw[n].dtype == (torch.float32 if n in ("g1", "g2") else tdtype(grad_dtype)) for n in sb.WEIGHT_NAMES)
     tol = TOL[dt]
     errs = {"dx": assert_close(host(dx), dx_ref, tol, f"dx (chunk {chunk})")}
     for n in sb.WEIGHT_NAMES:
@@ -57,6 +58,22 @@ def test_layer_backward_mid_bf16(chunk):
 
 def test_layer_backward_mid_bf16_ragged_rows():
     run_layer_case(MID16, 333, 100, batch=2, seed=1)
+
+
+# shapes whose weight gradients have enough output tiles for the grouped launch
+BIG16 = dict(dtype="bf16", hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, mlp_width=4096, vocab=1024)
+
+
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_layer_backward_grouped_weight_gradients(grad_dtype):
+    run_layer_case(BIG16, 512, 128, grad_dtype=grad_dtype)
+
+
+@pytest.mark.parametrize("cfg,T,chunk,batch", [(MID16, 640, 128, 1), (MID16, 333, 100, 2), (ODD16, 150, 64, 2)])
+def test_layer_backward_bf16_weight_gradients(cfg, T, chunk, batch):
+    # App. B.1: bf16 weights and gradients.  The accumulators are rounded to bf16 once per pass over them
+    # (one pass per two chunks); the bound stays the bf16 one.
+    run_layer_case(cfg, T, chunk, batch=batch, grad_dtype="bf16")
 
 
 def test_layer_backward_mid_fp32():
@@ -104,30 +121,33 @@ def test_gradients_accumulate_into_dw():
 
 
 # ------------------------------------------------------------------- head ---
-def head_case(cfg, B, T, chunk, objective, seed=0, **kw):
+def head_case(cfg, B, T, chunk, objective, seed=0, grad_dtype="f32", **kw):
     inp = synth.head_inputs(cfg, seed=seed, seq_len=T, batch=B, vocab=cfg["vocab"])
     dt = cfg["dtype"]
     h, w, tg = dev(inp["h"], dt), dev(inp["w"], dt), torch.from_numpy(inp["targets"]).cuda()
     extras = synth.grpo_extras(B, T, seed)
     if objective == "sft":
         ref = o_head.sft(inp["h"], inp["w"], inp["targets"], kw.get("loss_scale", 1.0))
-        hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, kw.get("loss_scale", 1.0))
+        hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, kw.get("loss_scale", 1.0),
+                         grad_dtype=code(grad_dtype))
         out = sb.streambp_lmhead_ce_backward(hc, w, h, tg)
     elif objective == "grpo":
         old = kw.get("old")
         ref = o_head.grpo(inp["h"], inp["w"], inp["targets"], extras["advantages"], extras["ref_logp"], old,
                           0.2, 0.04, kw.get("kl_mode", 0))
         hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_GRPO, 1.0, 0.2, 0.04,
-                         kw.get("kl_mode", 0))
+                         kw.get("kl_mode", 0), grad_dtype=code(grad_dtype))
         out = sb.streambp_lmhead_ce_backward(
             hc, w, h, tg, None if old is None else torch.from_numpy(old.astype(np.float32)).cuda(),
             torch.from_numpy(extras["ref_logp"]).cuda(), torch.from_numpy(extras["advantages"]).cuda())
     else:
         ref = o_head.dpo(inp["h"], inp["w"], inp["targets"], extras["ref_logp"], beta=0.3)
-        hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_DPO, 1.0, 0.2, 0.3, 0)
+        hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_DPO, 1.0, 0.2, 0.3, 0,
+                         grad_dtype=code(grad_dtype))
         out = sb.streambp_lmhead_ce_backward(hc, w, h, tg, None, torch.from_numpy(extras["ref_logp"]).cuda(), None)
     torch.cuda.synchronize()
     dh, dw, loss, n_active = out
+    assert dw.dtype == tdtype(grad_dtype)
     tol = TOL[dt]
     assert int(n_active.item()) == ref["n_active"]                       # integer: exact
     assert_close(host(dh), ref["dh"], tol, "dh")
@@ -167,6 +187,13 @@ def test_head_grpo_off_policy_with_clipping():
 
 def test_head_dpo():
     head_case(TINY, 2, 64, 24, "dpo")
+
+
+@pytest.mark.parametrize("objective", ["sft", "grpo", "dpo"])
+def test_head_bf16_weight_gradient(objective):
+    # dW kept in bf16 (App. B.1); for DPO the final rescale by sigmoid(beta * ell) - 1 runs on the bf16 tensor
+    head_case(MID16, 2, 300, 64, objective, grad_dtype="bf16", loss_scale=1.0 / 450)
+    head_case(ODD16, 2, 150, 64, objective, grad_dtype="bf16", loss_scale=1.0 / 225)
 
 
 # -------------------------------------------------------------- attention ---
