@@ -35,8 +35,9 @@ def oracle_stack(ids, emb, layers, g_final, w_head, targets, cfg, loss_scale):
                 n_active=hd["n_active"])
 
 
-@pytest.mark.parametrize("name,L,T,chunk,head_chunk", [("tiny", 3, 256, 64, 100), ("mid16", 2, 300, 128, 128)])
-def test_stack_forward_backward(name, L, T, chunk, head_chunk):
+@pytest.mark.parametrize("name,L,T,chunk,head_chunk,grad_dtype", [("tiny", 3, 256, 64, 100, "f32"), ("mid16", 2, 300, 128, 128, "f32"),
+                                                                   ("mid16", 2, 300, 128, 128, "bf16")])
+def test_stack_forward_backward(name, L, T, chunk, head_chunk, grad_dtype):
     cfg = dict(synth.CONFIGS["tiny"]) if name == "tiny" else dict(dtype="bf16", hidden=256, n_q_heads=4, n_kv_heads=2,
                                                                   head_dim=128, mlp_width=512, vocab=1024)
     dt = cfg["dtype"]
@@ -50,7 +51,7 @@ def test_stack_forward_backward(name, L, T, chunk, head_chunk):
     ref = oracle_stack(tok["ids"], emb, layers, g_final, w_head, tok["targets"], cfg, 1.0 / n_act)
 
     lw = [{k: dev(v, dt) for k, v in w.items()} for w in layers]
-    lc = lib_layer_cfg(cfg, T, chunk)
+    lc = lib_layer_cfg(cfg, T, chunk, grad_dtype=grad_dtype)
     sc = sb.stack_cfg(lc, L, cfg["vocab"], head_chunk, sb.SBP_OBJ_SFT, 1.0 / n_act)
     ckpt = [torch.empty((1, T, cfg["hidden"]), dtype=torch.bfloat16 if dt == "bf16" else torch.float32, device="cuda")
             for _ in range(L + 1)]
@@ -65,6 +66,8 @@ def test_stack_forward_backward(name, L, T, chunk, head_chunk):
     assert_close(host(ckpt[L])[0], ref["y_last"], ftol, "stack output")
     assert int(out["n_active"].item()) == ref["n_active"] == n_act
     assert abs(float(out["loss"].item()) - ref["loss"]) <= ftol * abs(ref["loss"])
+    want = torch.bfloat16 if grad_dtype == "bf16" else torch.float32
+    assert out["dw_head"].dtype == want and all(out["dlayers"][l]["wq"].dtype == want for l in range(L))
     assert_close(host(out["dw_head"]), ref["dw_head"], tol, "dw_head")
     assert_close(host(out["dg_final"]), ref["dg_final"], tol, "dg_final")
     assert_close(host(out["dx0"])[0], ref["dx0"], tol, "dx0")
