@@ -123,3 +123,74 @@ def test_head_32k_structure_and_sampled_rows():
     ts = tg[0, rows].cpu().numpy()[None]
     ref = o_head.sft(hs, w64, ts, 1.0 / n_act)
     assert_close(host(dh[0, rows]), ref["dh"][0], TOL, "dh sampled rows")
+
+
+# ---------------------------------------------------- the other workloads of the shape list ---
+LLAMA = synth.CONFIGS["llama_layer"]
+
+
+def test_llama_layer_widths_vs_oracle_and_8k_chunk_invariance():
+    # Llama-style layer (d=4096, 32q/8kv x128, F=14336): element by element against the oracle at a length it
+    # finishes in seconds, then the real shape (T=8192, chunk 1024) against itself at another chunk size.
+    T, chunk = 768, 256
+    inp = synth.layer_inputs(LLAMA, seed=4, seq_len=T)
+    _, dx_ref, g_ref = o_layer.layer_forward_backward(inp["x"], inp["w"], oracle_cfg(LLAMA), inp["dy"])
+    w = {k: dev(v, "bf16") for k, v in inp["w"].items()}
+    dx, dw = sb.streambp_layer_backward(lib_layer_cfg(LLAMA, T, chunk), w, dev(inp["x"], "bf16"), dev(inp["dy"], "bf16"))
+    torch.cuda.synchronize()
+    assert_close(host(dx), dx_ref, TOL, "dx")
+    for n in sb.WEIGHT_NAMES:
+        assert_close(host(dw[n]), g_ref[n], TOL, f"d{n}")
+    T = LLAMA["seq_len"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    x = torch.randn((1, T, LLAMA["hidden"]), generator=gen, device="cuda").to(torch.bfloat16)
+    dy = (torch.randn((1, T, LLAMA["hidden"]), generator=gen, device="cuda") * 1e-3).to(torch.bfloat16)
+    dx_a, dw_a = sb.streambp_layer_backward(lib_layer_cfg(LLAMA, T, LLAMA["chunk"]), w, x, dy)
+    dx_b, dw_b = sb.streambp_layer_backward(lib_layer_cfg(LLAMA, T, 3000), w, x, dy)       # ragged chunks
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dx_a.float()).all())
+    assert relerr(host(dx_b), host(dx_a)) < 1e-2
+    for n in sb.WEIGHT_NAMES:
+        assert relerr(host(dw_b[n]), host(dw_a[n])) < 1e-2, n
+
+
+def test_grpo_group_of_8_structure_sampled_rows_and_batch_independence():
+    # GRPO workload: 8 sequences x 16384 tokens, response = last 75 % of every sequence, on-policy, reference
+    # log-probs N(-2, 0.5), one advantage per sequence.
+    cfg = synth.CONFIGS["grpo"]
+    B, T, V, d = cfg["batch"], cfg["seq_len"], cfg["vocab"], cfg["hidden"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(6)
+    w = (torch.randn((V, d), generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+    h = torch.randn((B, T, d), generator=gen, device="cuda").to(torch.bfloat16)
+    tg = torch.randint(0, V, (B, T), generator=gen, device="cuda", dtype=torch.int32)
+    tg[:, :T // 4] = -1
+    adv = torch.randn((B,), generator=gen, device="cuda")
+    ref_logp = torch.randn((B, T), generator=gen, device="cuda") * 0.5 - 2.0
+    T_o = T - T // 4
+    hc = sb.head_cfg(sb.SBP_BF16, B, T, 2048, d, V, sb.SBP_OBJ_GRPO, 1.0, 0.2, 0.04, 1)
+    dh, dw, loss, n_active = sb.streambp_lmhead_ce_backward(hc, w, h, tg, None, ref_logp, adv)
+    torch.cuda.synchronize()
+    assert int(n_active.item()) == B * T_o                                 # integer: exact
+    assert torch.all(dh[:, :T // 4] == 0)                                  # prompt rows: exact zeros
+    assert bool(torch.isfinite(dh.float()).all()) and bool(torch.isfinite(loss).all())
+    assert dw.sum(dim=0).abs().max().item() < 1e-3 * dw.abs().max().item() * np.sqrt(V)   # rows of dz sum to zero
+    # Two response rows per sequence, one by one with the oracle.  Given only those rows the oracle normalises by
+    # T_o = 2 per sequence instead of the real count, so its gradient is scaled by 2 / T_o.
+    rows = [T // 4, T - 1]
+    ref = o_head.grpo(h[:, rows].double().cpu().numpy(), w.double().cpu().numpy(), tg[:, rows].cpu().numpy(),
+                      adv.double().cpu().numpy(), ref_logp[:, rows].double().cpu().numpy(), None, 0.2, 0.04, 1)
+    assert_close(host(dh[:, rows]), ref["dh"] * (len(rows) / T_o), TOL, "dh sampled rows")
+    del dw, dh
+    # Layer: the sequences of a batch do not interact, so sequence 3 alone reproduces its rows of dx bit for bit.
+    Hq, Hkv, dhd, F = (cfg[k] for k in ("n_q_heads", "n_kv_heads", "head_dim", "mlp_width"))
+    rn = lambda shape, std, mean=0.0: (torch.randn(shape, generator=gen, device="cuda") * std + mean).to(torch.bfloat16)
+    lw = dict(wq=rn((Hq * dhd, d), 0.02), wk=rn((Hkv * dhd, d), 0.02), wv=rn((Hkv * dhd, d), 0.02), wo=rn((d, Hq * dhd), 0.02),
+              wgate=rn((F, d), 0.02), wup=rn((F, d), 0.02), wdown=rn((d, F), 0.02), g1=rn((d,), 0.02, 1.0), g2=rn((d,), 0.02, 1.0))
+    x, dy = rn((B, T, d), 1.0), rn((B, T, d), 1e-3)
+    dx_all, dw_all = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, 2048, batch=B), lw, x, dy)
+    dx_one, dw_one = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, 2048, batch=1), lw, x[3:4].contiguous(), dy[3:4].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(dx_all[3], dx_one[0])
+    assert bool(torch.isfinite(dx_all.float()).all())
+    # Eq. 1 over sequences: the batch's weight gradient is the sum of the per-sequence ones
+    assert dw_all["wdown"].norm().item() > dw_one["wdown"].norm().item()
