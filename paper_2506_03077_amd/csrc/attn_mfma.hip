@@ -495,9 +495,6 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) breg[ks] = *(const bf16x8*)(src + ks * 16);
   }
-  f32x16 acc[4];   // dV^T (role P) or dK^T (role S): rows = head_dim, column = my key
-#pragma unroll
-  for (int i = 0; i < 4; ++i) acc[i] = zero16();
   const float sl = scale * LOG2E;
 
   // query tiles that can see at least one key of this workgroup: query position >= key0
@@ -521,7 +518,7 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
   auto tile_active = [&](int qbase) { return kw0 < n_total && q_start + min(qbase + QT, c) - 1 >= kw0; };
   auto lds_f4 = [](uint32_t addr) { return *(const float4*)(__attribute__((address_space(3))) const char*)(uintptr_t)addr; };
 
-  auto p_step = [&](int it, auto stage_c, int par) {
+  auto p_step = [&](f32x16 (&acc)[4], int it, auto stage_c, int par) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
     constexpr uint32_t so = (stage & 1) * 2 * TILE64_BYTES;        // offset of the stage from its address set
     const FragPre& fr = stage < 2 ? f0 : f2;
@@ -565,7 +562,7 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
     }
   };
 
-  auto s_step = [&](int it, auto stage_c, int par) {
+  auto s_step = [&](f32x16 (&acc)[4], int it, auto stage_c, int par) __attribute__((always_inline)) {
     constexpr int stage = decltype(stage_c)::value;
     constexpr uint32_t so = (stage & 1) * 2 * TILE64_BYTES;
     const FragPre& fr = stage < 2 ? f0 : f2;
@@ -599,41 +596,53 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
   // tile j has landed for everyone, P of tile j-1 is written, and the stage and the P slot about to be
   // overwritten (those of tile j-2) are no longer read.  Tile j lives in stage j % 3; the loop is unrolled by three
   // so that every stage offset is an immediate.
+  // The whole loop exists once per role (the role is a compile-time constant inside it): with one loop and a role
+  // branch in its body the register allocator gives the accumulator different homes in the two branches and copies
+  // all 64 registers in and out at every step.  Both copies execute the same number of barriers.
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
   using S2 = std::integral_constant<int, 2>;
-  auto body = [&](int j, auto st_p, auto st_s, int st_next) {
-    WAIT_VM0();
-    __syncthreads();
-    if (j + 1 < n_iter) issue(j + 1, st_next);
-    if (role_p) {
-      if (j < n_iter) p_step(j, st_p, j & 1);
-    } else {
-      if (j > 0) s_step(j - 1, st_s, (j - 1) & 1);
+  auto run = [&](auto role_c) __attribute__((always_inline)) {
+    constexpr bool RP = decltype(role_c)::value;
+    f32x16 acc[4];   // dV^T (role P) or dK^T (role S): rows = head_dim, column = my key
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = zero16();
+    auto body = [&](int j, auto st_p, auto st_s, int st_next) __attribute__((always_inline)) {
+      WAIT_VM0();
+      __syncthreads();
+      if (j + 1 < n_iter) issue(j + 1, st_next);
+      if constexpr (RP) {
+        if (j < n_iter) p_step(acc, j, st_p, j & 1);
+      } else {
+        if (j > 0 && j <= n_iter) s_step(acc, j - 1, st_s, (j - 1) & 1);
+      }
+    };
+    if (n_iter > 0) {
+      issue(0, 0);
+      // always whole groups of three steps (a step past the last tile is a barrier and nothing else): a loop with
+      // exits between the unrolled steps makes the compiler shuttle the accumulator between register sets
+      for (int j = 0; j <= n_iter; j += 3) {
+        body(j, S0{}, S2{}, 1);
+        body(j + 1, S1{}, S0{}, 2);
+        body(j + 2, S2{}, S1{}, 0);
+      }
+    }
+    if (my_key < n_total) {
+      float* out = (RP ? dv : dk) + (int64_t)my_key * kv_stride + (int64_t)kvh * DH;
+      const float f = RP ? 1.0f : scale;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          const int d0 = i * 32 + 8 * a + 4 * half;
+          float4 u = *(float4*)(out + d0);
+          u.x += acc[i][4 * a + 0] * f; u.y += acc[i][4 * a + 1] * f; u.z += acc[i][4 * a + 2] * f; u.w += acc[i][4 * a + 3] * f;
+          *(float4*)(out + d0) = u;
+        }
     }
   };
-  if (n_iter > 0) {
-    issue(0, 0);
-    for (int j = 0; j <= n_iter; j += 3) {
-      body(j, S0{}, S2{}, 1);
-      if (j + 1 <= n_iter) body(j + 1, S1{}, S0{}, 2);
-      if (j + 2 <= n_iter) body(j + 2, S2{}, S1{}, 0);
-    }
-  }
-
-  if (my_key < n_total) {
-    float* out = (role_p ? dv : dk) + (int64_t)my_key * kv_stride + (int64_t)kvh * DH;
-    const float f = role_p ? 1.0f : scale;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int d0 = i * 32 + 8 * a + 4 * half;
-        float4 u = *(float4*)(out + d0);
-        u.x += acc[i][4 * a + 0] * f; u.y += acc[i][4 * a + 1] * f; u.z += acc[i][4 * a + 2] * f; u.w += acc[i][4 * a + 3] * f;
-        *(float4*)(out + d0) = u;
-      }
-  }
+  if (role_p) run(std::true_type{});
+  else run(std::false_type{});
 }
 
 // delta[h, t] = sum_j d_o[t,h,j] * o[t,h,j]  (one wave per (t, h))
