@@ -48,7 +48,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int DH = 128;                  // head_dim of the MFMA path
 constexpr int ROW_BYTES = DH * 2;        // 256 B per tile row
 constexpr int AT_THREADS = 512;          // 8 waves (forward, dQ): 2 per SIMD
-constexpr int TQ = ATTN_TILE_Q;          // 128 queries per workgroup (fwd, dQ)
+constexpr int TQ = ATTN_TILE_Q;          // queries per workgroup (fwd, dQ): 8 waves x 32
 constexpr int TK = ATTN_TILE_K;          // 64 keys per step (fwd, dQ)
 constexpr int KV_TILE = 128;             // keys per workgroup (dK/dV): 4 key blocks x 2 roles = 8 waves
 constexpr int KV_THREADS = 512;

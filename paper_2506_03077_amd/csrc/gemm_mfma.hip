@@ -5,7 +5,7 @@
 //
 // Design (CDNA4):
 //  * 256x256 output tile per workgroup, 8 wavefronts (2 x 4), each wave owns a
-//    128x64 sub-tile = 4x2 v_mfma_f32_32x32x16_bf16 accumulators (128 AGPRs).
+//    128x64 sub-tile = 4x2 v_mfma_f32_32x32x16_bf16 accumulators (128 registers).
 //  * Operand tiles (256 x 64 bf16 each) go HBM -> LDS with 128-bit direct-to-LDS
 //    loads (no VGPR staging), double-buffered: tile kt+1 streams in while tile kt
 //    is consumed; one barrier per K step.
@@ -25,8 +25,11 @@
 //  * Ragged M (last chunk) is handled by clamping row loads and masking stores;
 //    ragged K in the TN form (chunk rows) by clamping loads and zeroing the A
 //    fragments of the out-of-range reduction rows.
-//  * Optional split-K (grid.z): partial tiles go to an fp32 scratch and a small
-//    kernel sums them in a fixed order (deterministic) into C.
+//  * Optional split-K (a power of two, for outputs with too few tiles to fill the chip): partial tiles go to an
+//    fp32 scratch and a small kernel sums them in a fixed order (deterministic) into C; each K slice is pinned to
+//    its own group of XCDs.
+//  * Weight gradients: C += by no-return fp32 atomic adds (one add per element per launch), or into a bf16 C by
+//    paired loads / stores; several reduction segments (operand pairs) per output tile; grouped launches.
 #include "launch.h"
 
 #include <algorithm>
