@@ -50,6 +50,15 @@ int32_t check_grad_dtype(int32_t dt, int32_t grad_dt) {
   return SBP_OK;
 }
 
+// Weight gradients are added once per group of chunks (one read-modify-write pass over every dW per group instead of
+// one per chunk): as many chunks as it takes to reach DW_GROUP_ROWS rows, at most MAX_DW_GROUP (the GEMM kernels take
+// up to four reduction segments per output).  The operands of the group's chunks stay alive until the launch.
+constexpr int MAX_DW_GROUP = 4;
+constexpr int DW_GROUP_ROWS = 4096;
+int dw_group_for(size_t chunk_rows) {
+  return (int)std::max<size_t>(1, std::min<size_t>(MAX_DW_GROUP, DW_GROUP_ROWS / std::max<size_t>(chunk_rows, 1)));
+}
+
 // ------------------------------------------------------------- layer ------
 struct LayerWs {
   void *K, *V;                 // [T, Hkv*dh] dt   cached for the whole sequence
@@ -59,18 +68,19 @@ struct LayerWs {
   float *h1, *dm, *dh1, *da, *proj;                                       // per chunk, fp32 [c, d]
   float *rstd1, *rstd2, *lse, *delta, *partial;
   float* gemm_scratch; size_t gemm_scratch_bytes;
-  // Second copy of the operands of the chunk's weight-gradient GEMMs (a, o, m, gate, up, act, dh1_t, dq, dkc, dvc):
-  // the weight gradients of two consecutive chunks are added in one launch, so one chunk's operands stay alive
-  // while the next chunk is processed.
-  void* alt[10];
+  // Further copies of the operands of the chunk's weight-gradient GEMMs (a, o, m, gate, up, act, dh1_t, dq, dkc, dvc):
+  // the weight gradients of dw_group consecutive chunks are added in one launch, so a chunk's operands stay alive
+  // while the next chunks are processed.
+  int dw_group;
+  void* alt[MAX_DW_GROUP - 1][10];
   size_t bytes;
 };
-// The workspace view a chunk uses: even chunks the primary operand buffers, odd chunks the second copy.
-LayerWs chunk_view(const LayerWs& s, int parity) {
+// The workspace view a chunk uses: set 0 = the primary operand buffers, sets 1.. the further copies.
+LayerWs chunk_view(const LayerWs& s, int set) {
   LayerWs v = s;
-  if (parity) {
+  if (set > 0) {
     void** ptrs[10] = {&v.a, &v.o, &v.m, &v.gate, &v.up, &v.act, &v.dh1_t, &v.dq, &v.dkc, &v.dvc};
-    for (int i = 0; i < 10; ++i) *ptrs[i] = s.alt[i];
+    for (int i = 0; i < 10; ++i) *ptrs[i] = s.alt[set - 1][i];
   }
   return v;
 }
@@ -128,7 +138,9 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   {
     const size_t sizes[10] = {cm * d * es, cm * qd * es, cm * d * es, cm * F * es, cm * F * es, cm * F * es,
                               cm * d * es, cm * qd * es, cm * kd * es, cm * kd * es};   // a, o, m, gate, up, act, dh1_t, dq, dkc, dvc
-    for (int i = 0; i < 10; ++i) w.alt[i] = cv.take_bytes(sizes[i]);
+    w.dw_group = dw_group_for(cm);
+    for (int g = 1; g < w.dw_group; ++g)
+      for (int i = 0; i < 10; ++i) w.alt[g - 1][i] = cv.take_bytes(sizes[i]);
   }
   w.bytes = cv.off;
   return w;
@@ -267,11 +279,11 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
     // chunks >= i are done (later queries are the only other readers of those
     // keys), so the K/V-side gradient and dx of the chunk can be finished at once.
     const int n_chunks = (int)cdiv(T, cm);
-    GemmArgs dws[14];          // weight-gradient GEMMs waiting for their launch (two chunks' worth)
+    GemmArgs dws[7 * MAX_DW_GROUP];   // weight-gradient GEMMs waiting for their launch (a group of chunks' worth)
     int n_dws = 0;
     for (int ci = n_chunks - 1; ci >= 0; --ci) {
       const int r0 = ci * cm, n = std::min(cm, T - r0);
-      const LayerWs s = chunk_view(s_all, ci & 1);
+      const LayerWs s = chunk_view(s_all, ci % s_all.dw_group);
       if ((rc = chunk_reforward(c, w, s, xb, r0, n, st))) return rc;
       const char* dyc = at(dyb, r0, d, es);
       // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
@@ -296,14 +308,14 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       HIPCHK(gemm(dx_gemm(s.dkc, w->wk, s.da, n, kd, d, dt, DT_F32, true), st));
       HIPCHK(gemm(dx_gemm(s.dvc, w->wv, s.da, n, kd, d, dt, DT_F32, true), st));
       // ---- the seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand): queued, and launched together
-      //      with those of the next chunk (one pass over every dW for two chunks' rows)
+      //      with those of the other chunks of the group (one pass over every dW for the group's rows)
       {
         const GemmArgs mine[7] = {dw_gemm(dyc, s.act, g->wdown, n, d, F, dt, gdt),  dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt, gdt),
                                   dw_gemm(s.up, s.m, g->wup, n, F, d, dt, gdt),    dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt, gdt),
                                   dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt, gdt),    dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt, gdt),
                                   dw_gemm(s.dvc, s.a, g->wv, n, kd, d, dt, gdt)};
         for (int i = 0; i < 7; ++i) dws[n_dws++] = mine[i];
-        if (n_dws == 14 || ci == 0) {
+        if (n_dws == 7 * s_all.dw_group || ci == 0) {
           HIPCHK(gemm_batch(dws, n_dws, st));
           n_dws = 0;
         }
@@ -356,14 +368,14 @@ static int32_t check_head_cfg(const sbp_head_cfg* c) {
   return SBP_OK;
 }
 
-// The weight gradient of the head is accumulated once per HEAD_DW_GROUP chunks: dz and the gathered h rows of that
+// The weight gradient of the head is accumulated once per group of chunks (dw_group_for): dz and the gathered h rows of that
 // many chunks stay alive and one GEMM with a segmented reduction adds them into dW, so the 8 bytes per element of
 // read-modify-write traffic on dW (the largest tensor of the path) are paid once per group instead of once per
 // chunk.  The fp32 logits - the dominant term - still exist for one chunk only.
-constexpr int HEAD_DW_GROUP = 2;
 struct HeadWs {
-  float* z; void* dz[HEAD_DW_GROUP]; float *row_loss, *seq_weight, *ell;
-  int32_t *index, *chunk_rows; void *hc[HEAD_DW_GROUP], *dhc;   // active-row compaction: row list, rows per chunk, gathered h / dh rows
+  int dw_group;
+  float* z; void* dz[MAX_DW_GROUP]; float *row_loss, *seq_weight, *ell;
+  int32_t *index, *chunk_rows; void *hc[MAX_DW_GROUP], *dhc;   // active-row compaction: row list, rows per chunk, gathered h / dh rows
   float* gemm_scratch; size_t gemm_scratch_bytes; size_t bytes;
 };
 static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
@@ -372,13 +384,14 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   Carver cv(ws);
   HeadWs h;
   h.z = cv.take<float>(cm * c->vocab);
-  for (int g = 0; g < HEAD_DW_GROUP; ++g) h.dz[g] = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
+  h.dw_group = dw_group_for(cm);
+  for (int g = 0; g < h.dw_group; ++g) h.dz[g] = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
   h.row_loss = cv.take<float>(cm);
   h.seq_weight = cv.take<float>(c->batch);
   h.ell = cv.take<float>(1);
   h.index = cv.take<int32_t>((size_t)rows);
   h.chunk_rows = cv.take<int32_t>((size_t)cdiv(rows, (int64_t)cm));
-  for (int g = 0; g < HEAD_DW_GROUP; ++g) h.hc[g] = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
+  for (int g = 0; g < h.dw_group; ++g) h.hc[g] = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
   h.dhc = cv.take_bytes(cm * c->hidden * dtype_size(c->dtype));
   h.gemm_scratch_bytes = c->dtype == SBP_BF16 ? gemm_scratch_bytes((int)cm, c->hidden, 4) : 0;
   h.gemm_scratch = (float*)cv.take_bytes(h.gemm_scratch_bytes);
@@ -422,7 +435,7 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
   const int n_chunks = (int)cdiv(rows, (int64_t)cm);
   HIPCHK(compact_active(targets, rows, cm, s.index, s.chunk_rows, n_chunks, st));
   HIPCHK(fill_zero(dh, (size_t)rows * d * es, st));          // ignored rows of dh: exact zeros
-  GemmArgs pending[HEAD_DW_GROUP];
+  GemmArgs pending[MAX_DW_GROUP];
   int n_pending = 0;
   for (int ci = 0; ci < n_chunks; ++ci) {
     const int32_t* idx = s.index + (size_t)ci * cm;
@@ -449,7 +462,7 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
     HIPCHK(scatter_rows(dt, s.dhc, idx, n_dev, dh, n, d, st));
     pending[n_pending] = dw_gemm(dz, hc, dw, n, V, d, dt, c->grad_dtype);
     pending[n_pending].rows_dev = n_dev;
-    if (++n_pending == HEAD_DW_GROUP || ci + 1 == n_chunks) {
+    if (++n_pending == s.dw_group || ci + 1 == n_chunks) {
       HIPCHK(gemm_batch(pending, n_pending, st));
       n_pending = 0;
     }

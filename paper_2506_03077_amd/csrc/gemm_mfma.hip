@@ -426,7 +426,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_seg_k(const SegLaunch sl, 
 // Several independent GEMMs of one layout / output mode in a single launch: the tiles of all problems form one
 // grid, so small problems fill the tail of large ones instead of each paying its own partial last round.
 constexpr int MAX_GROUP = 8;
-constexpr int MAX_GSEG = 2;      // reduction segments per grouped problem (accumulate form: two chunks' operands)
+constexpr int MAX_GSEG = MAX_SEG;   // reduction segments per grouped problem (accumulate form: several chunks' operands)
 struct GroupProblem {
   const bf16_t* A[MAX_GSEG]; const bf16_t* B[MAX_GSEG]; void* C;
   int M, N, K[MAX_GSEG], nseg;

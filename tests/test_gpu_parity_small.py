@@ -72,7 +72,7 @@ def test_layer_backward_grouped_weight_gradients(grad_dtype):
 @pytest.mark.parametrize("cfg,T,chunk,batch", [(MID16, 640, 128, 1), (MID16, 333, 100, 2), (ODD16, 150, 64, 2)])
 def test_layer_backward_bf16_weight_gradients(cfg, T, chunk, batch):
     # App. B.1: bf16 weights and gradients.  The accumulators are rounded to bf16 once per pass over them
-    # (one pass per two chunks); the bound stays the bf16 one.
+    # (one pass per group of chunks); the bound stays the bf16 one.
     run_layer_case(cfg, T, chunk, batch=batch, grad_dtype="bf16")
 
 
