@@ -64,44 +64,6 @@ constexpr float LN2 = 0.6931471805599453f;
 __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 __device__ __forceinline__ int tile_off(int row, int chunk) { return row * ROW_BYTES + ((chunk ^ swz(row)) << 4); }
 
-// Direct-to-LDS load of a 64-row tile: rows row0..row0+63 of a [*, stride] bf16 matrix (row index clamped to
-// row_max so that nothing past the valid rows is ever read), 128 columns starting at g.
-template <int NT = AT_THREADS>
-__device__ __forceinline__ void dma_tile64(const bf16_t* __restrict__ g, int64_t stride, int row0, int row_max, char* lds) {
-  const int tid = threadIdx.x;
-#pragma unroll
-  for (int i = 0; i < 1024 / NT; ++i) {
-    const int id = i * NT + tid;
-    const int row = id >> 4, pc = id & 15;
-    const int chunk = pc ^ swz(row);
-    const bf16_t* src = g + (int64_t)min(row0 + row, row_max) * stride + chunk * 8;
-    char* dst = lds + (size_t)(i * NT + (tid & ~63)) * 16;
-    __builtin_amdgcn_global_load_lds(src, LDS_AS(dst), 16, 0, 0);
-  }
-}
-
-// A operand, rows = tile rows, reduction = head_dim: lane l -> row row_base + l%32, columns 16*ks + 8*(l/32) .. +7
-__device__ __forceinline__ bf16x8 frag_rows(const char* lds, int row_base, int ks) {
-  const int l = threadIdx.x & 63;
-  return *(const bf16x8*)(lds + tile_off(row_base + (l & 31), ks * 2 + (l >> 5)));
-}
-
-// A operand, rows = head_dim columns of the tile (d_base + l%32), reduction = tile rows in the permuted order
-// slot (h, j) <-> tile row row_base + 8*(j>>2) + 4*h + (j&3)   (h = l/32), matching the accumulator layout.
-__device__ __forceinline__ bf16x8 frag_cols_tr(const char* lds, int row_base, int d_base) {
-  const int l = threadIdx.x & 63;
-  const int p = l & 15, g = l >> 4;
-  const int col = d_base + 16 * (g & 1) + 4 * (p & 3);
-  const int row = row_base + 4 * (g >> 1) + (p >> 2);
-  const int c = col >> 3, sub = (col & 7) << 1;
-  short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (__attribute__((address_space(3))) short4v*)(lds + tile_off(row, c) + sub));
-  short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (__attribute__((address_space(3))) short4v*)(lds + tile_off(row + 8, c) + sub));
-  short8v r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, r);
-}
-
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int ks) {
   bf16x8 o;
 #pragma unroll
