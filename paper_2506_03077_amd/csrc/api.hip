@@ -305,8 +305,11 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       // ---- K/V side of rows [r0, r0+n): final now
       HIPCHK(kv_grad_finish(dt, s.dK + (size_t)r0 * kd, s.dV + (size_t)r0 * kd, s.rope + (size_t)r0 * half, s.dkc, s.dvc,
                             n, c->n_kv_heads, c->head_dim, st));
-      HIPCHK(gemm(dx_gemm(s.dkc, w->wk, s.da, n, kd, d, dt, DT_F32, true), st));
-      HIPCHK(gemm(dx_gemm(s.dvc, w->wv, s.da, n, kd, d, dt, DT_F32, true), st));
+      {   // da += dkc W_k + dvc W_v: same output, one launch with two reduction segments
+        const GemmArgs kv[2] = {dx_gemm(s.dkc, w->wk, s.da, n, kd, d, dt, DT_F32, true),
+                                dx_gemm(s.dvc, w->wv, s.da, n, kd, d, dt, DT_F32, true)};
+        HIPCHK(gemm_batch(kv, 2, st));
+      }
       // ---- the seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand): queued, and launched together
       //      with those of the other chunks of the group (one pass over every dW for the group's rows)
       {

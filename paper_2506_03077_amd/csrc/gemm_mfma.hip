@@ -590,14 +590,17 @@ bool gemm_mfma_group_eligible(const GemmArgs* gs, int n) {
   if (n < 2 || n > MAX_BATCH) return false;
   int64_t tiles = 0;
   int owner[MAX_BATCH], nseg[MAX_BATCH] = {0};
-  if (group_fold(gs, n, owner) > MAX_GROUP) return false;
+  const int n_out = group_fold(gs, n, owner);
+  if (n_out > MAX_GROUP) return false;
   for (int i = 0; i < n; ++i) {
     if (!gemm_mfma_eligible(gs[i]) || gs[i].rows_dev) return false;
     if (gs[i].ta != gs[0].ta || gs[i].tb != gs[0].tb || gs[i].out_dt != gs[0].out_dt || gs[i].acc != gs[0].acc) return false;
     if (++nseg[owner[i]] > MAX_GSEG) return false;
     if (owner[i] == i) tiles += cdiv(gs[i].M, BM) * (gs[i].N / BN);
   }
-  return tiles >= 200 && tiles < (1 << 30);   // otherwise per-problem launches with split-K fill the chip better
+  // few tiles: per-problem launches with split-K fill the chip better - unless problems share an output, where one
+  // launch with several reduction segments replaces several passes over it
+  return (tiles >= 200 || n_out < n) && tiles < (1 << 30);
 }
 
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
