@@ -9,7 +9,7 @@ reforward, MLP / attention backward, dW accumulation), with all inputs already
 resident in HBM.  Prints ONE JSON line (see README for the fields).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|llama_layer|lmhead|grpo] [--seq-len T]
-                    [--chunk C] [--no-cpu-baseline] [--no-profile]
+                    [--chunk C] [--batch B] [--grad-dtype f32|bf16] [--no-cpu-baseline] [--no-profile]
 """
 from __future__ import annotations
 
@@ -95,6 +95,7 @@ def main():
     ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
                     help="element type of the weight-gradient accumulators (default fp32; bf16 is the paper's own training "
                          "setting, App. B.1, and halves the read-modify-write traffic on dW)")
+    ap.add_argument("--batch", type=int, default=None, help="sequences per call (default: the workload's own)")
     ap.add_argument("--seq-len", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=None)
     ap.add_argument("--head-chunk", type=int, default=None)
@@ -125,12 +126,12 @@ def main():
     cfg = dict(synth.CONFIGS[wl])
     has_layer, has_head = wl != "lmhead", wl != "llama_layer"
     grpo = wl == "grpo"
-    B = cfg["batch"]
+    B = args.batch or cfg["batch"]
     T = args.seq_len or cfg["seq_len"]
     c = args.chunk or cfg["chunk"]
     hc_rows = args.head_chunk or c
     gdt = sb.SBP_BF16 if args.grad_dtype == "bf16" else sb.SBP_F32
-    default_shape = (wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c
+    default_shape = (wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c and B == cfg["batch"]
                      and gdt == sb.SBP_F32)                                       # what the profiles cover
     d = cfg["hidden"]
     bf = torch.bfloat16
