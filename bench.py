@@ -94,7 +94,7 @@ def main():
                          "grpo: 7B-shaped layer + LM head, 8 sequences x 16k tokens, GRPO objective")
     ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
                     help="element type of the weight-gradient accumulators (default fp32; bf16 is the paper's own training "
-                         "setting, App. B.1, and halves the read-modify-write traffic on dW)")
+                         "setting, App. D (experiment setup), and halves the read-modify-write traffic on dW)")
     ap.add_argument("--batch", type=int, default=None, help="sequences per call (default: the workload's own)")
     ap.add_argument("--seq-len", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=None)

@@ -77,7 +77,7 @@ typedef struct {
   int32_t pos_offset;   /* RoPE position of row 0                             */
   int32_t grad_dtype;   /* element type of the weight-gradient matrices:
                            SBP_F32 (0, default) or SBP_BF16 (needs dtype ==
-                           SBP_BF16; App. B.1 of the paper trains with bf16
+                           SBP_BF16; App. D (experiment setup) of the paper uses bf16
                            weights and gradients).  A bf16 gradient is read,
                            added to in fp32 and rounded once per pass over it. */
 } sbp_layer_cfg;

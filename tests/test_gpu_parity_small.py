@@ -71,7 +71,7 @@ def test_layer_backward_grouped_weight_gradients(grad_dtype):
 
 @pytest.mark.parametrize("cfg,T,chunk,batch", [(MID16, 640, 128, 1), (MID16, 333, 100, 2), (ODD16, 150, 64, 2)])
 def test_layer_backward_bf16_weight_gradients(cfg, T, chunk, batch):
-    # App. B.1: bf16 weights and gradients.  The accumulators are rounded to bf16 once per pass over them
+    # App. D (experiment setup): bf16 weights and gradients.  The accumulators are rounded to bf16 once per pass over them
     # (one pass per group of chunks); the bound stays the bf16 one.
     run_layer_case(cfg, T, chunk, batch=batch, grad_dtype="bf16")
 
@@ -191,7 +191,7 @@ def test_head_dpo():
 
 @pytest.mark.parametrize("objective", ["sft", "grpo", "dpo"])
 def test_head_bf16_weight_gradient(objective):
-    # dW kept in bf16 (App. B.1); for DPO the final rescale by sigmoid(beta * ell) - 1 runs on the bf16 tensor
+    # dW kept in bf16 (App. D, experiment setup); for DPO the final rescale by sigmoid(beta * ell) - 1 runs on the bf16 tensor
     head_case(MID16, 2, 300, 64, objective, grad_dtype="bf16", loss_scale=1.0 / 450)
     head_case(ODD16, 2, 150, 64, objective, grad_dtype="bf16", loss_scale=1.0 / 225)
 
