@@ -196,6 +196,24 @@ def test_head_bf16_weight_gradient(objective):
     head_case(ODD16, 2, 150, 64, objective, grad_dtype="bf16", loss_scale=1.0 / 225)
 
 
+@pytest.mark.parametrize("objective", [sb.SBP_OBJ_SFT, sb.SBP_OBJ_GRPO])
+def test_head_with_no_active_row_is_a_no_op(objective):
+    # degenerate case: every target ignored -> n_active = 0, loss untouched, dh exactly zero, dw untouched
+    cfg, B, T = MID16, 2, 300
+    inp = synth.head_inputs(cfg, seed=3, seq_len=T, batch=B, vocab=cfg["vocab"])
+    tg = torch.full((B, T), -1, dtype=torch.int32, device="cuda")
+    extras = synth.grpo_extras(B, T, 3)
+    hc = sb.head_cfg(sb.SBP_BF16, B, T, 128, cfg["hidden"], cfg["vocab"], objective, 1.0)
+    dw0 = torch.full((cfg["vocab"], cfg["hidden"]), 0.5, dtype=torch.float32, device="cuda")
+    loss0 = torch.full((1,), 3.0, dtype=torch.float32, device="cuda")
+    dh, dw, loss, n_active = sb.streambp_lmhead_ce_backward(
+        hc, dev(inp["w"], "bf16"), dev(inp["h"], "bf16"), tg, None, torch.from_numpy(extras["ref_logp"]).cuda(),
+        torch.from_numpy(extras["advantages"]).cuda(), dw=dw0.clone(), loss=loss0.clone())
+    torch.cuda.synchronize()
+    assert int(n_active.item()) == 0
+    assert torch.all(dh == 0) and torch.equal(dw, dw0) and torch.equal(loss, loss0)
+
+
 # -------------------------------------------------------------- attention ---
 def attn_case(dtype, Hq, Hkv, dh, s, c, seed=0, extra_rows=0):
     inp = synth.attn_inputs(Hq, Hkv, dh, s, c, dtype, seed)
