@@ -289,8 +289,11 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
       HIPCHK(gemm(dx_gemm(dyc, w->wdown, s.dact, n, d, F, dt, dt, false), st));
       HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.dact, (int64_t)n * F, st));              // gate <- dgate, up <- dup
-      HIPCHK(gemm(dx_gemm(s.gate, w->wgate, s.dm, n, F, d, dt, DT_F32, false), st));
-      HIPCHK(gemm(dx_gemm(s.up, w->wup, s.dm, n, F, d, dt, DT_F32, true), st));
+      {   // dm = dgate W_g + dup W_u: two operand pairs, one launch
+        GemmArgs gm = dx_gemm(s.gate, w->wgate, s.dm, n, F, d, dt, DT_F32, false);
+        gm.A2 = s.up; gm.B2 = w->wup;
+        HIPCHK(gemm(gm, st));
+      }
       HIPCHK(rmsnorm_bwd(dt, s.dm, s.h1, true, w->g2, s.rstd2, dyc, false, s.dh1, s.dh1_t, g->g2, s.partial, n, d, st));
       // ---- attention-side backward
       HIPCHK(gemm(dx_gemm(s.dh1_t, w->wo, s.d_o, n, d, qd, dt, dt, false), st));

@@ -9,6 +9,7 @@ namespace sbp {
 hipError_t gemm_generic(const GemmArgs& g, hipStream_t st);
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st);
 bool gemm_mfma_eligible(const GemmArgs& g);
+bool gemm_mfma_pair_ok(const GemmArgs& g);
 bool gemm_mfma_group_eligible(const GemmArgs* gs, int n);
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n);
@@ -53,6 +54,13 @@ static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs 
 }
 
 hipError_t gemm(const GemmArgs& g, hipStream_t st) {
+  if (g.A2 && !(gemm_uses_mfma(g) && gemm_mfma_pair_ok(g))) {   // two operand pairs, no single launch for them: one after the other
+    GemmArgs first = g, second = g;
+    first.A2 = first.B2 = nullptr;
+    second.A = g.A2; second.B = g.B2; second.A2 = second.B2 = nullptr; second.acc = true;
+    hipError_t e = gemm(first, st);
+    return e != hipSuccess ? e : gemm(second, st);
+  }
   if (gemm_uses_mfma(g)) return gemm_mfma(g, st);      // times itself (it knows which kernel variant it launches)
   prof::Scope sc(prof::GEMM_GENERIC, 2.0 * g.M * g.N * g.K, g.rows_dev != nullptr, st);
   return gemm_generic(g, st);
@@ -87,10 +95,12 @@ extern "C" void streambp_debug_force_generic(int gemm_on, int attn_on) {
 // Direct access to the GEMM dispatcher for unit tests and kernel timing (not part of the public header).
 extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_dt, int out_dt, int acc, const void* A,
                                    const void* B, void* C, long long lda, long long ldb, long long ldc, void* scratch,
-                                   size_t scratch_bytes, void* stream) {
+                                   size_t scratch_bytes, void* stream, const void* A2, const void* B2) {
   sbp::GemmArgs g{A, B, C, M, N, K, lda, ldb, ldc, ta != 0, tb != 0, in_dt, out_dt, acc != 0};
   g.scratch = (float*)scratch;
   g.scratch_bytes = scratch_bytes;
+  g.A2 = A2;      // optional second operand pair (both or neither)
+  g.B2 = B2;
   hipError_t e = sbp::gemm(g, (hipStream_t)stream);
   return e == hipSuccess ? (sbp::gemm_uses_mfma(g) ? 1 : 0) : -5;
 }

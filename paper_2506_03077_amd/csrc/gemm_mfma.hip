@@ -365,7 +365,8 @@ template <bool TA, bool TB, int MODE>
 __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                         void* __restrict__ Cv, int M, int N, int K, int64_t lda,
                                                         int64_t ldb, int64_t ldc, int k_per_split,
-                                                        const int* __restrict__ rows_dev, int xcds_per_split) {
+                                                        const int* __restrict__ rows_dev, int xcds_per_split,
+                                                        const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN, n_tiles = tiles_m * tiles_n;
   int tm, tn, split = 0;
@@ -391,7 +392,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
     if (TA) K = min(K, rows); else M = min(M, rows);
     if (!TA && tm * BM >= M) return;  // no valid row in this tile
   }
-  const int k_begin = split * k_per_split;
+  int k_begin = split * k_per_split;
+  if (MODE == 3 && A2 != nullptr) {   // two operand pairs instead of two halves of K: slice 1 is A2 B2 over the whole K
+    k_begin = 0;
+    if (split == 1) { A = A2; B = B2; }
+  }
   const int k_end = min(K, k_begin + k_per_split);
   if (k_end <= k_begin && mode_accumulates(MODE)) return;   // nothing to add
   KSegments segs;
@@ -496,6 +501,12 @@ bool gemm_mfma_eligible(const GemmArgs& g) {
   return true;
 }
 
+// the operand-pair form needs two partial slices and a dense C
+bool gemm_mfma_pair_ok(const GemmArgs& g) {
+  return g.A2 && g.B2 && !g.ta && g.scratch && g.ldc == g.N && g.scratch_bytes >= (size_t)2 * g.M * g.ldc * sizeof(float) &&
+         !((uintptr_t)g.A2 & 15) && !((uintptr_t)g.B2 & 15);
+}
+
 constexpr int MAX_SPLITS = 8;
 // Split-K factor (a power of two <= 8) for outputs with too few tiles to fill the chip: the largest split that
 // still fits one round of 256 CUs and leaves every slice at least 8 K steps.  Splitting further does not reduce
@@ -521,7 +532,10 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   while (splits > 1 && g.scratch_bytes < (size_t)splits * g.M * g.ldc * sizeof(float)) splits /= 2;   // what the scratch holds
   int k_per_split = g.K;
   int xcds_per_split = 0;
-  if (splits > 1) {
+  if (g.A2) {               // operand-pair form (gemm_mfma_pair_ok has checked the scratch): slice = pair, each over all of K
+    splits = 2;
+    if ((tiles_m * tiles_n) % 4 == 0) xcds_per_split = 4;
+  } else if (splits > 1) {
     k_per_split = (int)(cdiv(cdiv(g.K, BK), splits) * BK);
     if ((int)cdiv(g.K, k_per_split) != splits) splits = (int)cdiv(g.K, k_per_split);
     if (8 % splits == 0 && (tiles_m * tiles_n) % (8 / splits) == 0) xcds_per_split = 8 / splits;
@@ -531,7 +545,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const bf16_t* B = (const bf16_t*)g.B;
 #define LAUNCH(TA, TB, MODE, CPTR) \
   gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split, g.rows_dev, \
-                                                       xcds_per_split)
+                                                       xcds_per_split, (const bf16_t*)g.A2, (const bf16_t*)g.B2)
 #define LAUNCH_LAYOUT(MODE, CPTR)                       \
   do {                                                  \
     if (!g.ta && g.tb) LAUNCH(false, true, MODE, CPTR); \
@@ -541,7 +555,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
   const int mode = splits > 1 ? 3 : (g.acc ? 2 : (g.out_dt == DT_BF16 ? 1 : 0));   // (both accumulate forms are timed as one kind)
   const int kind = prof::GEMM_SINGLE + layout * 4 + mode;
-  const double work = 2.0 * g.M * g.N * g.K;
+  const double work = 2.0 * g.M * g.N * g.K * (g.A2 ? 2 : 1);
   if (splits > 1) {
     {
       prof::Scope sc(kind, work, g.rows_dev != nullptr, st);   // times the GEMM kernel, not the reduction after it
@@ -593,7 +607,7 @@ bool gemm_mfma_group_eligible(const GemmArgs* gs, int n) {
   const int n_out = group_fold(gs, n, owner);
   if (n_out > MAX_GROUP) return false;
   for (int i = 0; i < n; ++i) {
-    if (!gemm_mfma_eligible(gs[i]) || gs[i].rows_dev) return false;
+    if (!gemm_mfma_eligible(gs[i]) || gs[i].rows_dev || gs[i].A2) return false;
     if (gs[i].ta != gs[0].ta || gs[i].tb != gs[0].tb || gs[i].out_dt != gs[0].out_dt || gs[i].acc != gs[0].acc) return false;
     if (++nseg[owner[i]] > MAX_GSEG) return false;
     if (owner[i] == i) tiles += cdiv(gs[i].M, BM) * (gs[i].N / BN);
@@ -651,7 +665,7 @@ bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n) {
   if (n < 2 || n > MAX_SEG) return false;
   for (int i = 0; i < n; ++i) {
     const GemmArgs& g = gs[i];
-    if (!gemm_mfma_eligible(g) || !g.ta || g.tb || !g.acc || g.out_dt != gs[0].out_dt) return false;
+    if (!gemm_mfma_eligible(g) || !g.ta || g.tb || !g.acc || g.out_dt != gs[0].out_dt || g.A2) return false;
     if (g.C != gs[0].C || g.M != gs[0].M || g.N != gs[0].N || g.lda != gs[0].lda || g.ldb != gs[0].ldb || g.ldc != gs[0].ldc) return false;
   }
   return true;

@@ -23,6 +23,10 @@ struct GemmArgs {
   // dW form): the kernels read it at run time and skip the work beyond it; the host-side M (resp. K) is the
   // upper bound the launch is sized for.
   const int* rows_dev = nullptr;
+  // Optional second operand pair of the same shapes and leading dimensions: C (=|+=) A B + A2 B2 in one launch
+  // (the two products become the two slices of a split-K launch; falls back to two launches where that does not fit).
+  const void* A2 = nullptr;
+  const void* B2 = nullptr;
 };
 // upper bound of the scratch a GEMM with M <= max_m rows and N <= max_n columns may use
 size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits);

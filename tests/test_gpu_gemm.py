@@ -72,6 +72,23 @@ def test_mfma_split_k_eight_ways_and_unaligned_groups():
     run(200, 1280, 2048, False, True, acc=True, expect_mfma=True, seed=4)   # ragged rows, 5 tiles x 4 slices
 
 
+def test_two_operand_pairs_in_one_launch():
+    # C = A B + A2 B2 (the shape of dm = dgate W_g + dup W_u): the two products are the two slices of one split-K launch;
+    # where that does not fit (no scratch, odd shapes) the dispatcher runs them one after the other
+    rng = np.random.default_rng(12)
+    for (M, N, K, scratch_ok, expect) in ((300, 512, 1024, True, 1), (300, 512, 1024, False, 1), (70, 45, 33, True, 0)):
+        A, A2 = (synth.to_storage(rng.normal(size=(M, K)), "bf16") for _ in range(2))
+        B, B2 = (synth.to_storage(rng.normal(size=(K, N)), "bf16") for _ in range(2))
+        want = A.astype(np.float64) @ B.astype(np.float64) + A2.astype(np.float64) @ B2.astype(np.float64)
+        C = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float32)
+        scratch = torch.empty(2 * M * N, dtype=torch.float32, device="cuda") if scratch_ok else None
+        used = sb.debug_gemm(dev(A, "bf16"), dev(B, "bf16"), C, M, N, K, False, False, False, scratch,
+                             A2=dev(A2, "bf16"), B2=dev(B2, "bf16"))
+        torch.cuda.synchronize()
+        assert used == expect
+        assert_close(host(C), want, 2e-5, f"pair M={M} N={N} K={K} scratch={scratch_ok}")
+
+
 def test_mfma_segmented_weight_gradient():
     # C += sum_s A_s^T B_s in one launch; segments of different length, two of them cut short by a device row count
     rng = np.random.default_rng(5)
