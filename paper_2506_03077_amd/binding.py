@@ -103,7 +103,7 @@ def lib():
         L.streambp_debug_force_generic.restype = None
         L.streambp_debug_force_generic.argtypes = [C.c_int, C.c_int]
         L.streambp_debug_gemm.restype = C.c_int
-        L.streambp_debug_gemm.argtypes = [C.c_int] * 8 + [vp, vp, vp, C.c_longlong, C.c_longlong, C.c_longlong, vp, sz, vp, vp, vp]
+        L.streambp_debug_gemm.argtypes = [C.c_int] * 8 + [vp, vp, vp, C.c_longlong, C.c_longlong, C.c_longlong, vp, sz, vp, vp, vp, vp]
         L.streambp_stack_workspace_bytes.restype = sz
         L.streambp_stack_workspace_bytes.argtypes = [C.POINTER(StackCfg)]
         L.streambp_stack_forward.restype = i32
@@ -344,13 +344,15 @@ def debug_force_generic(gemm=False, attn=False):
     lib().streambp_debug_force_generic(int(gemm), int(attn))
 
 
-def debug_gemm(A, B, C_out, M, N, K, ta, tb, acc=False, scratch=None, stream=None, A2=None, B2=None):
+def debug_gemm(A, B, C_out, M, N, K, ta, tb, acc=False, scratch=None, stream=None, A2=None, B2=None, row_stats=None):
     """C[M,N] (=|+=) op(A) op(B) [+ op(A2) op(B2)] through the library's GEMM dispatcher; returns 1 if the MFMA kernel
-    ran, 0 if the shape-agnostic one did.  A(m,k) = A[k,m] if ta else A[m,k]; B(k,n) = B[n,k] if tb else B[k,n]."""
+    ran, 0 if the shape-agnostic one did.  A(m,k) = A[k,m] if ta else A[m,k]; B(k,n) = B[n,k] if tb else B[k,n].
+    row_stats: optional fp32 [M, N/256, 2] output, (max, sum of exp(c - max)) of every row over every block of 256 columns
+    (MFMA store form C = A B^T with fp32 C only; the launch fails where that kernel cannot take the problem)."""
     rc = lib().streambp_debug_gemm(M, N, K, int(ta), int(tb), _dt_code(A), _dt_code(C_out), int(acc), _ptr(A), _ptr(B),
                                    _ptr(C_out), A.stride(0), B.stride(0), C_out.stride(0), _ptr(scratch),
                                    0 if scratch is None else scratch.numel() * scratch.element_size(), _stream(stream),
-                                   _ptr(A2), _ptr(B2))
+                                   _ptr(A2), _ptr(B2), _ptr(row_stats))
     if rc < 0:
         raise StreamBPError(rc, "debug_gemm launch failed")
     return rc
@@ -375,7 +377,8 @@ def _profile_kind_names():
     lay = (("false, true", "NT"), ("false, false", "NN"), ("true, false", "TN"))
     names = [f"gemm_mfma_k<{t}, {m}>" for t, _ in lay for m in range(4)]
     names += [f"gemm_mfma_group_k<{t}, {m}>" for t, _ in lay for m in range(4)]
-    names += ["gemm_generic_k", "attn_fwd (launch sequence)", "attn_bwd (delta + dq + dkv launch sequence)", "gemm_mfma_seg_k"]
+    names += ["gemm_generic_k", "attn_fwd (launch sequence)", "attn_bwd (delta + dq + dkv launch sequence)", "gemm_mfma_seg_k",
+              "gemm_mfma_k<false, true, 5>"]
     return tuple(names)
 
 

@@ -10,6 +10,7 @@ hipError_t gemm_generic(const GemmArgs& g, hipStream_t st);
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st);
 bool gemm_mfma_eligible(const GemmArgs& g);
 bool gemm_mfma_pair_ok(const GemmArgs& g);
+bool gemm_mfma_stats_ok(const GemmArgs& g);
 bool gemm_mfma_group_eligible(const GemmArgs* gs, int n);
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n);
@@ -27,6 +28,7 @@ void gemm_set_force_generic(bool on) { g_force_generic_gemm = on; }
 void attn_set_force_generic(bool on) { g_force_generic_attn = on; }
 
 bool gemm_uses_mfma(const GemmArgs& g) { return !g_force_generic_gemm && gemm_mfma_eligible(g); }
+bool gemm_row_stats_supported(const GemmArgs& g) { return gemm_uses_mfma(g) && gemm_mfma_stats_ok(g); }
 bool attn_uses_mfma(int dt, int dh, int Hq, int Hkv) { return !g_force_generic_attn && attn_mfma_eligible(dt, dh, Hq, Hkv); }
 
 // ---- optional per-launch timing (off by default; events are created when profiling is switched on,
@@ -54,6 +56,7 @@ static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs 
 }
 
 hipError_t gemm(const GemmArgs& g, hipStream_t st) {
+  if (g.row_stats && !gemm_row_stats_supported(g)) return hipErrorInvalidValue;   // only the MFMA store form emits them
   if (g.A2 && !(gemm_uses_mfma(g) && gemm_mfma_pair_ok(g))) {   // two operand pairs, no single launch for them: one after the other
     GemmArgs first = g, second = g;
     first.A2 = first.B2 = nullptr;
@@ -95,12 +98,13 @@ extern "C" void streambp_debug_force_generic(int gemm_on, int attn_on) {
 // Direct access to the GEMM dispatcher for unit tests and kernel timing (not part of the public header).
 extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_dt, int out_dt, int acc, const void* A,
                                    const void* B, void* C, long long lda, long long ldb, long long ldc, void* scratch,
-                                   size_t scratch_bytes, void* stream, const void* A2, const void* B2) {
+                                   size_t scratch_bytes, void* stream, const void* A2, const void* B2, void* row_stats) {
   sbp::GemmArgs g{A, B, C, M, N, K, lda, ldb, ldc, ta != 0, tb != 0, in_dt, out_dt, acc != 0};
   g.scratch = (float*)scratch;
   g.scratch_bytes = scratch_bytes;
   g.A2 = A2;      // optional second operand pair (both or neither)
   g.B2 = B2;
+  g.row_stats = (float2*)row_stats;   // optional [M, N/256] (max, sum of exp) pairs
   hipError_t e = sbp::gemm(g, (hipStream_t)stream);
   return e == hipSuccess ? (sbp::gemm_uses_mfma(g) ? 1 : 0) : -5;
 }

@@ -145,7 +145,8 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int n_tiles) {
 
 // One 256x256 output tile: K range [k_begin, k_end).
 // MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store, C already offset),
-//       4 = accumulate into a bf16 C (read, add in fp32, round once; weight-gradient form only)
+//       4 = accumulate into a bf16 C (read, add in fp32, round once; weight-gradient form only),
+//       5 = store fp32 and emit per-row (max, sum of exp) pairs over the tile's columns (`stats`)
 constexpr bool mode_accumulates(int mode) { return mode == 2 || mode == 4; }
 //
 // The main loop is written so that it contains no vector ALU instructions at all: global addresses are an SGPR base
@@ -166,7 +167,8 @@ struct KSegments {
 
 template <bool TA, bool TB, int MODE>
 __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restrict__ Cv, int M, int N, int64_t lda,
-                                          int64_t ldb, int64_t ldc, int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES]) {
+                                          int64_t ldb, int64_t ldc, int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES],
+                                          float2* __restrict__ stats = nullptr) {
   static_assert(NSTAGE == 2, "the main loop is unrolled over two LDS stages");
   constexpr bool AMN = TA, BMN = !TB;     // operand kept reduction-major in LDS (B stored [N,K] is the K-contiguous case)
   const int m0 = tm * BM, n0 = tn * BN;
@@ -244,7 +246,8 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = MODE == 5 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[cur][j], a[cur][i], acc[i][j], 0, 0, 0)   // C^T blocks
+                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -342,6 +345,56 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
     }
     return;
   }
+  if constexpr (MODE == 5) {
+    // Row statistics for a softmax over the columns of C: every row of the tile gets (max, sum of exp(c - max)) over
+    // the tile's 256 columns.  The products were formed with the operands swapped, so the accumulators hold C^T
+    // blocks: a lane owns one row of C (l % 32 inside the 32-row block) and 32 of its columns - per column block j
+    // and register quad q the four columns 8q + 4(l / 32) .. +3 - so the reduction over columns is in-lane, plus one
+    // exchange between the two lanes of a row, and C is stored 16 bytes at a time.  The NWAVE_N waves that share a row
+    // meet in LDS (the operand stages are free once every wave has left the main loop).
+    static_assert(FN == 2, "two column blocks per wave");
+    __syncthreads();
+    float2* part = (float2*)&smem[0][0][0];    // [NWAVE_N][BM]
+    constexpr float LOG2E = 1.4426950408889634f;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row_l = wm0 + i * 32 + (lane & 31);
+      if (m0 + row_l < M) {
+        float* crow = Cf + (int64_t)(m0 + row_l) * ldc + n0 + wn0 + 4 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            *(float4*)(crow + j * 32 + 8 * q) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+      }
+      float mx = acc[i][0][0];
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      float se = 0.f;
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) se += __builtin_amdgcn_exp2f((acc[i][j][r] - mx) * LOG2E);   // difference first: exact near the maximum
+      se += __shfl_xor(se, 32, WAVE);
+      if (lane < 32) part[(wave % NWAVE_N) * BM + row_l] = make_float2(mx, se);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < BM && m0 + (int)threadIdx.x < M) {
+      float2 p = part[threadIdx.x];
+#pragma unroll
+      for (int w = 1; w < NWAVE_N; ++w) {
+        const float2 q = part[w * BM + threadIdx.x];
+        const float m2 = fmaxf(p.x, q.x);
+        p.y = p.y * __builtin_amdgcn_exp2f((p.x - m2) * LOG2E) + q.y * __builtin_amdgcn_exp2f((q.x - m2) * LOG2E);
+        p.x = m2;
+      }
+      stats[(int64_t)(m0 + (int)threadIdx.x) * (N / BN) + tn] = p;
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -366,7 +419,8 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
                                                         void* __restrict__ Cv, int M, int N, int K, int64_t lda,
                                                         int64_t ldb, int64_t ldc, int k_per_split,
                                                         const int* __restrict__ rows_dev, int xcds_per_split,
-                                                        const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2) {
+                                                        const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2,
+                                                        float2* __restrict__ row_stats) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN, n_tiles = tiles_m * tiles_n;
   int tm, tn, split = 0;
@@ -401,7 +455,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
   if (k_end <= k_begin && mode_accumulates(MODE)) return;   // nothing to add
   KSegments segs;
   segs.n = 1; segs.A[0] = A; segs.B[0] = B; segs.K[0] = K; segs.k_begin[0] = k_begin; segs.k_end[0] = k_end;
-  gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem);
+  gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem, row_stats);
 }
 
 // Weight-gradient form with a segmented reduction: C += sum_s A_s^T B_s, every segment with its own run-time row
@@ -507,6 +561,11 @@ bool gemm_mfma_pair_ok(const GemmArgs& g) {
          !((uintptr_t)g.A2 & 15) && !((uintptr_t)g.B2 & 15);
 }
 
+// the row-statistics epilogue exists for the fp32 store form of C = A B^T
+bool gemm_mfma_stats_ok(const GemmArgs& g) {
+  return !g.ta && g.tb && g.out_dt == DT_F32 && !g.acc && !g.A2 && !((uintptr_t)g.row_stats & 7);
+}
+
 constexpr int MAX_SPLITS = 8;
 // Split-K factor (a power of two <= 8) for outputs with too few tiles to fill the chip: the largest split that
 // still fits one round of 256 CUs and leaves every slice at least 8 K steps.  Splitting further does not reduce
@@ -528,7 +587,7 @@ size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits) {
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const int tiles_m = (int)cdiv(g.M, BM), tiles_n = g.N / BN;
   int splits = gemm_mfma_splits(g);
-  if (g.scratch == nullptr || g.ldc != g.N) splits = 1;
+  if (g.scratch == nullptr || g.ldc != g.N || g.row_stats) splits = 1;
   while (splits > 1 && g.scratch_bytes < (size_t)splits * g.M * g.ldc * sizeof(float)) splits /= 2;   // what the scratch holds
   int k_per_split = g.K;
   int xcds_per_split = 0;
@@ -545,7 +604,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const bf16_t* B = (const bf16_t*)g.B;
 #define LAUNCH(TA, TB, MODE, CPTR) \
   gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split, g.rows_dev, \
-                                                       xcds_per_split, (const bf16_t*)g.A2, (const bf16_t*)g.B2)
+                                                       xcds_per_split, (const bf16_t*)g.A2, (const bf16_t*)g.B2, g.row_stats)
 #define LAUNCH_LAYOUT(MODE, CPTR)                       \
   do {                                                  \
     if (!g.ta && g.tb) LAUNCH(false, true, MODE, CPTR); \
@@ -554,7 +613,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   } while (0)
   const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
   const int mode = splits > 1 ? 3 : (g.acc ? 2 : (g.out_dt == DT_BF16 ? 1 : 0));   // (both accumulate forms are timed as one kind)
-  const int kind = prof::GEMM_SINGLE + layout * 4 + mode;
+  const int kind = g.row_stats ? (int)prof::GEMM_STATS : prof::GEMM_SINGLE + layout * 4 + mode;
   const double work = 2.0 * g.M * g.N * g.K * (g.A2 ? 2 : 1);
   if (splits > 1) {
     {
@@ -572,7 +631,8 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
     return hipGetLastError();
   }
   prof::Scope sc(kind, work, g.rows_dev != nullptr, st);
-  if (g.out_dt == DT_BF16 && g.acc) LAUNCH(true, false, 4, g.C);
+  if (g.row_stats) LAUNCH(false, true, 5, g.C);
+  else if (g.out_dt == DT_BF16 && g.acc) LAUNCH(true, false, 4, g.C);
   else if (g.out_dt == DT_BF16) LAUNCH_LAYOUT(1, g.C);
   else if (g.acc) LAUNCH_LAYOUT(2, g.C);
   else LAUNCH_LAYOUT(0, g.C);

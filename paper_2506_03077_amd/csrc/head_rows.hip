@@ -1,8 +1,9 @@
 // LM-head row kernels: per-row log-sum-exp over the chunk's logits, the
 // per-token objective coefficient (SFT / GRPO / DPO, paper Sec. 3.2.1) and
 // dz = coef * (onehot(target) - softmax(z)).  One workgroup per row, two passes
-// over the row (statistics, then dz); the label gather z[target] and the ignore
-// mask are integer-indexed and exact.
+// over the row (statistics, then dz) - or one, when the logits GEMM has already
+// reduced every 256-column block of the row to a (max, sum of exp) pair; the label
+// gather z[target] and the ignore mask are integer-indexed and exact.
 #include "launch.h"
 #include <algorithm>
 
@@ -35,7 +36,15 @@ __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
   // and rescales the sum when its max moves; the pairs are then merged across the workgroup.
   float mx = -INFINITY, se = 0.f;
   const bool vec = (a.V & 3) == 0;
-  if (vec) {
+  if (a.stats) {   // the logits GEMM left (max, sum of exp) per column block: merge those instead of reading the row
+    const float2* ps = a.stats + (int64_t)row * a.n_stat;
+    for (int t = tid; t < a.n_stat; t += HR_THREADS) {
+      const float2 p = ps[t];
+      const float m2 = fmaxf(mx, p.x);
+      se = se * __expf(mx - m2) + p.y * __expf(p.x - m2);
+      mx = m2;
+    }
+  } else if (vec) {
     const float4* z4 = (const float4*)z;
     for (int v = tid; v < a.V / 4; v += HR_THREADS) {
       const float4 t = z4[v];

@@ -27,7 +27,13 @@ struct GemmArgs {
   // (the two products become the two slices of a split-K launch; falls back to two launches where that does not fit).
   const void* A2 = nullptr;
   const void* B2 = nullptr;
+  // Optional row statistics of the output (store form C = A B^T with fp32 C, MFMA kernel only: ask
+  // gemm_row_stats_supported first): row_stats[m * (N / GEMM_STAT_COLS) + t] = (max, sum of exp(c - max)) of row m
+  // over the columns [t * GEMM_STAT_COLS, (t + 1) * GEMM_STAT_COLS), taken from the fp32 accumulators.
+  float2* row_stats = nullptr;
 };
+constexpr int GEMM_STAT_COLS = 256;
+bool gemm_row_stats_supported(const GemmArgs& g);
 // upper bound of the scratch a GEMM with M <= max_m rows and N <= max_n columns may use
 size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits);
 hipError_t gemm(const GemmArgs& g, hipStream_t st);
@@ -41,8 +47,9 @@ void gemm_set_force_generic(bool on);
 // ---- optional per-launch timing (off unless streambp_debug_profile_begin was called) ----
 namespace prof {
 // kinds 0..11: gemm_mfma_k<layout, mode> with layout NT=0, NN=1, TN=2 and mode 0..3; 12..23: the grouped kernel;
-// then the shape-agnostic GEMM and the attention forward / backward launch sequences
-enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, GEMM_SEG = 27, N_KIND = 28 };
+// then the shape-agnostic GEMM, the attention forward / backward launch sequences, the segmented weight-gradient GEMM and the
+// store form with row statistics (gemm_mfma_k<NT, 5>)
+enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, GEMM_SEG = 27, GEMM_STATS = 28, N_KIND = 29 };
 struct Scope {
   hipStream_t st; bool active = false; int kind = 0; double work = 0; bool bounded = false; hipEvent_t e0{}, e1{};
   // bounded: `work` was computed from a host-side upper bound of a run-time row count
@@ -117,6 +124,8 @@ struct HeadRowArgs {
   const int32_t* row_index; // optional: original row of each chunk row (compacted chunks); then targets / old_logp /
                             // ref_logp are indexed by it and row0 is ignored
   const int* rows_dev;      // optional device-side count of valid chunk rows (<= rows)
+  const float2* stats;      // optional [rows, n_stat]: per row and column block (max, sum of exp(z - max)) from the logits
+  int n_stat;               // GEMM; the kernel then reads z once instead of twice
   int rows, V, T;
   float loss_scale, clip_eps, kl_beta; int kl_mode;
   float* row_loss;          // [rows] scratch: per-row loss term (DPO: per-row signed log-ratio)

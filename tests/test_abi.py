@@ -67,8 +67,8 @@ def test_head_workspace_is_per_chunk():
     # the only term that grows with T is the int32 list of active rows (+ one count per chunk); no T*V or T*d term
     assert 0 < b - a <= 32768 * 4 + 16 * 4 + 512
     # chunk logits fp32 + dz bf16 of the two chunks (4096 rows) whose weight gradient is added in one pass + gathered h / dh rows
-    # + split-K scratch
-    assert a < 2048 * 152064 * (4 + 2 * 2) + 3 * 2048 * 3584 * 2 + 4 * 2048 * 3584 * 4 + (1 << 20)
+    # + split-K scratch + the (max, sum of exp) pair per row and block of 256 logits
+    assert a < 2048 * 152064 * (4 + 2 * 2) + 3 * 2048 * 3584 * 2 + 4 * 2048 * 3584 * 4 + 2048 * (152064 // 256) * 8 + (1 << 20)
     assert a < 32768 * 152064 * 4 / 7        # a seventh of the full-sequence fp32 logits alone
 
 

@@ -89,6 +89,35 @@ def test_two_operand_pairs_in_one_launch():
         assert_close(host(C), want, 2e-5, f"pair M={M} N={N} K={K} scratch={scratch_ok}")
 
 
+def test_row_statistics_from_the_store_epilogue():
+    # C = A B^T with fp32 C, plus per row and block of 256 columns the pair (max, sum of exp(c - max)) that the LM head's
+    # log-sum-exp is merged from: the maxima are those of the stored C bit for bit, the sums follow to fp32 rounding,
+    # rows beyond M are never written; a problem the MFMA kernel cannot take refuses the request instead of ignoring it
+    rng = np.random.default_rng(21)
+    for (M, N, K, scale) in ((256, 256, 64, 1.0), (300, 1024, 192, 1.0), (37, 512, 128, 8.0)):
+        A = synth.to_storage(rng.normal(size=(M, K)) * scale, "bf16")
+        B = synth.to_storage(rng.normal(size=(N, K)), "bf16")
+        C = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float32)
+        nb = N // 256
+        stats = torch.full((M + 3, nb, 2), -7.0, device="cuda", dtype=torch.float32)
+        used = sb.debug_gemm(dev(A, "bf16"), dev(B, "bf16"), C, M, N, K, False, True, row_stats=stats)
+        torch.cuda.synchronize()
+        assert used == 1
+        want = A.astype(np.float64) @ B.astype(np.float64).T
+        assert_close(host(C), want, 2e-5, f"C M={M} N={N} K={K}")
+        Cb = C.cpu().numpy().reshape(M, nb, 256)
+        st = stats.cpu().numpy()
+        assert np.array_equal(st[:M, :, 0], Cb.max(axis=2)), "block maxima differ from the stored C"
+        se = np.exp(Cb.astype(np.float64) - Cb.max(axis=2, keepdims=True)).sum(axis=2)
+        assert np.allclose(st[:M, :, 1], se, rtol=2e-5, atol=0), np.abs(st[:M, :, 1] / se - 1).max()   # 256 fp32 terms
+        assert np.all(st[M:] == -7.0), "statistics written past the last row"
+    A = torch.zeros((64, 96), device="cuda", dtype=torch.bfloat16)
+    B = torch.zeros((100, 96), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(sb.StreamBPError):
+        sb.debug_gemm(A, B, torch.zeros((64, 100), device="cuda"), 64, 100, 96, False, True,
+                      row_stats=torch.zeros((64, 1, 2), device="cuda"))
+
+
 def test_mfma_segmented_weight_gradient():
     # C += sum_s A_s^T B_s in one launch; segments of different length, two of them cut short by a device row count
     rng = np.random.default_rng(5)
