@@ -208,8 +208,9 @@ int32_t kv_prepass(const sbp_layer_cfg* c, const sbp_layer_weights* w, const Lay
 }
 
 // Partitioned reforward of rows [r0, r0+n): fills a, q, o, lse, h1, m, gate, up, act.
+// with_act = false leaves s.act unwritten: the backward gets it from swiglu_bwd, which reads gate and up anyway
 int32_t chunk_reforward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const LayerWs& s, const char* xb,
-                        int r0, int n, hipStream_t st) {
+                        int r0, int n, bool with_act, hipStream_t st) {
   const int dt = c->dtype;
   const size_t es = dtype_size(dt);
   const int d = c->hidden, F = c->mlp_width, qd = c->n_q_heads * c->head_dim;
@@ -228,7 +229,7 @@ int32_t chunk_reforward(const sbp_layer_cfg* c, const sbp_layer_weights* w, cons
     const GemmArgs gu[2] = {fwd_gemm(s.m, w->wgate, s.gate, n, F, d, dt, dt), fwd_gemm(s.m, w->wup, s.up, n, F, d, dt, dt)};
     HIPCHK(gemm_batch(gu, 2, st));
   }
-  HIPCHK(swiglu_fwd(dt, s.gate, s.up, s.act, (int64_t)n * F, st));
+  if (with_act) HIPCHK(swiglu_fwd(dt, s.gate, s.up, s.act, (int64_t)n * F, st));
   return SBP_OK;
 }
 
@@ -284,11 +285,11 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
     for (int ci = n_chunks - 1; ci >= 0; --ci) {
       const int r0 = ci * cm, n = std::min(cm, T - r0);
       const LayerWs s = chunk_view(s_all, ci % s_all.dw_group);
-      if ((rc = chunk_reforward(c, w, s, xb, r0, n, st))) return rc;
+      if ((rc = chunk_reforward(c, w, s, xb, r0, n, false, st))) return rc;
       const char* dyc = at(dyb, r0, d, es);
       // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
       HIPCHK(gemm(dx_gemm(dyc, w->wdown, s.dact, n, d, F, dt, dt, false), st));
-      HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.dact, (int64_t)n * F, st));              // gate <- dgate, up <- dup
+      HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.dact, s.act, (int64_t)n * F, st));       // gate <- dgate, up <- dup, act <- silu(gate) up
       {   // dm = dgate W_g + dup W_u: two operand pairs, one launch
         GemmArgs gm = dx_gemm(s.gate, w->wgate, s.dm, n, F, d, dt, DT_F32, false);
         gm.A2 = s.up; gm.B2 = w->wup;
@@ -354,7 +355,7 @@ int32_t streambp_layer_forward(const sbp_layer_cfg* c, const sbp_layer_weights* 
     if ((rc = kv_prepass(c, w, s, xb, st))) return rc;
     for (int r0 = 0; r0 < T; r0 += cm) {
       const int n = std::min(cm, T - r0);
-      if ((rc = chunk_reforward(c, w, s, xb, r0, n, st))) return rc;
+      if ((rc = chunk_reforward(c, w, s, xb, r0, n, true, st))) return rc;
       HIPCHK(gemm(fwd_gemm(s.act, w->wdown, s.proj, n, d, F, dt, DT_F32), st));
       HIPCHK(add_store(dt, s.h1, s.proj, at(yb, r0, d, es), (int64_t)n * d, st));
     }

@@ -351,12 +351,13 @@ __global__ void swiglu_fwd_k(const T* __restrict__ gate, const T* __restrict__ u
   }
 }
 template <typename T>
-__global__ void swiglu_bwd_k(T* __restrict__ gate, T* __restrict__ up, const T* __restrict__ dact, int64_t n) {
+__global__ void swiglu_bwd_k(T* __restrict__ gate, T* __restrict__ up, const T* __restrict__ dact, T* __restrict__ act, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     float z = ldf(gate + i), u = ldf(up + i), da = ldf(dact + i);
     float sg = sigmoidf_(z);
+    if (act) stf(act + i, z * sg * u);
     stf(gate + i, da * u * sg * (1.0f + z * (1.0f - sg)));
     stf(up + i, da * z * sg);
   }
@@ -374,19 +375,22 @@ __global__ void swiglu_fwd_bf16x8_k(const bf16x8* __restrict__ gate, const bf16x
     act[i] = a;
   }
 }
+template <bool WITH_ACT>
 __global__ void swiglu_bwd_bf16x8_k(bf16x8* __restrict__ gate, bf16x8* __restrict__ up,
-                                    const bf16x8* __restrict__ dact, int64_t n8) {
+                                    const bf16x8* __restrict__ dact, bf16x8* __restrict__ act, int64_t n8) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < n8; i += stride) {
-    bf16x8 g = gate[i], u = up[i], da = dact[i], dg, du;
+    bf16x8 g = gate[i], u = up[i], da = dact[i], dg, du, a;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       float z = (float)g[j], uu = (float)u[j], d = (float)da[j];
       float sg = sigmoidf_(z);
+      if (WITH_ACT) a[j] = (bf16_t)(z * sg * uu);
       dg[j] = (bf16_t)(d * uu * sg * (1.0f + z * (1.0f - sg)));
       du[j] = (bf16_t)(d * z * sg);
     }
+    if (WITH_ACT) act[i] = a;
     gate[i] = dg; up[i] = du;
   }
 }
@@ -402,12 +406,13 @@ hipError_t swiglu_fwd(int dt, const void* gate, const void* up, void* act, int64
   }
   return hipGetLastError();
 }
-hipError_t swiglu_bwd(int dt, void* gate, void* up, const void* dact, int64_t n, hipStream_t st) {
+hipError_t swiglu_bwd(int dt, void* gate, void* up, const void* dact, void* act, int64_t n, hipStream_t st) {
   if (n == 0) return hipSuccess;
   if (dt == DT_BF16 && n % 8 == 0) {
-    swiglu_bwd_bf16x8_k<<<ew_grid(n / 8), 256, 0, st>>>((bf16x8*)gate, (bf16x8*)up, (const bf16x8*)dact, n / 8);
+    if (act) swiglu_bwd_bf16x8_k<true><<<ew_grid(n / 8), 256, 0, st>>>((bf16x8*)gate, (bf16x8*)up, (const bf16x8*)dact, (bf16x8*)act, n / 8);
+    else swiglu_bwd_bf16x8_k<false><<<ew_grid(n / 8), 256, 0, st>>>((bf16x8*)gate, (bf16x8*)up, (const bf16x8*)dact, nullptr, n / 8);
   } else {
-    DISPATCH_DT(dt, T, (swiglu_bwd_k<T><<<ew_grid(n), 256, 0, st>>>((T*)gate, (T*)up, (const T*)dact, n)));
+    DISPATCH_DT(dt, T, (swiglu_bwd_k<T><<<ew_grid(n), 256, 0, st>>>((T*)gate, (T*)up, (const T*)dact, (T*)act, n)));
   }
   return hipGetLastError();
 }

@@ -79,8 +79,9 @@ hipError_t rmsnorm_bwd_plain(int dt, const void* dy, const void* x, const void* 
                              float* dg, float* partial, int rows, int d, hipStream_t st);
 // recompute rstd only (used when the statistic was not kept): not needed by the layer path
 hipError_t swiglu_fwd(int dt, const void* gate, const void* up, void* act, int64_t n, hipStream_t st);
-// in place: gate <- dgate, up <- dup, given dact
-hipError_t swiglu_bwd(int dt, void* gate, void* up, const void* dact, int64_t n, hipStream_t st);
+// in place: gate <- dgate, up <- dup, given dact; act (optional) <- silu(gate) * up of the incoming values, the same
+// numbers swiglu_fwd writes (for callers that need act only in the backward)
+hipError_t swiglu_bwd(int dt, void* gate, void* up, const void* dact, void* act, int64_t n, hipStream_t st);
 // y = T(a + b) with a, b fp32
 hipError_t add_store(int dt, const float* a, const float* b, void* y, int64_t n, hipStream_t st);
 // dkc = T(RoPE^T(dK rows)), dvc = T(dV rows);  dK, dV fp32 [rows, H, dh]
