@@ -282,6 +282,19 @@ def test_large_magnitudes_do_not_overflow():
     assert_close(host(dh_), ref["dh"], 1e-4, "dh")
     assert_close(host(dw_), ref["dw"], 1e-4, "dw")
     assert abs(float(loss.item()) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    # bf16 head on the MFMA path, where a row's log-sum-exp is merged from the (max, sum of exp) pairs of its 256-column
+    # tiles: rows of very different scale next to each other in one tile (every other row x 250: logits ~ N(0, 80^2))
+    hin = synth.head_inputs(MID16, seed=6, seq_len=150, batch=2, vocab=MID16["vocab"])
+    row_scale = np.where(np.arange(150) % 2 == 0, 1.0, 250.0)[None, :, None]
+    h_mix = synth.to_storage(hin["h"] * row_scale, "bf16")
+    ref = o_head.sft(h_mix, hin["w"], hin["targets"], 1.0 / 200)
+    hc = sb.head_cfg(sb.SBP_BF16, 2, 150, 128, MID16["hidden"], MID16["vocab"], sb.SBP_OBJ_SFT, 1.0 / 200)
+    dh_, dw_, loss, _ = sb.streambp_lmhead_ce_backward(hc, dev(hin["w"], "bf16"), dev(h_mix, "bf16"), torch.from_numpy(hin["targets"]).cuda())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dh_.float()).all()) and bool(torch.isfinite(dw_).all()) and bool(torch.isfinite(loss).all())
+    assert_close(host(dh_), ref["dh"], 2e-2, "dh (mixed row scales)")
+    assert_close(host(dw_), ref["dw"], 2e-2, "dw (mixed row scales)")
+    assert abs(float(loss.item()) - ref["loss"]) <= 2e-3 * abs(ref["loss"])
 
 
 def test_attn_empty_chunk_is_a_no_op():
