@@ -84,6 +84,17 @@ def test_layer_backward_odd_shapes_bf16():
     run_layer_case(ODD16, 150, 64, batch=2)
 
 
+def test_degenerate_sizes():
+    # one token (attention reduces to o = v), one-row chunks, through the fp32 kernels and the bf16 MFMA kernels
+    run_layer_case(TINY, 1, 1)
+    run_layer_case(TINY, 2, 5, batch=3)
+    run_layer_case(MID16, 1, 4)
+    run_layer_case(MID16, 3, 1)
+    head_case(TINY, 1, 1, 1, "sft")
+    head_case(MID16, 1, 2, 1, "sft")
+    head_case(dict(TINY, vocab=1), 2, 5, 2, "sft")      # one-word vocabulary: p = 1, loss 0, all gradients 0
+
+
 def test_layer_forward_matches_oracle():
     for cfg, T, chunk in ((TINY, 256, 64), (MID16, 333, 128)):
         inp = synth.layer_inputs(cfg, seed=2, seq_len=T)
