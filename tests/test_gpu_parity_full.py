@@ -194,3 +194,42 @@ def test_grpo_group_of_8_structure_sampled_rows_and_batch_independence():
     assert bool(torch.isfinite(dx_all.float()).all())
     # Eq. 1 over sequences: the batch's weight gradient is the sum of the per-sequence ones
     assert dw_all["wdown"].norm().item() > dw_one["wdown"].norm().item()
+
+
+NARROW = dict(dtype="bf16", hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=128, mlp_width=512)
+
+
+def test_attention_with_a_prefix_beyond_64k_vs_oracle():
+    # a short chunk at the end of a 70001-token prefix: row and key indices beyond 2^16, element by element against the oracle
+    Hq, Hkv, dh, s, c = 4, 2, 128, 69993, 8
+    inp = synth.attn_inputs(Hq, Hkv, dh, s, c, "bf16", 11)
+    scale = 1.0 / np.sqrt(dh)
+    o_ref, lse_ref = o_attn.chunk_forward(inp["q"], inp["k"], inp["v"], s, scale)
+    dq_ref, dk_ref, dv_ref = o_attn.chunk_backward(inp["q"], inp["k"], inp["v"], inp["d_o"], s, scale)
+    q, k, v, d_o = (dev(inp[n], "bf16") for n in ("q", "k", "v", "d_o"))
+    ac = sb.attn_cfg(sb.SBP_BF16, Hq, Hkv, dh, s, c, scale)
+    o, lse = sb.streambp_attn_chunk_forward(ac, q, k, v)
+    dq, dk, dv = sb.streambp_attn_chunk_backward(ac, q, k, v, o, lse, d_o)
+    torch.cuda.synchronize()
+    assert_close(host(o), o_ref, TOL, "o")
+    assert_close(host(lse), lse_ref, 2e-3, "lse")
+    assert_close(host(dq), dq_ref, TOL, "dq")
+    assert_close(host(dk)[:s + c], dk_ref, TOL, "dk")
+    assert_close(host(dv)[:s + c], dv_ref, TOL, "dv")
+
+
+def test_layer_70k_tokens_chunk_invariance():
+    # longer than 2^16 rows and not a multiple of anything: chunk 4096 (ragged tail) against chunk 25000
+    T = 70001
+    inp = synth.layer_inputs(NARROW, seed=4, seq_len=T)
+    w = {k: dev(v, "bf16") for k, v in inp["w"].items()}
+    x, dy = dev(inp["x"], "bf16"), dev(inp["dy"], "bf16")
+    dy[:, T - 1000:] = 0
+    dx_a, dw_a = sb.streambp_layer_backward(lib_layer_cfg(NARROW, T, 4096), w, x, dy)
+    dx_b, dw_b = sb.streambp_layer_backward(lib_layer_cfg(NARROW, T, 25000), w, x, dy)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dx_a.float()).all())
+    assert torch.all(dx_a[:, T - 1000:] == 0) and torch.all(dx_b[:, T - 1000:] == 0)     # causality
+    assert relerr(host(dx_b), host(dx_a)) < 1e-2
+    for n in sb.WEIGHT_NAMES:
+        assert relerr(host(dw_b[n]), host(dw_a[n])) < 1e-2, n
