@@ -41,6 +41,12 @@ def test_binding_mirrors_every_entry_point():
         assert hasattr(sb, n), n
 
 
+def test_profile_kind_names_match_the_library():
+    # the per-launch timing table of the binding names one entry per kind the library counts
+    assert sb.lib().streambp_debug_profile_kinds() == len(sb.PROFILE_KINDS)
+    assert "gemm_mfma_k<false, true, 5>" in sb.PROFILE_KINDS and "gemm_mfma_seg_k" in sb.PROFILE_KINDS
+
+
 def good_layer_cfg(**kw):
     base = dict(dtype=sb.SBP_F32, batch=1, seq_len=256, chunk=64, hidden=64, n_q_heads=4, n_kv_heads=4,
                 head_dim=16, mlp_width=172)
