@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
                     help="element type of the weight-gradient accumulators (default fp32; bf16 is the paper's own training "
                          "setting, App. D (experiment setup), and halves the read-modify-write traffic on dW)")
+    ap.add_argument("--dw-group-rows", type=int, default=0,
+                    help="rows of chunk operands kept alive per pass over the weight gradients (0 = the library's default, 8192)")
     ap.add_argument("--batch", type=int, default=None, help="sequences per call (default: the workload's own)")
     ap.add_argument("--seq-len", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=None)
@@ -132,7 +134,7 @@ def main():
     hc_rows = args.head_chunk or c
     gdt = sb.SBP_BF16 if args.grad_dtype == "bf16" else sb.SBP_F32
     default_shape = (wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c and B == cfg["batch"]
-                     and gdt == sb.SBP_F32)                                       # what the profiles cover
+                     and gdt == sb.SBP_F32 and args.dw_group_rows in (0, 8192))   # what the profiles cover
     d = cfg["hidden"]
     bf = torch.bfloat16
 
@@ -155,7 +157,7 @@ def main():
                  wo=normal((d, Hq * dh), 0.02), wgate=normal((F, d), 0.02), wup=normal((F, d), 0.02),
                  wdown=normal((d, F), 0.02), g1=normal((d,), 0.02, 1.0), g2=normal((d,), 0.02, 1.0))
         x = normal((B, T, d), 1.0)          # layer input (the checkpoint)
-        lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F, grad_dtype=gdt)
+        lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F, grad_dtype=gdt, dw_group_rows=args.dw_group_rows)
         ws_layer = torch.empty(sb.streambp_layer_workspace_bytes(lcfg), dtype=torch.uint8, device=dev)
         ws_bytes["layer_workspace"] = ws_layer.numel()
         dw = sb.new_layer_grads(w, gdt)
@@ -170,9 +172,9 @@ def main():
         if grpo:
             adv = torch.randn((B,), generator=gen, device=dev, dtype=torch.float32)
             ref_logp = torch.randn((B, T), generator=gen, device=dev, dtype=torch.float32) * 0.5 - 2.0
-            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_GRPO, grad_dtype=gdt)
+            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_GRPO, grad_dtype=gdt, dw_group_rows=args.dw_group_rows)
         else:
-            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act, grad_dtype=gdt)
+            hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act, grad_dtype=gdt, dw_group_rows=args.dw_group_rows)
         ws_head = torch.empty(sb.streambp_lmhead_workspace_bytes(hcfg), dtype=torch.uint8, device=dev)
         ws_bytes["head_workspace"] = ws_head.numel()
         ws_bytes["full_sequence_logits_fp32_would_be"] = B * T * V * 4
@@ -225,7 +227,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{names[wl]}, T={T}, chunk={c}, head chunk={hc_rows}, batch {B}, "
                                f"loss on the last 75% of the positions of every sequence, "
-                               f"{args.grad_dtype} weight-gradient accumulators",
+                               f"{args.grad_dtype} weight-gradient accumulators"
+                               + (f", weight gradients added once per {args.dw_group_rows} rows" if args.dw_group_rows else ""),
                    "algorithmic_tflop_per_step": fl["total"] / 1e12,
                    "algorithmic_tflop_per_step_if_ignored_rows_were_counted": fl["total_all_rows"] / 1e12,
                    "achieved_tflops": fl["total"] / dt / 1e12,

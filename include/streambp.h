@@ -80,6 +80,13 @@ typedef struct {
                            SBP_BF16; App. D (experiment setup) of the paper uses bf16
                            weights and gradients).  A bf16 gradient is read,
                            added to in fp32 and rounded once per pass over it. */
+  int32_t dw_group_rows; /* rows of chunk operands kept alive so that one pass over
+                           the weight gradients adds several chunks' products
+                           (Eq. 1: the summands may be added in any grouping):
+                           the group is min(4, max(1, dw_group_rows / chunk))
+                           chunks.  0 = default (8192).  More rows: fewer passes
+                           over every dW, more workspace (one more copy of a
+                           chunk's ten GEMM operand buffers per chunk of the group) */
 } sbp_layer_cfg;
 
 /* wq [Hq*dh, d]; wk, wv [Hkv*dh, d]; wo [d, Hq*dh]; wgate, wup [F, d];
@@ -141,6 +148,9 @@ typedef struct {
                            1 = exp(ref-logp) - (ref-logp) - 1                  */
   int32_t grad_dtype;   /* element type of dw: SBP_F32 (0, default) or SBP_BF16
                            (needs dtype == SBP_BF16)                            */
+  int32_t dw_group_rows; /* as in sbp_layer_cfg: dz and the gathered h rows of
+                           min(4, max(1, dw_group_rows / chunk)) chunks stay alive
+                           and dw is added to once per group.  0 = default (8192) */
 } sbp_head_cfg;
 
 size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg *cfg);

@@ -28,7 +28,7 @@ class LayerCfg(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
                 ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("mlp_width", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("pos_offset", C.c_int32),
-                ("grad_dtype", C.c_int32)]
+                ("grad_dtype", C.c_int32), ("dw_group_rows", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -42,7 +42,7 @@ class LayerGrads(C.Structure):
 class HeadCfg(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
                 ("hidden", C.c_int32), ("vocab", C.c_int32), ("objective", C.c_int32), ("loss_scale", C.c_float),
-                ("clip_eps", C.c_float), ("kl_beta", C.c_float), ("kl_mode", C.c_int32), ("grad_dtype", C.c_int32)]
+                ("clip_eps", C.c_float), ("kl_beta", C.c_float), ("kl_mode", C.c_int32), ("grad_dtype", C.c_int32), ("dw_group_rows", C.c_int32)]
 
 
 class AttnCfg(C.Structure):
@@ -166,9 +166,9 @@ def streambp_version():
 
 
 def layer_cfg(dtype, batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
-              rms_eps=1e-6, rope_theta=1e4, pos_offset=0, grad_dtype=SBP_F32):
+              rms_eps=1e-6, rope_theta=1e4, pos_offset=0, grad_dtype=SBP_F32, dw_group_rows=0):
     return LayerCfg(int(dtype), batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
-                    rms_eps, rope_theta, pos_offset, int(grad_dtype))
+                    rms_eps, rope_theta, pos_offset, int(grad_dtype), int(dw_group_rows))
 
 
 def streambp_layer_workspace_bytes(cfg: LayerCfg) -> int:
@@ -223,9 +223,9 @@ def streambp_layer_forward(cfg: LayerCfg, w, x, y=None, workspace=None, stream=N
 
 
 def head_cfg(dtype, batch, seq_len, chunk, hidden, vocab, objective=SBP_OBJ_SFT, loss_scale=1.0,
-             clip_eps=0.2, kl_beta=0.04, kl_mode=0, grad_dtype=SBP_F32):
+             clip_eps=0.2, kl_beta=0.04, kl_mode=0, grad_dtype=SBP_F32, dw_group_rows=0):
     return HeadCfg(int(dtype), batch, seq_len, chunk, hidden, vocab, objective, loss_scale, clip_eps, kl_beta, kl_mode,
-                   int(grad_dtype))
+                   int(grad_dtype), int(dw_group_rows))
 
 
 def streambp_lmhead_workspace_bytes(cfg: HeadCfg) -> int:

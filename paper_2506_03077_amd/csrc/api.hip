@@ -54,9 +54,10 @@ int32_t check_grad_dtype(int32_t dt, int32_t grad_dt) {
 // one per chunk): as many chunks as it takes to reach DW_GROUP_ROWS rows, at most MAX_DW_GROUP (the GEMM kernels take
 // up to four reduction segments per output).  The operands of the group's chunks stay alive until the launch.
 constexpr int MAX_DW_GROUP = 4;
-constexpr int DW_GROUP_ROWS = 4096;
-int dw_group_for(size_t chunk_rows) {
-  return (int)std::max<size_t>(1, std::min<size_t>(MAX_DW_GROUP, DW_GROUP_ROWS / std::max<size_t>(chunk_rows, 1)));
+constexpr int DW_GROUP_ROWS = 8192;
+int dw_group_for(size_t chunk_rows, int32_t cfg_rows) {   // cfg_rows: the config's dw_group_rows (0 = default)
+  const size_t rows = cfg_rows > 0 ? (size_t)cfg_rows : (size_t)DW_GROUP_ROWS;
+  return (int)std::max<size_t>(1, std::min<size_t>(MAX_DW_GROUP, rows / std::max<size_t>(chunk_rows, 1)));
 }
 
 // ------------------------------------------------------------- layer ------
@@ -89,6 +90,7 @@ int32_t check_layer_cfg(const sbp_layer_cfg* c) {
   if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
   if (!valid_dtype(c->dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", c->dtype);
   if (int32_t rc = check_grad_dtype(c->dtype, c->grad_dtype)) return rc;
+  if (c->dw_group_rows < 0) return fail(SBP_ERR_SHAPE, "dw_group_rows must be >= 0");
   if (c->batch < 1 || c->seq_len < 1 || c->chunk < 1) return fail(SBP_ERR_SHAPE, "batch, seq_len and chunk must be >= 1");
   if (c->hidden < 1 || c->mlp_width < 1) return fail(SBP_ERR_SHAPE, "hidden and mlp_width must be >= 1");
   if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads != 0)
@@ -138,7 +140,7 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   {
     const size_t sizes[10] = {cm * d * es, cm * qd * es, cm * d * es, cm * F * es, cm * F * es, cm * F * es,
                               cm * d * es, cm * qd * es, cm * kd * es, cm * kd * es};   // a, o, m, gate, up, act, dh1_t, dq, dkc, dvc
-    w.dw_group = dw_group_for(cm);
+    w.dw_group = dw_group_for(cm, c->dw_group_rows);
     for (int g = 1; g < w.dw_group; ++g)
       for (int i = 0; i < 10; ++i) w.alt[g - 1][i] = cv.take_bytes(sizes[i]);
   }
@@ -368,6 +370,7 @@ static int32_t check_head_cfg(const sbp_head_cfg* c) {
   if (!c) return fail(SBP_ERR_NULL, "cfg is NULL");
   if (!valid_dtype(c->dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype %d not supported", c->dtype);
   if (int32_t rc = check_grad_dtype(c->dtype, c->grad_dtype)) return rc;
+  if (c->dw_group_rows < 0) return fail(SBP_ERR_SHAPE, "dw_group_rows must be >= 0");
   if (c->batch < 1 || c->seq_len < 1 || c->chunk < 1 || c->hidden < 1 || c->vocab < 1)
     return fail(SBP_ERR_SHAPE, "batch, seq_len, chunk, hidden and vocab must be >= 1");
   if (c->objective < SBP_OBJ_SFT || c->objective > SBP_OBJ_DPO) return fail(SBP_ERR_UNSUPPORTED, "objective %d not supported", c->objective);
@@ -392,7 +395,7 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   Carver cv(ws);
   HeadWs h;
   h.z = cv.take<float>(cm * c->vocab);
-  h.dw_group = dw_group_for(cm);
+  h.dw_group = dw_group_for(cm, c->dw_group_rows);
   for (int g = 0; g < h.dw_group; ++g) h.dz[g] = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
   h.row_loss = cv.take<float>(cm);
   h.n_stat = c->vocab / GEMM_STAT_COLS;
@@ -556,7 +559,7 @@ sbp_head_cfg stack_head_cfg(const sbp_stack_cfg* c) {
   sbp_head_cfg h{};
   h.dtype = c->layer.dtype; h.batch = c->layer.batch; h.seq_len = c->layer.seq_len; h.chunk = c->head_chunk;
   h.hidden = c->layer.hidden; h.vocab = c->vocab; h.objective = c->objective; h.loss_scale = c->loss_scale;
-  h.clip_eps = c->clip_eps; h.kl_beta = c->kl_beta; h.kl_mode = c->kl_mode; h.grad_dtype = c->layer.grad_dtype;
+  h.clip_eps = c->clip_eps; h.kl_beta = c->kl_beta; h.kl_mode = c->kl_mode; h.grad_dtype = c->layer.grad_dtype; h.dw_group_rows = c->layer.dw_group_rows;
   return h;
 }
 int32_t check_stack_cfg(const sbp_stack_cfg* c) {

@@ -43,7 +43,7 @@ def oracle_cfg(cfg):
                 pos_offset=cfg.get("pos_offset", 0))
 
 
-def lib_layer_cfg(cfg, seq_len, chunk, batch=1, grad_dtype="f32"):
+def lib_layer_cfg(cfg, seq_len, chunk, batch=1, grad_dtype="f32", dw_group_rows=0):
     return sb.layer_cfg(code(cfg["dtype"]), batch, seq_len, chunk, cfg["hidden"], cfg["n_q_heads"],
                         cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"], cfg.get("rms_eps", 1e-6),
-                        cfg.get("rope_theta", 1e4), cfg.get("pos_offset", 0), code(grad_dtype))
+                        cfg.get("rope_theta", 1e4), cfg.get("pos_offset", 0), code(grad_dtype), dw_group_rows)

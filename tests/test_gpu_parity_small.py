@@ -25,14 +25,14 @@ MID32 = dict(MID16, dtype="f32")
 ODD16 = dict(dtype="bf16", hidden=72, n_q_heads=6, n_kv_heads=2, head_dim=24, mlp_width=172, vocab=333)
 
 
-def run_layer_case(cfg, T, chunk, batch=1, seed=0, pos_offset=0, grad_dtype="f32"):
+def run_layer_case(cfg, T, chunk, batch=1, seed=0, pos_offset=0, grad_dtype="f32", dw_group_rows=0):
     cfg = dict(cfg, pos_offset=pos_offset)
     inp = synth.layer_inputs(cfg, seed=seed, seq_len=T, batch=batch)
     _, dx_ref, g_ref = o_layer.layer_forward_backward(inp["x"], inp["w"], oracle_cfg(cfg), inp["dy"])
     dt = cfg["dtype"]
     w = {k: dev(v, dt) for k, v in inp["w"].items()}
     x, dy = dev(inp["x"], dt), dev(inp["dy"], dt)
-    dx, dw = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, chunk, batch, grad_dtype), w, x, dy)
+    dx, dw = sb.streambp_layer_backward(lib_layer_cfg(cfg, T, chunk, batch, grad_dtype, dw_group_rows), w, x, dy)
     torch.cuda.synchronize()
     assert all(dw[n].dtype == (torch.float32 if n in ("g1", "g2") else tdtype(grad_dtype)) for n in sb.WEIGHT_NAMES)
     tol = TOL[dt]
@@ -67,6 +67,17 @@ BIG16 = dict(dtype="bf16", hidden=1024, n_q_heads=8, n_kv_heads=2, head_dim=128,
 @pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
 def test_layer_backward_grouped_weight_gradients(grad_dtype):
     run_layer_case(BIG16, 512, 128, grad_dtype=grad_dtype)
+
+
+@pytest.mark.parametrize("rows", [1, 128, 256, 384, 512, 100000])
+def test_weight_gradient_group_size_is_a_free_choice(rows):
+    # Eq. 1: the per-chunk summands of a weight gradient may be added in any grouping.  dw_group_rows picks how many chunks'
+    # operands stay alive for one pass over every dW: 1 chunk (rows <= chunk), 2, 3, 4 (the cap); 9 chunks of 128 rows, the
+    # last one ragged, so groups of every size end on a partial group.  Layer and head, fp32 and bf16 accumulators.
+    run_layer_case(BIG16, 1100, 128, dw_group_rows=rows)
+    run_layer_case(MID16, 1100, 128, grad_dtype="bf16", dw_group_rows=rows)
+    head_case(MID16, 2, 600, 128, "sft", loss_scale=1.0 / 900, dw_group_rows=rows)
+    head_case(MID16, 2, 600, 128, "grpo", grad_dtype="bf16", dw_group_rows=rows)
 
 
 @pytest.mark.parametrize("cfg,T,chunk,batch", [(MID16, 640, 128, 1), (MID16, 333, 100, 2), (ODD16, 150, 64, 2)])
@@ -140,21 +151,21 @@ def head_case(cfg, B, T, chunk, objective, seed=0, grad_dtype="f32", **kw):
     if objective == "sft":
         ref = o_head.sft(inp["h"], inp["w"], inp["targets"], kw.get("loss_scale", 1.0))
         hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, kw.get("loss_scale", 1.0),
-                         grad_dtype=code(grad_dtype))
+                         grad_dtype=code(grad_dtype), dw_group_rows=kw.get("dw_group_rows", 0))
         out = sb.streambp_lmhead_ce_backward(hc, w, h, tg)
     elif objective == "grpo":
         old = kw.get("old")
         ref = o_head.grpo(inp["h"], inp["w"], inp["targets"], extras["advantages"], extras["ref_logp"], old,
                           0.2, 0.04, kw.get("kl_mode", 0))
         hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_GRPO, 1.0, 0.2, 0.04,
-                         kw.get("kl_mode", 0), grad_dtype=code(grad_dtype))
+                         kw.get("kl_mode", 0), grad_dtype=code(grad_dtype), dw_group_rows=kw.get("dw_group_rows", 0))
         out = sb.streambp_lmhead_ce_backward(
             hc, w, h, tg, None if old is None else torch.from_numpy(old.astype(np.float32)).cuda(),
             torch.from_numpy(extras["ref_logp"]).cuda(), torch.from_numpy(extras["advantages"]).cuda())
     else:
         ref = o_head.dpo(inp["h"], inp["w"], inp["targets"], extras["ref_logp"], beta=0.3)
         hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_DPO, 1.0, 0.2, 0.3, 0,
-                         grad_dtype=code(grad_dtype))
+                         grad_dtype=code(grad_dtype), dw_group_rows=kw.get("dw_group_rows", 0))
         out = sb.streambp_lmhead_ce_backward(hc, w, h, tg, None, torch.from_numpy(extras["ref_logp"]).cuda(), None)
     torch.cuda.synchronize()
     dh, dw, loss, n_active = out
