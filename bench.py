@@ -8,8 +8,9 @@ by the layer-wise StreamBP of one decoder layer (K/V pre-pass, then per chunk:
 reforward, MLP / attention backward, dW accumulation), with all inputs already
 resident in HBM.  Prints ONE JSON line (see README for the fields).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|llama_layer|lmhead|grpo] [--seq-len T]
-                    [--chunk C] [--batch B] [--grad-dtype f32|bf16] [--no-cpu-baseline] [--no-profile]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|llama_layer|lmhead|grpo|stack] [--seq-len T]
+                    [--chunk C] [--batch B] [--prompt-frac P] [--layers L] [--grad-dtype f32|bf16] [--no-cpu-baseline]
+                    [--no-profile]
 """
 from __future__ import annotations
 
@@ -24,13 +25,14 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # 256 CU x 4096 flop/clk/CU x 2.4 GHz (dense bf16 MFMA); vendor figure ~2.5 PF
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per launch of the dominant kernel, measured with two rocprofv3 --pmc runs of this script
-# (FETCH_SIZE, WRITE_SIZE, scaled by a 1 GiB copy-like kernel: profiles/bench_7b_layer_lmhead_32k_hbm_traffic.txt).
-# It cannot be read inside the timed process, so the last measured figure is recorded here.
-MEASURED_TRAFFIC = {"gemm_mfma_k<false, false, 3>": 1.119e9}
+# HBM-side bytes per launch of the dominant kernel of the default workload.  Hardware counters cannot be read inside
+# the timed process: the figure is the one two rocprofv3 --pmc runs of this script measured (FETCH_SIZE, WRITE_SIZE, scaled
+# by a 1 GiB copy-like kernel) and is reported together with the file under profiles/ that holds those runs; for any
+# other kernel or shape the field is null.
+MEASURED_TRAFFIC = {}     # kernel symbol -> (bytes per launch, file under profiles/)
 
 
-def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=True):
+def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=True, n_layers=1):
     """Work the method must do (Sec. 3.2): 6*P per token for the linear maps (reforward, dX, dW), 14*dh per
     visible causal (query, key) pair per query head (4 forward + 10 backward), 6*d*V per row of the head.
     T = tokens per sequence, batch sequences (no attention across sequences), active_rows over the whole batch."""
@@ -39,8 +41,8 @@ def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=Tru
     if has_layer:
         Hq, Hkv, dh, F = (cfg[k] for k in ("n_q_heads", "n_kv_heads", "head_dim", "mlp_width"))
         p_lin = d * Hq * dh + 2 * d * Hkv * dh + Hq * dh * d + 3 * d * F
-        linear = 6.0 * p_lin * T * batch
-        attn = 14.0 * dh * Hq * (T * (T + 1) / 2.0) * batch
+        linear = 6.0 * p_lin * T * batch * n_layers
+        attn = 14.0 * dh * Hq * (T * (T + 1) / 2.0) * batch * n_layers
     if has_head:
         V = cfg["vocab"]
         head_all = 6.0 * d * V * T * batch
@@ -88,10 +90,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", choices=("7b", "llama_layer", "lmhead", "grpo"), default="7b",
-                    help="7b (default, the workload the metric is quoted on): 7B-shaped layer + LM head, 32k tokens, SFT; "
-                         "llama_layer: one Llama-style layer, 8k tokens; lmhead: LM head + cross-entropy only, 32k rows; "
-                         "grpo: 7B-shaped layer + LM head, 8 sequences x 16k tokens, GRPO objective")
+    ap.add_argument("--workload", choices=("7b", "llama_layer", "lmhead", "grpo", "stack"), default="7b",
+                    help="7b (default, the workload the metric is quoted on): 7B-shaped layer + LM head, 32k tokens, SFT on all "
+                         "positions; llama_layer: one Llama-style layer, 8k tokens; lmhead: LM head + cross-entropy only, 32k rows, "
+                         "first 25%% ignored; grpo: 7B-shaped layer + LM head, 8 sequences x 16k tokens, GRPO objective, response = "
+                         "last 75%%; stack: the whole 7B-shaped stack (28 layers + head) from per-layer checkpoints")
+    ap.add_argument("--prompt-frac", type=float, default=None,
+                    help="fraction of every sequence, from its start, whose targets are ignored (default: 0 for 7b / stack - "
+                         "SFT on all positions - and 0.25 for lmhead / grpo, as their workloads say)")
+    ap.add_argument("--layers", type=int, default=None, help="stack workload: number of layers (default 28)")
     ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
                     help="element type of the weight-gradient accumulators (default fp32; bf16 is the paper's own training "
                          "setting, App. D (experiment setup), and halves the read-modify-write traffic on dW)")
@@ -103,6 +110,8 @@ def main():
     ap.add_argument("--head-chunk", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-masked-run", action="store_true",
+                    help="skip the second timing of the default workload with the first 25%% of the positions ignored")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run one plain elementwise kernel that reads 1 GiB and writes 1 GiB (reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -125,21 +134,24 @@ def main():
     torch.cuda.set_device(dev)
 
     wl = args.workload
-    cfg = dict(synth.CONFIGS[wl])
+    stack = wl == "stack"
+    cfg = dict(synth.CONFIGS["7b" if stack else wl])
     has_layer, has_head = wl != "lmhead", wl != "llama_layer"
     grpo = wl == "grpo"
     B = args.batch or cfg["batch"]
     T = args.seq_len or cfg["seq_len"]
     c = args.chunk or cfg["chunk"]
     hc_rows = args.head_chunk or c
+    L = (args.layers or cfg["n_layers"]) if stack else 1
+    prompt_frac = args.prompt_frac if args.prompt_frac is not None else (0.25 if wl in ("lmhead", "grpo") else 0.0)
     gdt = sb.SBP_BF16 if args.grad_dtype == "bf16" else sb.SBP_F32
     default_shape = (wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c and B == cfg["batch"]
-                     and gdt == sb.SBP_F32 and args.dw_group_rows in (0, 8192))   # what the profiles cover
+                     and prompt_frac == 0.0 and gdt == sb.SBP_F32 and args.dw_group_rows in (0, 8192))   # what the profiles cover
     d = cfg["hidden"]
     bf = torch.bfloat16
 
     # ---- synthetic inputs, generated on the device (seeded): weights N(0, 0.02), hidden states N(0, 1),
-    # gains 1 + N(0, 0.02), upstream gradients N(0, 1e-3), target ids uniform in [0, V) with the first 25% of the
+    # gains 1 + N(0, 0.02), upstream gradients N(0, 1e-3), target ids uniform in [0, V); the first prompt_frac of the
     # positions of every sequence ignored (prompt); GRPO: advantages N(0, 1) per sequence, reference log-probs
     # N(-2, 0.5), on-policy (no old log-probs).
     gen = torch.Generator(device=dev)
@@ -148,24 +160,23 @@ def main():
     def normal(shape, std, mean=0.0):
         return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std + mean).to(bf)
 
-    n_prompt = T // 4
+    n_prompt = int(round(prompt_frac * T))
     n_act = B * (T - n_prompt)
     ws_bytes = {}
+
+    def layer_weights():
+        Hq, Hkv, dh, F = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"]
+        return dict(wq=normal((Hq * dh, d), 0.02), wk=normal((Hkv * dh, d), 0.02), wv=normal((Hkv * dh, d), 0.02),
+                    wo=normal((d, Hq * dh), 0.02), wgate=normal((F, d), 0.02), wup=normal((F, d), 0.02),
+                    wdown=normal((d, F), 0.02), g1=normal((d,), 0.02, 1.0), g2=normal((d,), 0.02, 1.0))
+
     if has_layer:
         Hq, Hkv, dh, F = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"]
-        w = dict(wq=normal((Hq * dh, d), 0.02), wk=normal((Hkv * dh, d), 0.02), wv=normal((Hkv * dh, d), 0.02),
-                 wo=normal((d, Hq * dh), 0.02), wgate=normal((F, d), 0.02), wup=normal((F, d), 0.02),
-                 wdown=normal((d, F), 0.02), g1=normal((d,), 0.02, 1.0), g2=normal((d,), 0.02, 1.0))
-        x = normal((B, T, d), 1.0)          # layer input (the checkpoint)
         lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F, grad_dtype=gdt, dw_group_rows=args.dw_group_rows)
-        ws_layer = torch.empty(sb.streambp_layer_workspace_bytes(lcfg), dtype=torch.uint8, device=dev)
-        ws_bytes["layer_workspace"] = ws_layer.numel()
-        dw = sb.new_layer_grads(w, gdt)
-        dx = torch.empty_like(x)
+        assert sb.streambp_layer_fast_path(lcfg) == 1, sb.streambp_last_error()
+        ws_bytes["layer_workspace"] = sb.streambp_layer_workspace_bytes(lcfg)
     if has_head:
         V = cfg["vocab"]
-        w_head = normal((V, d), 0.02)
-        h = normal((B, T, d), 1.0)          # hidden states entering the head
         targets = torch.randint(0, V, (B, T), generator=gen, device=dev, dtype=torch.int32)
         targets[:, :n_prompt] = -1
         adv = ref_logp = None
@@ -175,23 +186,58 @@ def main():
             hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_GRPO, grad_dtype=gdt, dw_group_rows=args.dw_group_rows)
         else:
             hcfg = sb.head_cfg(sb.SBP_BF16, B, T, hc_rows, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act, grad_dtype=gdt, dw_group_rows=args.dw_group_rows)
-        ws_head = torch.empty(sb.streambp_lmhead_workspace_bytes(hcfg), dtype=torch.uint8, device=dev)
-        ws_bytes["head_workspace"] = ws_head.numel()
+        assert sb.streambp_lmhead_fast_path(hcfg) == 1, sb.streambp_last_error()
+        ws_bytes["head_workspace"] = sb.streambp_lmhead_workspace_bytes(hcfg)
         ws_bytes["full_sequence_logits_fp32_would_be"] = B * T * V * 4
+        w_head = normal((V, d), 0.02)
         dw_head = torch.zeros((V, d), dtype=torch.bfloat16 if gdt == sb.SBP_BF16 else torch.float32, device=dev)
-        dh_out = torch.empty_like(h)
         loss = torch.zeros(1, dtype=torch.float32, device=dev)
         n_active = torch.zeros(1, dtype=torch.int64, device=dev)
-    else:
-        dh_out = normal((B, T, d), 1e-3)    # upstream gradient of the layer
 
-    def step():
-        if has_head:
-            sb.streambp_lmhead_ce_backward(hcfg, w_head, h, targets, ref_logp=ref_logp, advantages=adv, dh=dh_out, dw=dw_head,
-                                           loss=loss, n_active=n_active, workspace=ws_head)
+    if stack:
+        # Whole stack: the chunked forward fills one checkpoint per layer (untimed here: the metric is the backward),
+        # then the timed step is streambp_stack_backward = final norm, LM head, L x layer StreamBP, embedding scatter-add.
+        layers = [layer_weights() for _ in range(L)]
+        g_final = normal((d,), 0.02, 1.0)
+        emb = normal((V, d), 0.02)
+        ids = torch.randint(0, V, (B, T), generator=gen, device=dev, dtype=torch.int32)
+        scfg = sb.stack_cfg(lcfg, L, V, hc_rows, sb.SBP_OBJ_SFT, 1.0 / n_act)
+        ws_stack = torch.empty(sb.streambp_stack_workspace_bytes(scfg), dtype=torch.uint8, device=dev)
+        ws_bytes["stack_workspace"] = ws_stack.numel()
+        ckpt = [torch.empty((B, T, d), dtype=bf, device=dev) for _ in range(L + 1)]
+        ws_bytes["checkpoints"] = sum(t.numel() * 2 for t in ckpt)
+        t0 = time.perf_counter()
+        sb.streambp_stack_forward(scfg, layers, ckpt, emb=emb, ids=ids, workspace=ws_stack)
+        torch.cuda.synchronize()
+        forward_s = time.perf_counter() - t0
+        grads = dict(dlayers=[sb.new_layer_grads(w, gdt) for w in layers], dg_final=torch.zeros(d, dtype=torch.float32, device=dev),
+                     dw_head=dw_head, demb=torch.zeros((V, d), dtype=torch.float32, device=dev),
+                     dx0=torch.empty((B, T, d), dtype=bf, device=dev), loss=loss, n_active=n_active)
+
+        def step():
+            sb.streambp_stack_backward(scfg, layers, g_final, w_head, ckpt, targets, ids=ids, workspace=ws_stack, **grads)
+        dx = grads["dx0"]
+    else:
         if has_layer:
-            # the head's dH is the upstream gradient of the layer (the final norm is left out of the timed step)
-            sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
+            w = layer_weights()
+            x = normal((B, T, d), 1.0)          # layer input (the checkpoint)
+            ws_layer = torch.empty(ws_bytes["layer_workspace"], dtype=torch.uint8, device=dev)
+            dw = sb.new_layer_grads(w, gdt)
+            dx = torch.empty_like(x)
+        if has_head:
+            h = normal((B, T, d), 1.0)          # hidden states entering the head
+            ws_head = torch.empty(ws_bytes["head_workspace"], dtype=torch.uint8, device=dev)
+            dh_out = torch.empty_like(h)
+        else:
+            dh_out = normal((B, T, d), 1e-3)    # upstream gradient of the layer
+
+        def step():
+            if has_head:
+                sb.streambp_lmhead_ce_backward(hcfg, w_head, h, targets, ref_logp=ref_logp, advantages=adv, dh=dh_out, dw=dw_head,
+                                               loss=loss, n_active=n_active, workspace=ws_head)
+            if has_layer:
+                # the head's dH is the upstream gradient of the layer (the final norm is left out of the timed step)
+                sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
 
     if args.pmc_calibrate:   # 2^28 fp32 elements: the add kernel fetches 1 GiB and writes 1 GiB
         ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -200,47 +246,60 @@ def main():
         torch.cuda.synchronize()
         del ca, cb
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / max(args.steps, 1)
+    def timed(n_warm, n_steps):
+        for _ in range(n_warm):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / max(n_steps, 1)
+
+    generic_before = sb.streambp_generic_launches()
+    dt = timed(args.warmup, args.steps)
+    assert sb.streambp_generic_launches() == generic_before, "a launch left the MFMA kernels"
 
     if has_head:
         assert int(n_active.item()) == n_act
-        assert bool(torch.isfinite(loss).all()) and bool(torch.isfinite(dh_out.float()).all())
+        assert bool(torch.isfinite(loss).all())
+        if not stack:
+            assert bool(torch.isfinite(dh_out.float()).all())
     if has_layer:
         assert bool(torch.isfinite(dx.float()).all())
 
-    fl = algorithmic_flops(cfg, T, n_act, B, has_layer, has_head)
+    fl = algorithmic_flops(cfg, T, n_act, B, has_layer, has_head, L)
     names = {"7b": "7B-shaped decoder layer (d=3584, 28q/4kv x128, F=18944) + LM head (V=152064)",
              "llama_layer": "Llama-style decoder layer (d=4096, 32q/8kv x128, F=14336), upstream gradient N(0,1e-3)",
              "lmhead": "LM head + cross-entropy (d=3584, V=152064)",
-             "grpo": "7B-shaped decoder layer + LM head (V=152064), GRPO objective (on-policy, reference log-probs)"}
+             "grpo": "7B-shaped decoder layer + LM head (V=152064), GRPO objective (on-policy, reference log-probs)",
+             "stack": f"7B-shaped stack: {L} decoder layers (d=3584, 28q/4kv x128, F=18944) from per-layer checkpoints + final norm "
+                      f"+ LM head (V=152064) + embedding gradient"}
+    loss_on = ("loss on all positions" if n_prompt == 0 else
+               f"loss on the last {100 * (T - n_prompt) / T:.0f}% of the positions of every sequence (the rest ignored)")
     out = {
-        "metric": "backward tokens/s per layer+LM head at 32k seq",
+        "metric": "backward tokens/s per layer+LM head at 32k seq" if not stack else "backward tokens/s, whole stack at 32k seq",
         "value": B * T / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{names[wl]}, T={T}, chunk={c}, head chunk={hc_rows}, batch {B}, "
-                               f"loss on the last 75% of the positions of every sequence, "
+        "config": {"workload": f"{names[wl]}, T={T}, chunk={c}, head chunk={hc_rows}, batch {B}, {loss_on}, "
                                f"{args.grad_dtype} weight-gradient accumulators"
                                + (f", weight gradients added once per {args.dw_group_rows} rows" if args.dw_group_rows else ""),
                    "algorithmic_tflop_per_step": fl["total"] / 1e12,
-                   "algorithmic_tflop_per_step_if_ignored_rows_were_counted": fl["total_all_rows"] / 1e12,
                    "achieved_tflops": fl["total"] / dt / 1e12,
                    "frac_of_bf16_mfma_peak": fl["total"] / dt / 1e12 / PEAK_BF16_TFLOPS,
                    "peak_activation_bytes": ws_bytes,
                    "torch_max_memory_allocated": int(torch.cuda.max_memory_allocated())},
     }
+    if n_prompt:
+        out["config"]["algorithmic_tflop_per_step_if_ignored_rows_were_counted"] = fl["total_all_rows"] / 1e12
+    if stack:
+        out["config"]["forward_with_checkpoints_s"] = forward_s
 
     # ---- roofline of the dominant kernel (largest total time), durations from HIP events recorded on the
     # launch stream around every launch during one more pass over the same workload.
     if not args.no_profile:
-        sb.debug_profile_begin(20000)
+        sb.debug_profile_begin(20000 * max(1, L // 4))
         step()
         torch.cuda.synchronize()
         prof = sb.debug_profile_end()
@@ -257,13 +316,29 @@ def main():
                                      tflops=fl_k / v["ms"] / 1e9, tflop=fl_k / 1e12)
         dom = max(per_kernel, key=lambda kname: per_kernel[kname]["ms"])
         pk = per_kernel[dom]
+        traffic = MEASURED_TRAFFIC.get(dom) if default_shape else None
+        if args.traffic_bytes is not None:
+            traffic = (args.traffic_bytes, "command line (--traffic-bytes)")
         out["roofline"] = {"bound": "mfma", "kernel": dom, "launches_per_step": pk["launches"],
                            "avg_launch_ms": pk["avg_launch_ms"], "avg_launch_tflop": pk["tflop"] / pk["launches"],
                            "achieved": pk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": pk["tflops"] / PEAK_BF16_TFLOPS,
-                           "traffic": args.traffic_bytes if args.traffic_bytes is not None else
-                           (MEASURED_TRAFFIC.get(dom) if default_shape else None)}
+                           "traffic": traffic[0] if traffic else None,
+                           "traffic_source": traffic[1] if traffic else None}
         out["config"]["per_kernel"] = per_kernel
+
+    # ---- second figure for the default workload: the same step with the first quarter of the positions ignored (the
+    # prompt mask of the LM-head workload of the shape list); the library compacts those rows away.
+    if default_shape and not args.no_masked_run:
+        n_prompt2 = T // 4
+        targets[:, :n_prompt2] = -1
+        n_act2 = B * (T - n_prompt2)
+        hcfg.loss_scale = 1.0 / n_act2
+        dt2 = timed(1, max(1, min(args.steps, 3)))
+        fl2 = algorithmic_flops(cfg, T, n_act2, B, has_layer, has_head, L)
+        out["config"]["same_step_with_first_25pct_of_positions_ignored"] = dict(
+            ms_per_step=dt2 * 1e3, tokens_per_s=B * T / dt2, algorithmic_tflop_per_step=fl2["total"] / 1e12,
+            achieved_tflops=fl2["total"] / dt2 / 1e12, frac_of_bf16_mfma_peak=fl2["total"] / dt2 / 1e12 / PEAK_BF16_TFLOPS)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(dict(synth.CONFIGS["7b"]))
     print(json.dumps(out))

@@ -160,12 +160,17 @@ size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg *cfg);
  * softmax) -> dh rows = dz W, dw += dz^T h.
  *   w [V, d] in; h [B, T, d] in
  *   targets [B, T] int32 in: id the row must predict (labels already shifted
- *       by the caller); negative = ignored row (its dh row is exactly zero)
+ *       by the caller); negative = ignored row (its dh row is exactly zero).
+ *       An id >= vocab is a caller error that only the device can see: such rows
+ *       are treated as ignored (the id is never used as an index) and the call
+ *       reports them through n_active
  *   old_logp [B, T] fp32 or NULL (GRPO; NULL = on-policy, ratio 1)
  *   ref_logp [B, T] fp32 (GRPO, DPO; NULL for SFT)
  *   advantages [B] fp32 (GRPO; NULL otherwise)
  *   dh [B, T, d] out (cfg.dtype);  dw [V, d] (cfg.grad_dtype) +=
- *   loss: device fp32 scalar, +=.   n_active: device int64 scalar, out.
+ *   loss: device fp32 scalar, +=.   n_active: device int64 scalar, out: the
+ *       number of rows with 0 <= target < vocab - or, if any target is >= vocab,
+ *       minus the number of such targets (the gradients then cover the valid rows only).
  * GRPO: L = -(1/B) sum_j (1/T_o,j) sum_{t active in j} f(j,t) with T_o,j the
  * number of active rows of sequence j.
  * DPO (batch must be 2: row 0 chosen, row 1 rejected): gradients are first
@@ -188,7 +193,7 @@ typedef struct {
   int32_t n_q_heads, n_kv_heads, head_dim;
   int32_t q_start;               /* s: global position of the chunk's row 0   */
   int32_t q_len;                 /* c                                         */
-  float scale;                   /* usually 1/sqrt(head_dim)                  */
+  float scale;                   /* usually 1/sqrt(head_dim); must be positive and finite */
 } sbp_attn_cfg;
 
 size_t streambp_attn_workspace_bytes(const sbp_attn_cfg *cfg);
@@ -219,7 +224,8 @@ int32_t streambp_rmsnorm_backward(int32_t dtype, int64_t n_rows, int32_t hidden,
                                   const void *x, const void *g, const void *dy, void *dx,
                                   float *dg, void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
-/* x[t] = emb[ids[t]] ; demb[ids[t]] += dx[t] (fp32 accumulators, atomic adds). */
+/* x[t] = emb[ids[t]] ; demb[ids[t]] += dx[t] (fp32 accumulators, atomic adds).  An id outside [0, vocab) is never
+ * used as an index: its row of x is zero and its row of dx is dropped. */
 int32_t streambp_embedding_forward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab,
                                    const int32_t *ids, const void *emb, void *x, void *hip_stream);
 int32_t streambp_embedding_backward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab,
@@ -271,6 +277,17 @@ int32_t streambp_stack_backward(const sbp_stack_cfg *cfg, const sbp_layer_weight
 
 const char *streambp_version(void);
 const char *streambp_last_error(void);
+/* Which kernels a configuration gets (host arithmetic only).  1: every GEMM and the attention of the configuration
+ * run on the bf16 MFMA kernels (needs bf16 storage, head_dim 128 and hidden, n_q_heads*head_dim, n_kv_heads*head_dim,
+ * mlp_width - for the head: hidden and vocab - multiples of 256, 16-byte aligned tensors).  0: some of it runs on the
+ * shape-agnostic fp32-ALU kernels, a correctness path that is orders of magnitude slower (streambp_last_error() says
+ * which dimension is the reason); nothing is refused.  Negative: the configuration itself is invalid. */
+int32_t streambp_layer_fast_path(const sbp_layer_cfg *cfg);
+int32_t streambp_lmhead_fast_path(const sbp_head_cfg *cfg);
+/* Number of bf16 GEMM / attention launches, since the library was loaded, that ran on the shape-agnostic kernels because
+ * the MFMA kernels could not take their shape or alignment.  A caller that expects the fast path checks that this does
+ * not move across its calls. */
+int64_t streambp_generic_launches(void);
 /* Number of (query tile, key tile) pairs the attention kernels visit for a
  * chunk, and the tile sizes; host arithmetic only, for the causal-skip check
  * (Sec. 3.2.2, computational efficiency: about (1+D)/(2D) of the full square). */

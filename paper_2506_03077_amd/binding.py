@@ -100,6 +100,12 @@ def lib():
         L.streambp_embedding_backward.argtypes = [i32, i64, i32, i32, vp, vp, vp, vp]
         L.streambp_attn_tile_pairs.restype = i64
         L.streambp_attn_tile_pairs.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.streambp_layer_fast_path.restype = i32
+        L.streambp_layer_fast_path.argtypes = [C.POINTER(LayerCfg)]
+        L.streambp_lmhead_fast_path.restype = i32
+        L.streambp_lmhead_fast_path.argtypes = [C.POINTER(HeadCfg)]
+        L.streambp_generic_launches.restype = i64
+        L.streambp_generic_launches.argtypes = []
         L.streambp_debug_force_generic.restype = None
         L.streambp_debug_force_generic.argtypes = [C.c_int, C.c_int]
         L.streambp_debug_gemm.restype = C.c_int
@@ -331,6 +337,20 @@ def streambp_embedding_backward(ids, dx, vocab, demb=None, stream=None):
         demb = torch.zeros((vocab, d), dtype=torch.float32, device=dx.device)
     _check(lib().streambp_embedding_backward(_dt_code(dx), ids.numel(), d, vocab, _ptr(ids), _ptr(dx), _ptr(demb), _stream(stream)))
     return demb
+
+
+def streambp_layer_fast_path(cfg: LayerCfg) -> int:
+    """1: the whole configuration runs on the bf16 MFMA kernels; 0: part of it on the shape-agnostic kernels."""
+    return int(lib().streambp_layer_fast_path(C.byref(cfg)))
+
+
+def streambp_lmhead_fast_path(cfg: HeadCfg) -> int:
+    return int(lib().streambp_lmhead_fast_path(C.byref(cfg)))
+
+
+def streambp_generic_launches() -> int:
+    """bf16 launches that ran on the shape-agnostic kernels since the library was loaded."""
+    return int(lib().streambp_generic_launches())
 
 
 def streambp_attn_tile_pairs(q_start, q_len):

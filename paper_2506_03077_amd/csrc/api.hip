@@ -439,14 +439,14 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
   const int cm = (int)std::min<int64_t>(c->chunk, rows);
   const int d = c->hidden, V = c->vocab;
 
-  HIPCHK(count_active(targets, c->batch, c->seq_len, s.seq_weight, n_active, st));
+  HIPCHK(count_active(targets, c->batch, c->seq_len, V, s.seq_weight, n_active, st));
   if (c->objective == SBP_OBJ_DPO) HIPCHK(fill_zero(s.ell, sizeof(float), st));
   // Rows with an ignored target contribute nothing (dz = 0): only the active rows are pushed through the
   // GEMMs.  Positions are independent (Sec. 3.2.1), so the active rows of all sequences are chunked as one
   // flat list; the list and the per-chunk row counts live on the device (no host synchronisation), and the
   // kernels of a chunk read their row count at run time.
   const int n_chunks = (int)cdiv(rows, (int64_t)cm);
-  HIPCHK(compact_active(targets, rows, cm, s.index, s.chunk_rows, n_chunks, st));
+  HIPCHK(compact_active(targets, rows, cm, V, s.index, s.chunk_rows, n_chunks, st));
   HIPCHK(fill_zero(dh, (size_t)rows * d * es, st));          // ignored rows of dh: exact zeros
   GemmArgs pending[MAX_DW_GROUP];
   int n_pending = 0;
@@ -498,6 +498,8 @@ static int32_t check_attn_cfg(const sbp_attn_cfg* c) {
   if (c->head_dim < 1 || c->head_dim > 256) return fail(SBP_ERR_SHAPE, "head_dim must be in [1, 256]");
   if (c->q_start < 0 || c->q_len < 0) return fail(SBP_ERR_SHAPE, "q_start and q_len must be >= 0");
   if ((int64_t)c->q_start + c->q_len > INT32_MAX) return fail(SBP_ERR_SHAPE, "q_start + q_len overflows");
+  // the kernels take row maxima of the raw scores before scaling them, which is only right for a positive finite scale
+  if (!(c->scale > 0.f) || !std::isfinite(c->scale)) return fail(SBP_ERR_SHAPE, "scale must be positive and finite");
   return SBP_OK;
 }
 
@@ -538,6 +540,29 @@ int32_t streambp_attn_chunk_backward(const sbp_attn_cfg* c, const void* q, const
   HIPCHK(attn_backward(a, (hipStream_t)hip_stream));
   return SBP_OK;
 }
+
+// Which kernels a configuration gets.  The bf16 MFMA GEMMs need every matrix dimension of the layer (hidden, the q and
+// k/v widths, mlp_width - resp. hidden and vocab for the head) to be a multiple of 256, the MFMA attention head_dim 128;
+// anything else runs on the shape-agnostic fp32-ALU kernels, which are a correctness path and orders of magnitude slower.
+int32_t streambp_layer_fast_path(const sbp_layer_cfg* c) {
+  if (int32_t rc = check_layer_cfg(c)) return rc;
+  if (c->dtype != SBP_BF16) return fail(0, "fp32 storage: the shape-agnostic kernels are the only path"), 0;
+  const int qd = c->n_q_heads * c->head_dim, kd = c->n_kv_heads * c->head_dim;
+  if (c->head_dim != 128) return fail(0, "head_dim %d: the MFMA attention kernels take 128 only", c->head_dim), 0;
+  const int dims[4] = {c->hidden, qd, kd, c->mlp_width};
+  const char* names[4] = {"hidden", "n_q_heads*head_dim", "n_kv_heads*head_dim", "mlp_width"};
+  for (int i = 0; i < 4; ++i)
+    if (dims[i] % 256) return fail(0, "%s = %d is not a multiple of 256: its GEMMs leave the MFMA kernels", names[i], dims[i]), 0;
+  return 1;
+}
+int32_t streambp_lmhead_fast_path(const sbp_head_cfg* c) {
+  if (int32_t rc = check_head_cfg(c)) return rc;
+  if (c->dtype != SBP_BF16) return fail(0, "fp32 storage: the shape-agnostic kernels are the only path"), 0;
+  if (c->hidden % 256) return fail(0, "hidden = %d is not a multiple of 256: the head's GEMMs leave the MFMA kernels", c->hidden), 0;
+  if (c->vocab % 256) return fail(0, "vocab = %d is not a multiple of 256: the head's GEMMs leave the MFMA kernels", c->vocab), 0;
+  return 1;
+}
+int64_t streambp_generic_launches(void) { return (int64_t)generic_bf16_launches(); }
 
 int64_t streambp_attn_tile_pairs(int32_t q_start, int32_t q_len, int32_t* tile_q, int32_t* tile_k) {
   // Work is skipped per wave: a wave owns ATTN_WAVE_Q query rows and walks key tiles of ATTN_TILE_K.
@@ -683,7 +708,7 @@ int32_t streambp_embedding_forward(int32_t dtype, int64_t n_rows, int32_t hidden
   if (!valid_dtype(dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype");
   if (n_rows < 0 || hidden < 1 || vocab < 1 || n_rows > INT32_MAX) return fail(SBP_ERR_SHAPE, "bad shape");
   if (!ids || !emb || !x) return fail(SBP_ERR_NULL, "NULL pointer");
-  HIPCHK(embedding_fwd(dtype, ids, emb, x, n_rows, hidden, (hipStream_t)hip_stream));
+  HIPCHK(embedding_fwd(dtype, ids, emb, x, n_rows, hidden, vocab, (hipStream_t)hip_stream));
   return SBP_OK;
 }
 int32_t streambp_embedding_backward(int32_t dtype, int64_t n_rows, int32_t hidden, int32_t vocab, const int32_t* ids,
@@ -691,7 +716,7 @@ int32_t streambp_embedding_backward(int32_t dtype, int64_t n_rows, int32_t hidde
   if (!valid_dtype(dtype)) return fail(SBP_ERR_UNSUPPORTED, "dtype");
   if (n_rows < 0 || hidden < 1 || vocab < 1 || n_rows > INT32_MAX) return fail(SBP_ERR_SHAPE, "bad shape");
   if (!ids || !dx || !demb) return fail(SBP_ERR_NULL, "NULL pointer");
-  HIPCHK(embedding_bwd(dtype, ids, dx, demb, n_rows, hidden, (hipStream_t)hip_stream));
+  HIPCHK(embedding_bwd(dtype, ids, dx, demb, n_rows, hidden, vocab, (hipStream_t)hip_stream));
   return SBP_OK;
 }
 

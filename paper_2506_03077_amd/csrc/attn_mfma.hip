@@ -471,8 +471,8 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
     dma_tile64(tl, d_o + corner, q_stride, c - qt * QT, lds0 + (uint32_t)((stage * 2 + 1) * TILE64_BYTES));
     if (wave < 2) {   // 64 log-sum-exp values (wave 0) and 64 deltas (wave 1), 4 B per lane, also direct to LDS
       const int row = min(qt * QT + lane, c - 1);
-      const float* src = (wave == 0 ? lse2 : delta) + (int64_t)hh * c + row;
-      __builtin_amdgcn_global_load_lds(src, LDS_AS(wave == 0 ? &sL[stage][0] : &sDl[stage][0]), 4, 0, 0);
+      dma4(uniform_ptr((wave == 0 ? lse2 : delta) + (int64_t)hh * c), (uint32_t)row * 4u,
+           __builtin_amdgcn_readfirstlane(lds_addr(wave == 0 ? &sL[stage][0] : &sDl[stage][0])));
     }
   };
   // One 64-query tile = two 32-query blocks.  `active`: the wave has a valid key and some query of the tile is
@@ -635,7 +635,7 @@ hipError_t attn_backward_generic(const AttnArgs& a, hipStream_t st);
 
 hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st) {
   if (a.q_len == 0) return hipSuccess;
-  if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o)) return attn_forward_generic(a, st);
+  if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o)) { note_generic_bf16_launch(); return attn_forward_generic(a, st); }
   dim3 grid((unsigned)cdiv(a.q_len, TQ), a.Hq);
   attn_fwd_mfma_k<<<grid, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (bf16_t*)a.o, a.lse,
                                                a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
@@ -645,8 +645,10 @@ hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st) {
 hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st) {
   if (a.q_len == 0) return hipSuccess;
   if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o) || !aligned16(a.d_o) || !aligned16(a.dq) ||
-      !aligned16(a.dk) || !aligned16(a.dv))
+      !aligned16(a.dk) || !aligned16(a.dv)) {
+    note_generic_bf16_launch();
     return attn_backward_generic(a, st);
+  }
   const int64_t pairs = (int64_t)a.q_len * a.Hq;
   float* lse2 = a.delta + pairs;   // second half of the [2, Hq, c] scratch
   attn_delta_mfma_k<<<(unsigned)cdiv(pairs, 4), 256, 0, st>>>((const bf16_t*)a.o, (const bf16_t*)a.d_o, a.lse, a.delta, lse2, a.Hq,

@@ -57,8 +57,15 @@ __device__ __forceinline__ float block_max(float v, float* red) {
 // vmcnt waits of a pipeline into vmcnt(0), and this addressing form needs no vector ALU work per load - in an
 // MFMA loop every VALU instruction queues behind the MFMAs of the SIMD's other wave, so per-load 64-bit address
 // arithmetic (what the flat form needs) stretches the issue of a tile's loads several-fold.
+// Every direct-to-LDS load of the library goes through these two functions, each of which sets m0 itself: no kernel
+// mixes them with the compiler's builtin form, whose m0 bookkeeping the compiler could otherwise merge or hoist
+// across an asm statement it cannot see into (m0 is a reserved register and cannot be named as a clobber).
 __device__ __forceinline__ void dma16(const char* base /*uniform*/, uint32_t voff, uint32_t lds_wave_base /*uniform*/) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_wave_base) : "memory");
+}
+// 32-bit form: lane l's dword lands at LDS address lds_wave_base + 4 l.
+__device__ __forceinline__ void dma4(const char* base /*uniform*/, uint32_t voff, uint32_t lds_wave_base /*uniform*/) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(base), "s"(lds_wave_base) : "memory");
 }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;

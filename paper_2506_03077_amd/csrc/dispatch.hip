@@ -1,7 +1,9 @@
 // Kernel selection: bf16 MFMA kernels when the problem fits their tiling, the
 // shape-agnostic kernels otherwise.
+#include "../../include/streambp_debug.h"
 #include "launch.h"
 
+#include <atomic>
 #include <vector>
 
 namespace sbp {
@@ -21,8 +23,12 @@ hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st);
 hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st);
 bool attn_mfma_eligible(int dt, int dh, int Hq, int Hkv);
 
-static bool g_force_generic_gemm = false;
-static bool g_force_generic_attn = false;
+static std::atomic<bool> g_force_generic_gemm{false};
+static std::atomic<bool> g_force_generic_attn{false};
+// bf16 problems that ran on the shape-agnostic fp32-ALU kernels (shape or alignment outside what the MFMA kernels take)
+static std::atomic<long long> g_generic_bf16_launches{0};
+long long generic_bf16_launches() { return g_generic_bf16_launches.load(); }
+void note_generic_bf16_launch() { ++g_generic_bf16_launches; }
 
 void gemm_set_force_generic(bool on) { g_force_generic_gemm = on; }
 void attn_set_force_generic(bool on) { g_force_generic_attn = on; }
@@ -35,7 +41,7 @@ bool attn_uses_mfma(int dt, int dh, int Hq, int Hkv) { return !g_force_generic_a
 // never inside an entry point) -------------------------------------------------------------------
 namespace prof {
 struct Rec { int kind; double work; bool bounded; hipEvent_t e0, e1; };
-static bool g_on = false;
+static std::atomic<bool> g_on{false};
 static std::vector<hipEvent_t> g_pool;
 static std::vector<Rec> g_recs;
 static size_t g_next = 0;
@@ -65,6 +71,7 @@ hipError_t gemm(const GemmArgs& g, hipStream_t st) {
     return e != hipSuccess ? e : gemm(second, st);
   }
   if (gemm_uses_mfma(g)) return gemm_mfma(g, st);      // times itself (it knows which kernel variant it launches)
+  if (g.in_dt == DT_BF16) ++g_generic_bf16_launches;
   prof::Scope sc(prof::GEMM_GENERIC, 2.0 * g.M * g.N * g.K, g.rows_dev != nullptr, st);
   return gemm_generic(g, st);
 }
@@ -81,11 +88,15 @@ hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st) {
 }
 hipError_t attn_forward(const AttnArgs& a, hipStream_t st) {
   prof::Scope sc(prof::ATTN_FWD, 4.0 * a.dh * causal_pairs(a), false, st);
-  return attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) ? attn_forward_mfma(a, st) : attn_forward_generic(a, st);
+  if (attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv)) return attn_forward_mfma(a, st);
+  if (a.dt == DT_BF16) ++g_generic_bf16_launches;
+  return attn_forward_generic(a, st);
 }
 hipError_t attn_backward(const AttnArgs& a, hipStream_t st) {
   prof::Scope sc(prof::ATTN_BWD, 10.0 * a.dh * causal_pairs(a), false, st);
-  return attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) ? attn_backward_mfma(a, st) : attn_backward_generic(a, st);
+  if (attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv)) return attn_backward_mfma(a, st);
+  if (a.dt == DT_BF16) ++g_generic_bf16_launches;
+  return attn_backward_generic(a, st);
 }
 
 }  // namespace sbp
@@ -95,7 +106,7 @@ extern "C" void streambp_debug_force_generic(int gemm_on, int attn_on) {
   sbp::attn_set_force_generic(attn_on != 0);
 }
 
-// Direct access to the GEMM dispatcher for unit tests and kernel timing (not part of the public header).
+// Direct access to the GEMM dispatcher for unit tests and kernel timing (declared in include/streambp_debug.h).
 extern "C" int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_dt, int out_dt, int acc, const void* A,
                                    const void* B, void* C, long long lda, long long ldb, long long ldc, void* scratch,
                                    size_t scratch_bytes, void* stream, const void* A2, const void* B2, void* row_stats) {
@@ -121,7 +132,7 @@ extern "C" int streambp_debug_gemm_dw_segments(int n, int M, int N, const int* K
     gs[i] = sbp::GemmArgs{A[i], B[i], C, M, N, K[i], lda, ldb, ldc, true, false, in_dt, out_dt, true};
     gs[i].rows_dev = rows_dev ? rows_dev[i] : nullptr;
   }
-  const bool seg = !sbp::g_force_generic_gemm && sbp::gemm_mfma_seg_eligible(gs, n);
+  const bool seg = !sbp::g_force_generic_gemm.load() && sbp::gemm_mfma_seg_eligible(gs, n);
   hipError_t e = sbp::gemm_batch(gs, n, (hipStream_t)stream);
   return e == hipSuccess ? (seg ? 1 : 0) : -5;
 }

@@ -474,26 +474,29 @@ hipError_t fill_zero(void* p, size_t bytes, hipStream_t st) {
   return hipGetLastError();
 }
 
+// An id outside [0, vocab) is never used as an index: its row of x is zero and its row of dx is dropped.
 template <typename T>
-__global__ void embedding_fwd_k(const int32_t* __restrict__ ids, const T* __restrict__ emb, T* __restrict__ x, int d) {
+__global__ void embedding_fwd_k(const int32_t* __restrict__ ids, const T* __restrict__ emb, T* __restrict__ x, int d, int vocab) {
   const int64_t row = blockIdx.x;
   const int64_t id = ids[row];
-  for (int j = threadIdx.x; j < d; j += blockDim.x) x[row * d + j] = emb[id * d + j];
+  const bool ok = id >= 0 && id < vocab;
+  for (int j = threadIdx.x; j < d; j += blockDim.x) x[row * d + j] = ok ? emb[id * d + j] : (T)0.0f;
 }
 template <typename T>
-__global__ void embedding_bwd_k(const int32_t* __restrict__ ids, const T* __restrict__ dx, float* __restrict__ demb, int d) {
+__global__ void embedding_bwd_k(const int32_t* __restrict__ ids, const T* __restrict__ dx, float* __restrict__ demb, int d, int vocab) {
   const int64_t row = blockIdx.x;
   const int64_t id = ids[row];
+  if (id < 0 || id >= vocab) return;
   for (int j = threadIdx.x; j < d; j += blockDim.x) atomicAdd(demb + id * d + j, ldf(dx + row * d + j));
 }
-hipError_t embedding_fwd(int dt, const int32_t* ids, const void* emb, void* x, int64_t rows, int d, hipStream_t st) {
+hipError_t embedding_fwd(int dt, const int32_t* ids, const void* emb, void* x, int64_t rows, int d, int vocab, hipStream_t st) {
   if (rows == 0) return hipSuccess;
-  DISPATCH_DT(dt, T, (embedding_fwd_k<T><<<(unsigned)rows, 256, 0, st>>>(ids, (const T*)emb, (T*)x, d)));
+  DISPATCH_DT(dt, T, (embedding_fwd_k<T><<<(unsigned)rows, 256, 0, st>>>(ids, (const T*)emb, (T*)x, d, vocab)));
   return hipGetLastError();
 }
-hipError_t embedding_bwd(int dt, const int32_t* ids, const void* dx, float* demb, int64_t rows, int d, hipStream_t st) {
+hipError_t embedding_bwd(int dt, const int32_t* ids, const void* dx, float* demb, int64_t rows, int d, int vocab, hipStream_t st) {
   if (rows == 0) return hipSuccess;
-  DISPATCH_DT(dt, T, (embedding_bwd_k<T><<<(unsigned)rows, 256, 0, st>>>(ids, (const T*)dx, demb, d)));
+  DISPATCH_DT(dt, T, (embedding_bwd_k<T><<<(unsigned)rows, 256, 0, st>>>(ids, (const T*)dx, demb, d, vocab)));
   return hipGetLastError();
 }
 

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
   const int64_t orig = a.row_index ? (int64_t)a.row_index[row] : a.row0 + row;   // row in the caller's [B*T] order
   const int64_t aux = a.row_index ? orig : (int64_t)row;        // index into targets / old_logp / ref_logp as passed
   const int tgt = a.targets[aux];
-  if (tgt < 0) {   // ignored row: exact zeros, no loss term
+  if (tgt < 0 || tgt >= a.V) {   // ignored row (or an id outside the vocabulary, which is never used as an index): exact zeros, no loss term
     const int64_t row_bytes = (int64_t)a.V * sizeof(T);
     if ((row_bytes & 15) == 0) {
       uint4* p16 = (uint4*)dz;
@@ -139,7 +139,7 @@ hipError_t reduce_add(const float* v, int n, float* out, hipStream_t st, const i
 
 // Stable compaction of the active rows (target >= 0) by one workgroup: per-thread counts over a contiguous
 // slice, an exclusive scan of the 1024 counts in LDS, then each thread writes its slice's indices in order.
-__global__ __launch_bounds__(1024) void compact_active_k(const int32_t* __restrict__ targets, int64_t rows, int chunk,
+__global__ __launch_bounds__(1024) void compact_active_k(const int32_t* __restrict__ targets, int64_t rows, int chunk, int V,
                                                          int32_t* __restrict__ index, int32_t* __restrict__ chunk_rows,
                                                          int n_chunks) {
   __shared__ int cnt[1024];
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(1024) void compact_active_k(const int32_t* __restri
   const int64_t per = (rows + 1023) / 1024;
   const int64_t b = min(rows, (int64_t)tid * per), e = min(rows, b + per);
   int c = 0;
-  for (int64_t r = b; r < e; ++r) c += targets[r] >= 0 ? 1 : 0;
+  for (int64_t r = b; r < e; ++r) c += (uint32_t)targets[r] < (uint32_t)V ? 1 : 0;   // 0 <= target < V
   cnt[tid] = c;
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {       // inclusive Hillis-Steele scan
@@ -158,13 +158,13 @@ __global__ __launch_bounds__(1024) void compact_active_k(const int32_t* __restri
   }
   int pos = cnt[tid] - c;
   for (int64_t r = b; r < e; ++r)
-    if (targets[r] >= 0) index[pos++] = (int32_t)r;
+    if ((uint32_t)targets[r] < (uint32_t)V) index[pos++] = (int32_t)r;
   const int total = cnt[1023];
   for (int i = tid; i < n_chunks; i += 1024) chunk_rows[i] = min(chunk, max(0, total - i * chunk));
 }
-hipError_t compact_active(const int32_t* targets, int64_t rows, int chunk, int32_t* index, int32_t* chunk_rows, int n_chunks,
+hipError_t compact_active(const int32_t* targets, int64_t rows, int chunk, int V, int32_t* index, int32_t* chunk_rows, int n_chunks,
                           hipStream_t st) {
-  compact_active_k<<<1, 1024, 0, st>>>(targets, rows, chunk, index, chunk_rows, n_chunks);
+  compact_active_k<<<1, 1024, 0, st>>>(targets, rows, chunk, V, index, chunk_rows, n_chunks);
   return hipGetLastError();
 }
 
@@ -195,27 +195,35 @@ hipError_t scatter_rows(int dt, const void* src, const int32_t* index, const int
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(1024) void count_active_k(const int32_t* __restrict__ targets, int B, int T,
+// Active rows are those with 0 <= target < V.  A target >= V is a caller error the host cannot see (the ids live on
+// the device): such rows are treated as ignored everywhere - the id is never used as an index - and the call reports
+// them by writing minus their number to n_active instead of the count of active rows.
+__global__ __launch_bounds__(1024) void count_active_k(const int32_t* __restrict__ targets, int B, int T, int V,
                                                        float* __restrict__ seq_weight, int64_t* __restrict__ n_active) {
-  __shared__ int red[16];
-  int64_t total = 0;
+  __shared__ int red[16], red_bad[16];
+  int64_t total = 0, total_bad = 0;
   for (int j = 0; j < B; ++j) {
-    int cnt = 0;
-    for (int t = threadIdx.x; t < T; t += 1024) cnt += targets[(int64_t)j * T + t] >= 0 ? 1 : 0;
+    int cnt = 0, bad = 0;
+    for (int t = threadIdx.x; t < T; t += 1024) {
+      const int tg = targets[(int64_t)j * T + t];
+      cnt += (uint32_t)tg < (uint32_t)V ? 1 : 0;
+      bad += tg >= V ? 1 : 0;
+    }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, WAVE);
+    for (int off = 32; off > 0; off >>= 1) { cnt += __shfl_xor(cnt, off, WAVE); bad += __shfl_xor(bad, off, WAVE); }
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = cnt;
+    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = cnt; red_bad[threadIdx.x >> 6] = bad; }
     __syncthreads();
-    int tot = 0;
-    for (int i = 0; i < 16; ++i) tot += red[i];
+    int tot = 0, tot_bad = 0;
+    for (int i = 0; i < 16; ++i) { tot += red[i]; tot_bad += red_bad[i]; }
     if (threadIdx.x == 0 && seq_weight) seq_weight[j] = tot > 0 ? 1.0f / ((float)B * (float)tot) : 0.0f;
     total += tot;
+    total_bad += tot_bad;
   }
-  if (threadIdx.x == 0) *n_active = total;
+  if (threadIdx.x == 0) *n_active = total_bad > 0 ? -total_bad : total;
 }
-hipError_t count_active(const int32_t* targets, int B, int T, float* seq_weight, int64_t* n_active, hipStream_t st) {
-  count_active_k<<<1, 1024, 0, st>>>(targets, B, T, seq_weight, n_active);
+hipError_t count_active(const int32_t* targets, int B, int T, int V, float* seq_weight, int64_t* n_active, hipStream_t st) {
+  count_active_k<<<1, 1024, 0, st>>>(targets, B, T, V, seq_weight, n_active);
   return hipGetLastError();
 }
 

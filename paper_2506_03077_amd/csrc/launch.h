@@ -43,6 +43,9 @@ hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_uses_mfma(const GemmArgs& g);
 // force the generic kernel (debug / A-B tests)
 void gemm_set_force_generic(bool on);
+// bf16 problems that have run on the shape-agnostic kernels since the library was loaded
+long long generic_bf16_launches();
+void note_generic_bf16_launch();
 
 // ---- optional per-launch timing (off unless streambp_debug_profile_begin was called) ----
 namespace prof {
@@ -88,8 +91,9 @@ hipError_t add_store(int dt, const float* a, const float* b, void* y, int64_t n,
 hipError_t kv_grad_finish(int dt, const float* dK, const float* dV, const float2* tab, void* dkc, void* dvc,
                           int rows, int H, int dh, hipStream_t st);
 hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
-hipError_t embedding_fwd(int dt, const int32_t* ids, const void* emb, void* x, int64_t rows, int d, hipStream_t st);
-hipError_t embedding_bwd(int dt, const int32_t* ids, const void* dx, float* demb, int64_t rows, int d, hipStream_t st);
+// ids outside [0, vocab) are never used as an index: their x row is zero, their dx row is dropped
+hipError_t embedding_fwd(int dt, const int32_t* ids, const void* emb, void* x, int64_t rows, int d, int vocab, hipStream_t st);
+hipError_t embedding_bwd(int dt, const int32_t* ids, const void* dx, float* demb, int64_t rows, int d, int vocab, hipStream_t st);
 
 // ---- chunk attention ----
 struct AttnArgs {
@@ -134,10 +138,11 @@ struct HeadRowArgs {
 hipError_t head_rows(const HeadRowArgs& a, hipStream_t st);
 // loss += sum(row_loss[0..rows)) in a fixed order
 hipError_t reduce_add(const float* v, int n, float* out, hipStream_t st, const int* n_dev = nullptr);
-// per-sequence active counts -> seq_weight[j] = 1/(B*T_o,j) (0 if empty), n_active total
-hipError_t count_active(const int32_t* targets, int B, int T, float* seq_weight, int64_t* n_active, hipStream_t st);
-// index[0..n_active) = rows with target >= 0 in increasing order; chunk_rows[i] = clamp(n_active - i*chunk, 0, chunk)
-hipError_t compact_active(const int32_t* targets, int64_t rows, int chunk, int32_t* index, int32_t* chunk_rows, int n_chunks,
+// per-sequence active counts (0 <= target < V) -> seq_weight[j] = 1/(B*T_o,j) (0 if empty), n_active total - or minus the
+// number of targets >= V if there is any
+hipError_t count_active(const int32_t* targets, int B, int T, int V, float* seq_weight, int64_t* n_active, hipStream_t st);
+// index[0..n_active) = rows with 0 <= target < V in increasing order; chunk_rows[i] = clamp(n_active - i*chunk, 0, chunk)
+hipError_t compact_active(const int32_t* targets, int64_t rows, int chunk, int V, int32_t* index, int32_t* chunk_rows, int n_chunks,
                           hipStream_t st);
 // dst[r,:] = src[index[r],:] for r < *rows_dev, zero rows after;  scatter: dst[index[r],:] = src[r,:] for r < *rows_dev
 hipError_t gather_rows(int dt, const void* src, const int32_t* index, const int* rows_dev, void* dst, int max_rows, int d, hipStream_t st);

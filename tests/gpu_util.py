@@ -4,7 +4,9 @@ import torch
 
 from paper_2506_03077_amd import binding as sb
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}      # norm-wise relative error bound per tensor
+TOL = {"f32": 1e-4, "bf16": 2e-2}      # relative error bound per tensor (norm-wise, and max-abs scaled by max|ref|)
+BLOCK = 256                            # edge of the blocks of the per-block gate: the output tile of the MFMA GEMMs
+BLOCK_SLACK = 4.0                      # a block's norm-wise error may be this many times the tensor's bound
 
 
 def tdtype(dtype):
@@ -31,9 +33,46 @@ def relerr(got, want):
     return float(np.linalg.norm(got - want) / den) if den > 0 else float(np.linalg.norm(got))
 
 
+def block_errors(got, want, block=BLOCK):
+    """Norm-wise error of every block x block tile of the tensor seen as a matrix [prod(leading dims), last dim],
+    each relative to the larger of the reference tile's norm and the norm a tile of the tensor's mean square would
+    have (so that tiles of near-zero reference values are measured against the tensor's scale, not against nothing)."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    if want.ndim < 2:
+        got, want = got.reshape(1, -1), want.reshape(1, -1)
+    got, want = got.reshape(-1, got.shape[-1]), want.reshape(-1, want.shape[-1])
+    R, Cn = want.shape
+    pr, pc = (-R) % block, (-Cn) % block
+
+    def tiles(a):
+        a = np.pad(a, ((0, pr), (0, pc)))
+        return (a.reshape((R + pr) // block, block, (Cn + pc) // block, block) ** 2).sum(axis=(1, 3))
+
+    diff2, ref2 = tiles(got - want), tiles(want)
+    floor2 = np.mean(want * want) * block * block
+    den2 = np.maximum(ref2, floor2)
+    # an all-zero reference: any deviation at all is an infinite error
+    return np.sqrt(np.where(den2 > 0, diff2 / np.where(den2 > 0, den2, 1.0), np.where(diff2 > 0, np.inf, 0.0)))
+
+
 def assert_close(got, want, tol, name):
+    """Three gates: norm-wise error of the whole tensor <= tol; largest elementwise deviation <= tol * max|ref|; and the
+    norm-wise error of every 256 x 256 tile <= BLOCK_SLACK * tol, so that one wrong output tile of a large tensor -
+    which moves the whole-tensor norm by far less than tol - still fails."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, f"{name}: shape {got.shape} != {want.shape}"
     e = relerr(got, want)
     assert np.isfinite(e) and e <= tol, f"{name}: norm-wise relative error {e:.3e} > {tol:.1e}"
+    ref_max = float(np.max(np.abs(want))) if want.size else 0.0
+    dev_max = float(np.max(np.abs(got - want))) if want.size else 0.0
+    assert dev_max <= tol * ref_max or dev_max == 0.0, \
+        f"{name}: max-abs error {dev_max:.3e} > {tol:.1e} * max|ref| = {tol * ref_max:.3e}"
+    if want.size:
+        be = block_errors(got, want)
+        i = np.unravel_index(int(np.argmax(be)), be.shape)
+        assert be[i] <= BLOCK_SLACK * tol, f"{name}: tile {i} of {be.shape} has norm-wise error {be[i]:.3e} > {BLOCK_SLACK * tol:.1e}"
     return e
 
 

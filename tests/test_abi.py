@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/streambp.h declares;
+"""The C-ABI library loads and exports every symbol include/*.h declares;
 host-side validation returns the documented error codes (no GPU needed: every
 check happens before the first HIP call)."""
 import ctypes as C
@@ -12,10 +12,22 @@ from paper_2506_03077_amd import binding as sb
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    src = open(os.path.join(ROOT, "include", "streambp.h")).read()
+def declared_functions(header="streambp.h"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(streambp_\w+)\s*\(", src)))
+
+
+def test_every_exported_symbol_is_declared_in_a_header():
+    # nothing is exported behind the headers' back: the library's dynamic symbols named streambp_* are exactly
+    # those of include/streambp.h plus the test hooks of include/streambp_debug.h
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", sb.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = sorted({line.split()[-1] for line in out.splitlines() if line.split()[-1].startswith("streambp_")})
+    declared = sorted(set(declared_functions()) | set(declared_functions("streambp_debug.h")))
+    assert exported == declared
+    assert all(n.startswith("streambp_debug_") for n in declared_functions("streambp_debug.h"))
+    assert not any(n.startswith("streambp_debug_") for n in declared_functions())
 
 
 def test_header_declares_the_three_named_entry_points():
@@ -26,7 +38,7 @@ def test_header_declares_the_three_named_entry_points():
 
 def test_library_exports_every_declared_symbol():
     L = sb.lib()
-    for n in declared_functions():
+    for n in declared_functions() + declared_functions("streambp_debug.h"):
         assert hasattr(L, n), n
     assert b"gfx950" in L.streambp_version()
 
@@ -142,6 +154,23 @@ def test_head_and_attn_codes():
     assert sb.streambp_attn_workspace_bytes(ac) == 0
     ac = sb.attn_cfg(sb.SBP_BF16, 8, 2, 128, -1, 64, 0.1)
     assert L.streambp_attn_chunk_forward(C.byref(ac), 256, 256, 256, 256, 256, None) == -2
+    for bad_scale in (0.0, -0.1, float("nan"), float("inf")):     # the kernels order raw scores: scale must be > 0
+        ac = sb.attn_cfg(sb.SBP_BF16, 8, 2, 128, 0, 64, bad_scale)
+        assert L.streambp_attn_chunk_forward(C.byref(ac), 256, 256, 256, 256, 256, None) == -2
+
+
+def test_fast_path_query_names_the_configs_that_leave_the_mfma_kernels():
+    big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
+    assert sb.streambp_layer_fast_path(good_layer_cfg(**big)) == 1
+    assert sb.streambp_layer_fast_path(good_layer_cfg(**dict(big, mlp_width=18944 + 64))) == 0
+    assert "mlp_width" in sb.streambp_last_error()
+    assert sb.streambp_layer_fast_path(good_layer_cfg(**dict(big, head_dim=64, n_q_heads=56, n_kv_heads=8))) == 0
+    assert sb.streambp_layer_fast_path(good_layer_cfg()) == 0                       # fp32 storage
+    assert sb.streambp_layer_fast_path(good_layer_cfg(chunk=0)) == -2
+    assert sb.streambp_lmhead_fast_path(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 152064)) == 1
+    assert sb.streambp_lmhead_fast_path(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 151936)) == 0   # 593.5 x 256
+    assert "vocab" in sb.streambp_last_error()
+    assert sb.streambp_generic_launches() >= 0
 
 
 def test_attn_tile_pairs_follow_the_causal_count():

@@ -45,3 +45,12 @@ def test_more_than_one_gpu_is_refused():
     import sys
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert p.returncode != 0 and "ONE GPU" in p.stderr
+
+
+def test_whole_stack_flops():
+    # 28 layers + head on all 32768 positions: 28 * (45.82 + 26.94) + 107.15 TF = 2.144 PF
+    cfg = synth.CONFIGS["7b"]
+    fl = bench.algorithmic_flops(cfg, 32768, 32768, n_layers=28)
+    assert abs(fl["total"] / 1e15 - 2.144) < 0.002
+    one = bench.algorithmic_flops(cfg, 32768, 32768)
+    assert abs(one["total"] / 1e12 - 179.9) < 0.05 and one["total"] == one["total_all_rows"]

@@ -2,8 +2,11 @@
 (bf16, d=3584, 28q/4kv x128, F=18944, V=152064, chunk 2048).
 
 The fp64 oracle cannot run a 32k-token layer (it is a plain full-sequence backprop), so:
-  * layer and head are compared element by element against the oracle at the real widths and a
-    sequence length the oracle finishes in tens of seconds (several chunks, prefix attention);
+  * layer and head are compared element by element against the oracle at the real widths AND the real chunk size
+    (2048 rows; also 512 and no partition), at a sequence length the oracle finishes in tens of seconds
+    (T = 4608 for the layer: two full chunks and a ragged one; 8792 rows for the head: four full chunks and a
+    ragged one), so that the kernels' launch shapes - split-K factors, operand pairs, grouped multi-segment
+    weight-gradient passes - are those of the benchmark;
   * at the full 32k length, chunk attention is compared element by element against the oracle
     for one whole KV group (the oracle's cost there is small), and the layer / head are checked
     through properties that hold at any size (chunk-size invariance, exact zeros of ignored
@@ -26,34 +29,80 @@ C7B = synth.CONFIGS["7b"]
 TOL = 2e-2
 
 
-def test_layer_7b_widths_vs_oracle():
-    T, chunk = 1536, 512
-    inp = synth.layer_inputs(C7B, seed=0, seq_len=T)
-    _, dx_ref, g_ref = o_layer.layer_forward_backward(inp["x"], inp["w"], oracle_cfg(C7B), inp["dy"])
+_LAYER_REF = {}
+
+
+def layer_reference(cfg, T, seed):
+    """Oracle gradients of one layer, computed once per (shape, T, seed) and shared by the chunk sizes compared with them."""
+    key = (cfg["hidden"], cfg["mlp_width"], T, seed)
+    if key not in _LAYER_REF:
+        inp = synth.layer_inputs(cfg, seed=seed, seq_len=T)
+        _, dx_ref, g_ref = o_layer.layer_forward_backward(inp["x"], inp["w"], oracle_cfg(cfg), inp["dy"])
+        _LAYER_REF[key] = (inp, dx_ref, g_ref)
+    return _LAYER_REF[key]
+
+
+@pytest.mark.parametrize("chunk", [2048, 512, 4608])
+def test_layer_7b_widths_vs_oracle(chunk):
+    # 7B widths, T = 4608 = 2.25 chunks of 2048 (the chunk bench.py times; the last chunk ragged).  At chunk 2048 the layer
+    # runs what the bench runs: the two-way XCD-pinned split-K input-gradient GEMMs over 112 output tiles, the operand-pair
+    # dm GEMM, and ONE grouped weight-gradient launch with three reduction segments of 2048, 2048 and 512 rows; chunk 512
+    # takes the 8-way split-K and groups of four chunks, chunk = T no partition at all.
+    T = 4608
+    assert sb.streambp_layer_fast_path(lib_layer_cfg(C7B, T, chunk)) == 1
+    inp, dx_ref, g_ref = layer_reference(C7B, T, 0)
     w = {k: dev(v, "bf16") for k, v in inp["w"].items()}
+    before = sb.streambp_generic_launches()
     dx, dw = sb.streambp_layer_backward(lib_layer_cfg(C7B, T, chunk), w, dev(inp["x"], "bf16"), dev(inp["dy"], "bf16"))
     torch.cuda.synchronize()
-    assert_close(host(dx), dx_ref[0] if dx_ref.ndim == 3 and dx.ndim == 2 else dx_ref, TOL, "dx")
+    assert sb.streambp_generic_launches() == before        # nothing left the MFMA kernels
+    assert_close(host(dx), dx_ref, TOL, f"dx (chunk {chunk})")
     for n in sb.WEIGHT_NAMES:
-        assert_close(host(dw[n]), g_ref[n], TOL, f"d{n}")
+        assert_close(host(dw[n]), g_ref[n], TOL, f"d{n} (chunk {chunk})")
 
 
 def test_head_full_vocab_vs_oracle():
-    T, chunk = 768, 512
+    # V = 152064 at the bench's chunk of 2048 rows with 8792 active rows: four full chunks, whose weight gradient is one
+    # four-segment pass over dW, then a ragged fifth chunk (600 rows) that is a pass of its own; every row of dh and every
+    # 256 x 256 tile of dW (8316 of them) is compared with the oracle.
+    T, chunk = 8792, 2048
     cfg = synth.CONFIGS["lmhead"]
-    inp = synth.head_inputs(cfg, seed=0, seq_len=T)
+    inp = synth.head_inputs(cfg, seed=0, seq_len=T, prompt_frac=0.0)
     n_act = int((inp["targets"] >= 0).sum())
+    assert n_act == T
     ref = o_head.sft(inp["h"], inp["w"], inp["targets"], 1.0 / n_act)
     hc = sb.head_cfg(sb.SBP_BF16, 1, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, 1.0 / n_act)
+    assert sb.streambp_lmhead_fast_path(hc) == 1
+    before = sb.streambp_generic_launches()
     dh, dw, loss, n_active = sb.streambp_lmhead_ce_backward(hc, dev(inp["w"], "bf16"), dev(inp["h"], "bf16"),
                                                             torch.from_numpy(inp["targets"]).cuda())
     torch.cuda.synchronize()
+    assert sb.streambp_generic_launches() == before
     assert int(n_active.item()) == n_act
     assert_close(host(dh), ref["dh"], TOL, "dh")
     assert_close(host(dw), ref["dw"], TOL, "dw")
     assert abs(float(loss.item()) - ref["loss"]) < 2e-3 * ref["loss"]
     # random-init logits are ~N(0, 0.02^2 * d): mean loss ~ ln V + var/2
     assert abs(ref["loss"] - (np.log(cfg["vocab"]) + 0.5 * 0.02 ** 2 * cfg["hidden"])) < 0.1
+
+
+def test_head_full_vocab_with_prompt_mask_vs_oracle():
+    # the same with the first quarter of the rows ignored (the LM-head workload of the shape list): the active rows are
+    # compacted, 2304 of them = one full chunk and a ragged one in ONE two-segment pass over dW
+    T, chunk = 3072, 2048
+    cfg = synth.CONFIGS["lmhead"]
+    inp = synth.head_inputs(cfg, seed=1, seq_len=T)
+    n_act = int((inp["targets"] >= 0).sum())
+    ref = o_head.sft(inp["h"], inp["w"], inp["targets"], 1.0 / n_act)
+    hc = sb.head_cfg(sb.SBP_BF16, 1, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, 1.0 / n_act)
+    dh, dw, loss, n_active = sb.streambp_lmhead_ce_backward(hc, dev(inp["w"], "bf16"), dev(inp["h"], "bf16"),
+                                                            torch.from_numpy(inp["targets"]).cuda())
+    torch.cuda.synchronize()
+    assert int(n_active.item()) == n_act == T - T // 4
+    assert torch.all(dh[:, :T // 4] == 0)
+    assert_close(host(dh), ref["dh"], TOL, "dh")
+    assert_close(host(dw), ref["dw"], TOL, "dw")
+    assert abs(float(loss.item()) - ref["loss"]) < 2e-3 * ref["loss"]
 
 
 def test_attention_last_chunk_of_32k_one_kv_group_vs_oracle():
@@ -130,11 +179,11 @@ LLAMA = synth.CONFIGS["llama_layer"]
 
 
 def test_llama_layer_widths_vs_oracle_and_8k_chunk_invariance():
-    # Llama-style layer (d=4096, 32q/8kv x128, F=14336): element by element against the oracle at a length it
-    # finishes in seconds, then the real shape (T=8192, chunk 1024) against itself at another chunk size.
-    T, chunk = 768, 256
-    inp = synth.layer_inputs(LLAMA, seed=4, seq_len=T)
-    _, dx_ref, g_ref = o_layer.layer_forward_backward(inp["x"], inp["w"], oracle_cfg(LLAMA), inp["dy"])
+    # Llama-style layer (d=4096, 32q/8kv x128, F=14336): element by element against the oracle at the config's own chunk
+    # of 1024 rows (T = 2560: two chunks and a ragged third, one three-segment weight-gradient launch), then the real shape
+    # (T=8192, chunk 1024) against itself at another chunk size.
+    T, chunk = 2560, LLAMA["chunk"]
+    inp, dx_ref, g_ref = layer_reference(LLAMA, T, 4)
     w = {k: dev(v, "bf16") for k, v in inp["w"].items()}
     dx, dw = sb.streambp_layer_backward(lib_layer_cfg(LLAMA, T, chunk), w, dev(inp["x"], "bf16"), dev(inp["dy"], "bf16"))
     torch.cuda.synchronize()

@@ -12,7 +12,7 @@ from oracle import layer as o_layer
 from paper_2506_03077_amd import binding as sb
 from paper_2506_03077_amd import synth
 
-from gpu_util import TOL, assert_close, code, dev, host, lib_layer_cfg, oracle_cfg, tdtype
+from gpu_util import TOL, assert_close, code, dev, host, lib_layer_cfg, oracle_cfg, relerr, tdtype
 
 pytestmark = pytest.mark.gpu
 
@@ -272,6 +272,13 @@ def test_attn_bf16_dh128(s, c):
     attn_case("bf16", 8, 2, 128, s, c, extra_rows=3)
 
 
+# Peaked softmax rows (one probability ~1): dS = P (dP - delta) is then a difference of two nearly equal numbers for the
+# dominant key, and delta = rowsum(dO * O) is formed from the bf16-rounded O (relative 2^-9): the rounding of O is
+# amplified by |dP| / |dP - delta|.  This is a property of any backward that keeps O in bf16, not of the tiling; the
+# bound for this one adversarial case is therefore 1.5x the general bf16 bound.
+PEAKED_TOL = 3e-2
+
+
 def test_large_magnitudes_do_not_overflow():
     # Scores / logits far outside the range where exp would survive without the running-max shift: peaked softmax rows
     # (probabilities 0 and 1 to rounding), results must stay finite and match the oracle.
@@ -290,8 +297,11 @@ def test_large_magnitudes_do_not_overflow():
         assert bool(torch.isfinite(t.float()).all())
     assert_close(host(o), o_ref, 2e-2, "o")
     assert_close(host(lse), lse_ref, 2e-3, "lse")
-    assert_close(host(dq), dq_ref, 3e-2, "dq")
-    assert_close(host(dk)[:s + c], dk_ref, 3e-2, "dk")
+    print("large-magnitude attention: norm-wise errors",
+          {n: f"{e:.2e}" for n, e in (("dq", relerr(host(dq), dq_ref)), ("dk", relerr(host(dk)[:s + c], dk_ref)),
+                                      ("dv", relerr(host(dv)[:s + c], dv_ref)))})
+    assert_close(host(dq), dq_ref, PEAKED_TOL, "dq")
+    assert_close(host(dk)[:s + c], dk_ref, PEAKED_TOL, "dk")
     assert_close(host(dv)[:s + c], dv_ref, 2e-2, "dv")
     # head: hidden states x 40 -> logits ~ N(0, 48^2) at the tiny shape, far beyond exp's fp32 range unshifted
     hin = synth.head_inputs(TINY, seed=5, seq_len=64, batch=2, vocab=TINY["vocab"])
@@ -317,6 +327,87 @@ def test_large_magnitudes_do_not_overflow():
     assert_close(host(dh_), ref["dh"], 2e-2, "dh (mixed row scales)")
     assert_close(host(dw_), ref["dw"], 2e-2, "dw (mixed row scales)")
     assert abs(float(loss.item()) - ref["loss"]) <= 2e-3 * abs(ref["loss"])
+
+
+def test_causality_is_bit_exact_inside_the_visible_range():
+    # Property 3.1 / the causal mask as integer arithmetic: query t never sees key u > t, also when u lies inside the chunk's
+    # visible range (same chunk, same 64-key tile, same 32-query wave).  Changing x rows (resp. q, k, v rows) after t must
+    # leave the rows up to t of the layer's output (resp. of o and lse) bit-identical.
+    cfg, T, chunk = MID16, 640, 256
+    inp = synth.layer_inputs(cfg, seed=9, seq_len=T)
+    w = {k: dev(v, "bf16") for k, v in inp["w"].items()}
+    x = dev(inp["x"], "bf16")
+    y = sb.streambp_layer_forward(lib_layer_cfg(cfg, T, chunk), w, x)
+    for t in (0, 31, 63, 300, 511, 638):            # wave, tile and chunk boundaries and the middle of a tile
+        x2 = x.clone()
+        x2[:, t + 1:] = (x2[:, t + 1:].float() * -3.0 + 0.5).to(torch.bfloat16)     # finite, very different values
+        y2 = sb.streambp_layer_forward(lib_layer_cfg(cfg, T, chunk), w, x2)
+        torch.cuda.synchronize()
+        assert torch.equal(y2[:, :t + 1], y[:, :t + 1]), f"rows <= {t} changed"
+        assert not torch.equal(y2[:, t + 1:], y[:, t + 1:])
+    Hq, Hkv, dh, s, c = 8, 2, 128, 300, 200
+    a = synth.attn_inputs(Hq, Hkv, dh, s, c, "bf16", 3)
+    q, k, v = (dev(a[n], "bf16") for n in ("q", "k", "v"))
+    ac = sb.attn_cfg(sb.SBP_BF16, Hq, Hkv, dh, s, c, 1.0 / np.sqrt(dh))
+    o, lse = sb.streambp_attn_chunk_forward(ac, q, k, v)
+    for t in (0, 19, 20, 83, 198):                   # position s + t: tile boundaries of the prefix fall at t = 20, 84
+        q2, k2, v2 = q.clone(), k.clone(), v.clone()
+        q2[t + 1:] = -q2[t + 1:]
+        k2[s + t + 1:] = (k2[s + t + 1:].float() * 5.0).to(torch.bfloat16)
+        v2[s + t + 1:] = (v2[s + t + 1:].float() + 7.0).to(torch.bfloat16)
+        o2, lse2 = sb.streambp_attn_chunk_forward(ac, q2, k2, v2)
+        torch.cuda.synchronize()
+        assert torch.equal(o2[:t + 1], o[:t + 1]) and torch.equal(lse2[:, :t + 1], lse[:, :t + 1]), f"queries <= {t} changed"
+        assert not torch.equal(o2[t + 1:], o[t + 1:])
+    # and through the shape-agnostic fp32 kernels
+    a = synth.attn_inputs(4, 2, 16, 37, 50, "f32", 4)
+    q, k, v = (dev(a[n], "f32") for n in ("q", "k", "v"))
+    ac = sb.attn_cfg(sb.SBP_F32, 4, 2, 16, 37, 50, 0.25)
+    o, lse = sb.streambp_attn_chunk_forward(ac, q, k, v)
+    k2, v2 = k.clone(), v.clone()
+    k2[37 + 11:] *= -2.0
+    v2[37 + 11:] += 1.0
+    o2, lse2 = sb.streambp_attn_chunk_forward(ac, q, k2, v2)
+    torch.cuda.synchronize()
+    assert torch.equal(o2[:11], o[:11]) and torch.equal(lse2[:, :11], lse[:, :11])
+
+
+@pytest.mark.parametrize("cfg", [MID16, TINY])
+def test_target_ids_outside_the_vocabulary_are_flagged_and_never_indexed(cfg):
+    # ids >= V (also the largest int32) cannot be seen by the host: the kernels treat those rows as ignored, never use
+    # the id as an index, and report their number as a negative n_active; the other rows' gradients are the oracle's
+    B, T, chunk, V = 2, 150, 64, cfg["vocab"]
+    dt = cfg["dtype"]
+    inp = synth.head_inputs(cfg, seed=8, seq_len=T, batch=B, vocab=V)
+    bad = inp["targets"].copy()
+    bad[0, 100], bad[1, 60], bad[1, 149] = V, V + 7, np.iinfo(np.int32).max
+    as_ignored = np.where(bad >= V, -1, bad).astype(np.int32)
+    ref = o_head.sft(inp["h"], inp["w"], as_ignored, 1.0 / 100)
+    hc = sb.head_cfg(code(dt), B, T, chunk, cfg["hidden"], V, sb.SBP_OBJ_SFT, 1.0 / 100)
+    dh, dw, loss, n_active = sb.streambp_lmhead_ce_backward(hc, dev(inp["w"], dt), dev(inp["h"], dt), torch.from_numpy(bad).cuda())
+    torch.cuda.synchronize()
+    assert int(n_active.item()) == -3
+    assert_close(host(dh), ref["dh"], TOL[dt], "dh")
+    assert_close(host(dw), ref["dw"], TOL[dt], "dw")
+    assert torch.all(dh[torch.from_numpy(bad >= V).cuda()] == 0)
+    assert abs(float(loss.item()) - ref["loss"]) <= TOL[dt] * max(1.0, abs(ref["loss"]))
+
+
+def test_embedding_ids_outside_the_table_are_never_indexed():
+    V, d, n = 50, 72, 40
+    rng = np.random.default_rng(1)
+    ids_np = rng.integers(0, V, n).astype(np.int32)
+    ids_np[[3, 17, 39]] = [-1, V, np.iinfo(np.int32).max]
+    ids = torch.from_numpy(ids_np).cuda()
+    emb = dev(rng.normal(size=(V, d)), "f32")
+    x = sb.streambp_embedding_forward(ids, emb)
+    ok = torch.from_numpy((ids_np >= 0) & (ids_np < V)).cuda()
+    assert torch.equal(x[ok], emb[ids[ok].long()]) and torch.all(x[~ok] == 0)
+    dx = dev(rng.normal(size=(n, d)), "f32")
+    demb = sb.streambp_embedding_backward(ids, dx, V)
+    want = np.zeros((V, d))
+    np.add.at(want, ids_np[ok.cpu().numpy()], host(dx)[ok.cpu().numpy()])
+    assert_close(host(demb), want, 1e-6, "demb")
 
 
 def test_attn_empty_chunk_is_a_no_op():

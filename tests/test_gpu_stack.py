@@ -75,3 +75,43 @@ def test_stack_forward_backward(name, L, T, chunk, head_chunk, grad_dtype):
     for l in range(L):
         for n in sb.WEIGHT_NAMES:
             assert_close(host(out["dlayers"][l][n]), ref["dlayers"][l][n], tol, f"layer {l} d{n}")
+
+
+def test_stack_of_four_7b_layers_at_32k_structure_and_chunk_invariance():
+    # The 7B-shaped stack at its full length (T = 32768, chunk 2048, V = 152064) with four layers: the oracle cannot run this
+    # size, so what is checked holds at any size - exact n_active, finite outputs, the loss of random-init logits
+    # (ln V + var/2), rows after the last position that carries a loss get exactly zero gradient through every layer
+    # (causality), and the weight gradients of layer 0 - which depend on everything above it - do not depend on the chunk
+    # size beyond rounding order (Eq. 1).
+    cfg = dict(synth.CONFIGS["7b"])
+    L, T, V, d = 4, cfg["seq_len"], cfg["vocab"], cfg["hidden"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(12)
+    bf = torch.bfloat16
+    rn = lambda shape, std, mean=0.0: (torch.randn(shape, generator=gen, device="cuda") * std + mean).to(bf)
+    Hq, Hkv, dh, F = (cfg[k] for k in ("n_q_heads", "n_kv_heads", "head_dim", "mlp_width"))
+    layers = [dict(wq=rn((Hq * dh, d), 0.02), wk=rn((Hkv * dh, d), 0.02), wv=rn((Hkv * dh, d), 0.02), wo=rn((d, Hq * dh), 0.02),
+                   wgate=rn((F, d), 0.02), wup=rn((F, d), 0.02), wdown=rn((d, F), 0.02), g1=rn((d,), 0.02, 1.0), g2=rn((d,), 0.02, 1.0))
+              for _ in range(L)]
+    g_final, w_head, emb = rn((d,), 0.02, 1.0), rn((V, d), 0.02), rn((V, d), 1.0)
+    ids = torch.randint(0, V, (1, T), generator=gen, device="cuda", dtype=torch.int32)
+    targets = torch.randint(0, V, (1, T), generator=gen, device="cuda", dtype=torch.int32)
+    last = T - 5000
+    targets[:, last + 1:] = -1                                    # no loss after position `last`
+    n_act = last + 1
+    results = []
+    for chunk in (2048, 4096):
+        sc = sb.stack_cfg(lib_layer_cfg(cfg, T, chunk), L, V, 2048, sb.SBP_OBJ_SFT, 1.0 / n_act)
+        ckpt = [torch.empty((1, T, d), dtype=bf, device="cuda") for _ in range(L + 1)]
+        sb.streambp_stack_forward(sc, layers, ckpt, emb, ids)
+        out = sb.streambp_stack_backward(sc, layers, g_final, w_head, ckpt, targets, ids=ids)
+        torch.cuda.synchronize()
+        assert int(out["n_active"].item()) == n_act
+        assert abs(float(out["loss"].item()) - (np.log(V) + 0.5 * 0.02 ** 2 * d)) < 0.15
+        assert bool(torch.isfinite(out["dx0"].float()).all()) and bool(torch.isfinite(ckpt[L].float()).all())
+        assert torch.all(out["dx0"][:, last + 1:] == 0)           # causality through four layers: exact zeros
+        assert float(out["dx0"][:, :last + 1].float().abs().max()) > 0
+        results.append({n: out["dlayers"][0][n] for n in sb.WEIGHT_NAMES})
+        del out, ckpt
+    from gpu_util import relerr
+    for n in sb.WEIGHT_NAMES:
+        assert relerr(host(results[1][n]), host(results[0][n])) < 1.5e-2, n
