@@ -211,6 +211,20 @@ int32_t streambp_attn_chunk_backward(const sbp_attn_cfg *cfg, const void *q, con
                                      const void *d_o, void *dq, float *dk, float *dv,
                                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same backward for callers that cannot allocate device memory and have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Identical arguments, kernels and results,
+ * but the scratch (2 floats per (query, head) pair) is a fixed array inside the library's own device image - 2 MiB
+ * that every GPU the library runs on holds until the process ends - so the call takes no workspace and makes no
+ * allocation of any kind.  Limit: q_len * n_q_heads <= 262144 (e.g. 2048 queries x 128 heads); larger chunks return
+ * SBP_ERR_WORKSPACE and must use the call above.  All calls on one GPU share that array: calls that overlap on one
+ * GPU (two streams, two threads) race and must be ordered by the caller; nothing in it has to be cleared between calls
+ * (every element a call reads it has written first).  The first call on a device looks the array's address up (a symbol
+ * query, no allocation): make that call outside stream capture. */
+int32_t streambp_attn_chunk_backward_noalloc(const sbp_attn_cfg *cfg, const void *q, const void *k,
+                                             const void *v, const void *o, const float *lse,
+                                             const void *d_o, void *dq, float *dk, float *dv,
+                                             void *hip_stream);
+
 /* ------------------------------------------------ stack glue (Sec. 2, 3.1) -- */
 
 /* Final RMSNorm between the layer stack and the LM head, and the embedding

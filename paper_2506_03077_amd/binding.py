@@ -88,6 +88,8 @@ def lib():
         L.streambp_attn_chunk_forward.argtypes = [C.POINTER(AttnCfg), vp, vp, vp, vp, vp, vp]
         L.streambp_attn_chunk_backward.restype = i32
         L.streambp_attn_chunk_backward.argtypes = [C.POINTER(AttnCfg), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.streambp_attn_chunk_backward_noalloc.restype = i32
+        L.streambp_attn_chunk_backward_noalloc.argtypes = [C.POINTER(AttnCfg), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.streambp_rmsnorm_workspace_bytes.restype = sz
         L.streambp_rmsnorm_workspace_bytes.argtypes = [i64, i32]
         L.streambp_rmsnorm_forward.restype = i32
@@ -294,6 +296,13 @@ def streambp_attn_chunk_backward(cfg: AttnCfg, q, k, v, o, lse, d_o, dq=None, dk
     _check(lib().streambp_attn_chunk_backward(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
                                               _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), workspace.numel(),
                                               _stream(stream)))
+    return dq, dk, dv
+
+
+def streambp_attn_chunk_backward_noalloc(cfg: AttnCfg, q, k, v, o, lse, d_o, dq, dk, dv, stream=None):
+    """The backward without a workspace (the library's built-in scratch); every output tensor is the caller's."""
+    _check(lib().streambp_attn_chunk_backward_noalloc(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                                      _ptr(dq), _ptr(dk), _ptr(dv), _stream(stream)))
     return dq, dk, dv
 
 

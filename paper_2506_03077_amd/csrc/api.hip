@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 using namespace sbp;
 
@@ -563,6 +564,52 @@ int32_t streambp_lmhead_fast_path(const sbp_head_cfg* c) {
   return 1;
 }
 int64_t streambp_generic_launches(void) { return (int64_t)generic_bf16_launches(); }
+
+// ---- the same backward for callers that cannot allocate ------------------------------------------------------
+// The per-call scratch of the attention backward (delta and the log2-domain log-sum-exp, 2 floats per (query, head)
+// pair) lives in device memory that belongs to the library's code object instead of a caller workspace.  Every GPU
+// the library runs on holds its own copy of the array at its own address; the address is looked up once per device
+// (a symbol query, not an allocation) and only that pointer - never the array's name, which on the host is a stand-in
+// and not a device address - is handed to kernels.
+constexpr int64_t STATIC_SCRATCH_PAIRS = 1 << 18;            // q_len * n_q_heads <= 262144 (2 MiB of scratch)
+static __device__ __align__(256) float g_static_scratch[2 * STATIC_SCRATCH_PAIRS];
+constexpr int STATIC_MAX_DEVICES = 64;
+static float* g_static_scratch_ptr[STATIC_MAX_DEVICES];      // per device, filled on the first call on that device
+static std::mutex g_static_scratch_mu;
+
+int32_t streambp_attn_chunk_backward_noalloc(const sbp_attn_cfg* c, const void* q, const void* k, const void* v, const void* o,
+                                             const float* lse, const void* d_o, void* dq, float* dk, float* dv,
+                                             void* hip_stream) {
+  int32_t rc = check_attn_cfg(c);
+  if (rc) return rc;
+  if (c->q_len == 0) return SBP_OK;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return fail(SBP_ERR_NULL, "all tensor pointers must be non-NULL");
+  const int64_t pairs = (int64_t)c->q_len * c->n_q_heads;
+  if (pairs > STATIC_SCRATCH_PAIRS)
+    return fail(SBP_ERR_WORKSPACE, "q_len * n_q_heads = %lld exceeds the %lld pairs the built-in scratch holds; use "
+                "streambp_attn_chunk_backward with a caller workspace", (long long)pairs, (long long)STATIC_SCRATCH_PAIRS);
+  int dev = -1;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(SBP_ERR_UNSUPPORTED, "device index %d out of range", dev);
+  float* scratch;
+  {
+    std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+    if (!g_static_scratch_ptr[dev]) {
+      void* p = nullptr;
+      HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)));
+      if (!p) return fail(SBP_ERR_HIP, "hipGetSymbolAddress returned a null address for the built-in scratch");
+      g_static_scratch_ptr[dev] = (float*)p;
+    }
+    scratch = g_static_scratch_ptr[dev];
+  }
+  AttnArgs a{};
+  a.dt = c->dtype; a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads; a.dh = c->head_dim;
+  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale;
+  a.q = q; a.k = k; a.v = v; a.o = (void*)o; a.lse = (float*)lse;
+  a.d_o = d_o; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = scratch;
+  HIPCHK(attn_backward(a, (hipStream_t)hip_stream));
+  return SBP_OK;
+}
 
 int64_t streambp_attn_tile_pairs(int32_t q_start, int32_t q_len, int32_t* tile_q, int32_t* tile_k) {
   // Work is skipped per wave: a wave owns ATTN_WAVE_Q query rows and walks key tiles of ATTN_TILE_K.

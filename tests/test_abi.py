@@ -159,6 +159,15 @@ def test_head_and_attn_codes():
         assert L.streambp_attn_chunk_forward(C.byref(ac), 256, 256, 256, 256, 256, None) == -2
 
 
+def test_noalloc_backward_rejects_what_the_builtin_scratch_cannot_hold():
+    L = sb.lib()
+    ac = sb.attn_cfg(sb.SBP_BF16, 128, 8, 128, 0, 2049, 0.1)      # 2049 x 128 pairs > 262144
+    assert L.streambp_attn_chunk_backward_noalloc(C.byref(ac), 256, 256, 256, 256, 256, 256, 256, 256, 256, None) == -4
+    assert "built-in scratch" in sb.streambp_last_error()
+    ac = sb.attn_cfg(sb.SBP_BF16, 128, 8, 128, 0, 2048, 0.1)      # exactly at the limit: the NULL check is what stops it
+    assert L.streambp_attn_chunk_backward_noalloc(C.byref(ac), None, 256, 256, 256, 256, 256, 256, 256, 256, None) == -1
+
+
 def test_fast_path_query_names_the_configs_that_leave_the_mfma_kernels():
     big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
     assert sb.streambp_layer_fast_path(good_layer_cfg(**big)) == 1
