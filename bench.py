@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--head-chunk", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--fusions", type=int, default=None,
+                    help="A/B: bit mask of the optional fusions of the layer path (see include/streambp_debug.h); default: the library's")
     ap.add_argument("--no-masked-run", action="store_true",
                     help="skip the second timing of the default workload with the first 25%% of the positions ignored")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -130,6 +132,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     sb.lib()   # fails loudly if the HIP library is missing
+    if args.fusions is not None:
+        sb.debug_set_fusions(args.fusions)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 

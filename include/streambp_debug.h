@@ -18,6 +18,13 @@ extern "C" {
 /* Route every GEMM / every attention call through the shape-agnostic kernels (process-wide switch). */
 void streambp_debug_force_generic(int gemm_on, int attn_on);
 
+/* Which optional fusions the layer entry points use (process-wide switch, for A/B timing; results agree to rounding):
+ * bit 0: SwiGLU adjoint in the epilogue of the dact = dy W_down GEMM instead of an elementwise pass;
+ * bit 1: rotary embedding of q, and its adjoint on dq, inside the attention kernels instead of two elementwise passes.
+ * The default is what measured fastest on MI355X. */
+void streambp_debug_set_fusions(int mask);
+int streambp_debug_get_fusions(void);
+
 /* One GEMM through the library's dispatcher: C[M,N] (=|+=) op(A) op(B) [+ op(A2) op(B2)], fp32 accumulation.
  *   A(m,k) = ta ? A[k*lda+m] : A[m*lda+k];  B(k,n) = tb ? B[n*ldb+k] : B[k*ldb+n];  in_dt / out_dt: SBP_F32 or SBP_BF16.
  *   scratch: optional device fp32 buffer for split-K partial tiles;  row_stats: optional device [M, N/256] pairs

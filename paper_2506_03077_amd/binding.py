@@ -108,6 +108,9 @@ def lib():
         L.streambp_lmhead_fast_path.argtypes = [C.POINTER(HeadCfg)]
         L.streambp_generic_launches.restype = i64
         L.streambp_generic_launches.argtypes = []
+        L.streambp_debug_set_fusions.restype = None
+        L.streambp_debug_set_fusions.argtypes = [C.c_int]
+        L.streambp_debug_get_fusions.restype = C.c_int
         L.streambp_debug_force_generic.restype = None
         L.streambp_debug_force_generic.argtypes = [C.c_int, C.c_int]
         L.streambp_debug_gemm.restype = C.c_int
@@ -368,6 +371,14 @@ def streambp_attn_tile_pairs(q_start, q_len):
     return int(n), tq.value, tk.value
 
 
+def debug_set_fusions(mask):
+    """Optional fusions of the layer path (bit 0: SwiGLU adjoint in the dact GEMM's epilogue; bit 1: RoPE of q / dq inside
+    the attention kernels); returns the previous mask."""
+    old = lib().streambp_debug_get_fusions()
+    lib().streambp_debug_set_fusions(int(mask))
+    return old
+
+
 def debug_force_generic(gemm=False, attn=False):
     """Route GEMMs / attention through the shape-agnostic kernels (A/B testing of the MFMA kernels)."""
     lib().streambp_debug_force_generic(int(gemm), int(attn))
@@ -407,7 +418,7 @@ def _profile_kind_names():
     names = [f"gemm_mfma_k<{t}, {m}>" for t, _ in lay for m in range(4)]
     names += [f"gemm_mfma_group_k<{t}, {m}>" for t, _ in lay for m in range(4)]
     names += ["gemm_generic_k", "attn_fwd (launch sequence)", "attn_bwd (delta + dq + dkv launch sequence)", "gemm_mfma_seg_k",
-              "gemm_mfma_k<false, true, 5>"]
+              "gemm_mfma_k<false, true, 5>", "gemm_mfma_k<false, false, 6>"]
     return tuple(names)
 
 

@@ -220,11 +220,12 @@ int32_t chunk_reforward(const sbp_layer_cfg* c, const sbp_layer_weights* w, cons
   const char* xc = at(xb, r0, d, es);
   HIPCHK(rmsnorm_fwd(dt, xc, nullptr, w->g1, s.a, nullptr, s.rstd1, n, d, c->rms_eps, st));
   HIPCHK(gemm(fwd_gemm(s.a, w->wq, s.q, n, qd, d, dt, dt), st));
-  HIPCHK(rope_apply(dt, s.q, s.rope + (size_t)r0 * (c->head_dim / 2), n, c->n_q_heads, c->head_dim, false, st));
   AttnArgs aa{};
   aa.dt = dt; aa.Hq = c->n_q_heads; aa.Hkv = c->n_kv_heads; aa.dh = c->head_dim;
   aa.q_start = r0; aa.q_len = n; aa.scale = 1.0f / std::sqrt((float)c->head_dim);
   aa.q = s.q; aa.k = s.K; aa.v = s.V; aa.o = s.o; aa.lse = s.lse;
+  if (fusion_mask() & FUSE_ROPE_Q) aa.rope_q = s.rope + (size_t)r0 * (c->head_dim / 2);   // RoPE(q) inside the attention kernel, which leaves s.q rotated
+  else HIPCHK(rope_apply(dt, s.q, s.rope + (size_t)r0 * (c->head_dim / 2), n, c->n_q_heads, c->head_dim, false, st));
   HIPCHK(attn_forward(aa, st));
   HIPCHK(gemm(fwd_gemm(s.o, w->wo, s.proj, n, d, qd, dt, DT_F32), st));
   HIPCHK(rmsnorm_fwd(dt, xc, s.proj, w->g2, s.m, s.h1, s.rstd2, n, d, c->rms_eps, st));
@@ -291,8 +292,17 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       if ((rc = chunk_reforward(c, w, s, xb, r0, n, false, st))) return rc;
       const char* dyc = at(dyb, r0, d, es);
       // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
-      HIPCHK(gemm(dx_gemm(dyc, w->wdown, s.dact, n, d, F, dt, dt, false), st));
-      HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.dact, s.act, (int64_t)n * F, st));       // gate <- dgate, up <- dup, act <- silu(gate) up
+      {   // dact = dy W_d with the SwiGLU adjoint in the GEMM's epilogue: gate <- dgate, up <- dup, act <- silu(gate) up;
+          // dact itself is only materialised where the fused kernel cannot take the shape
+        GemmArgs gd = dx_gemm(dyc, w->wdown, s.dact, n, d, F, dt, dt, false);
+        if (fusion_mask() & FUSE_SWIGLU) {
+          gd.swiglu_gate = s.gate; gd.swiglu_up = s.up; gd.swiglu_act = s.act;
+          HIPCHK(gemm(gd, st));
+        } else {
+          HIPCHK(gemm(gd, st));
+          HIPCHK(swiglu_bwd(dt, s.gate, s.up, s.dact, s.act, (int64_t)n * F, st));
+        }
+      }
       {   // dm = dgate W_g + dup W_u: two operand pairs, one launch
         GemmArgs gm = dx_gemm(s.gate, w->wgate, s.dm, n, F, d, dt, DT_F32, false);
         gm.A2 = s.up; gm.B2 = w->wup;
@@ -306,8 +316,9 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       aa.q_start = r0; aa.q_len = n; aa.scale = 1.0f / std::sqrt((float)c->head_dim);
       aa.q = s.q; aa.k = s.K; aa.v = s.V; aa.o = s.o; aa.lse = s.lse;
       aa.d_o = s.d_o; aa.dq = s.dq; aa.dk = s.dK; aa.dv = s.dV; aa.delta = s.delta;
+      if (fusion_mask() & FUSE_ROPE_Q) aa.rope_q = s.rope + (size_t)r0 * half;   // dq leaves the kernel rotated back (RoPE's adjoint)
       HIPCHK(attn_backward(aa, st));
-      HIPCHK(rope_apply(dt, s.dq, s.rope + (size_t)r0 * half, n, c->n_q_heads, c->head_dim, true, st));
+      if (!(fusion_mask() & FUSE_ROPE_Q)) HIPCHK(rope_apply(dt, s.dq, s.rope + (size_t)r0 * half, n, c->n_q_heads, c->head_dim, true, st));
       HIPCHK(gemm(dx_gemm(s.dq, w->wq, s.da, n, qd, d, dt, DT_F32, false), st));
       // ---- K/V side of rows [r0, r0+n): final now
       HIPCHK(kv_grad_finish(dt, s.dK + (size_t)r0 * kd, s.dV + (size_t)r0 * kd, s.rope + (size_t)r0 * half, s.dkc, s.dvc,

@@ -171,10 +171,10 @@ __device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r >> 2) + 4 *
 // 8 waves x 32 queries; K/V tiles of 64 keys stream through two LDS stages.  The softmax denominator is taken from
 // the matrix pipe as well (one extra MFMA per k16 step against an all-ones operand sums the rounded probabilities
 // of each query), which takes 32 additions per tile off the vector ALU - the busier of the two units here.
-__global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const bf16_t* __restrict__ k,
                                                                  const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                                  float* __restrict__ lse, int Hq, int Hkv, int q_start,
-                                                                 int c, float scale) {
+                                                                 int c, float scale, const float2* __restrict__ rope) {
   __shared__ __attribute__((aligned(1024))) char sT[4][TILE64_BYTES];   // stage st: K = sT[2 st], V = sT[2 st + 1]
 
   const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
@@ -199,9 +199,28 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(const bf16_t* __re
 
   bf16x8 bq[8];
   {
-    const bf16_t* qp = q + ((int64_t)q_row * Hq + h) * DH + half * 8;
+    bf16_t* qp = q + ((int64_t)q_row * Hq + h) * DH + half * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) bq[ks] = *(const bf16x8*)(qp + ks * 16);
+    if (rope) {
+      // Rotary embedding of the query on load: the lane holds elements ks*16 + half*8 + e of its query, and the
+      // rotate-half partner of element j < 64 is j + 64, i.e. the same e of fragment ks + 4 of the same lane.  The
+      // rotated row is written back so that the backward kernels, which read q through LDS, find it rotated.
+      const float2* tr = rope + (int64_t)q_row * (DH / 2) + half * 8;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float2 cs = tr[ks * 16 + e];
+          const float x1 = (float)bq[ks][e], x2 = (float)bq[ks + 4][e];
+          bq[ks][e] = (bf16_t)(x1 * cs.x - x2 * cs.y);
+          bq[ks + 4][e] = (bf16_t)(x2 * cs.x + x1 * cs.y);
+        }
+      if (q_valid) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) *(bf16x8*)(qp + ks * 16) = bq[ks];
+      }
+    }
   }
   bf16x8 ones;
 #pragma unroll
@@ -305,7 +324,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
                                                                     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
                                                                     const float* __restrict__ lse, const float* __restrict__ delta,
                                                                     bf16_t* __restrict__ dq, int Hq, int Hkv, int q_start, int c,
-                                                                    float scale) {
+                                                                    float scale, const float2* __restrict__ rope) {
   __shared__ __attribute__((aligned(1024))) char sT[4][TILE64_BYTES];   // stage st: K = sT[2 st], V = sT[2 st + 1]
 
   const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
@@ -392,15 +411,36 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
 
   if (q_valid) {
     bf16_t* op = dq + ((int64_t)my_q * Hq + h) * DH;
+    if (rope) {
+      // adjoint of the rotary embedding on the way out: element j < 64 (accumulator block i < 2) pairs with j + 64
+      // (block i + 2, same register of the same lane); rotation by the negative angle
+      const float2* tr = rope + (int64_t)my_q * (DH / 2) + 4 * half;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        bf16x4 w;
+        for (int a = 0; a < 4; ++a) {
+          bf16x4 w1, w2;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(acc[i][4 * a + e] * scale);
-        *(bf16x4*)(op + i * 32 + 8 * a + 4 * half) = w;
-      }
+          for (int e = 0; e < 4; ++e) {
+            const float2 cs = tr[i * 32 + 8 * a + e];
+            const float d1 = acc[i][4 * a + e] * scale, d2 = acc[i + 2][4 * a + e] * scale;
+            w1[e] = (bf16_t)(d1 * cs.x + d2 * cs.y);
+            w2[e] = (bf16_t)(d2 * cs.x - d1 * cs.y);
+          }
+          *(bf16x4*)(op + i * 32 + 8 * a + 4 * half) = w1;
+          *(bf16x4*)(op + (i + 2) * 32 + 8 * a + 4 * half) = w2;
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          bf16x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(acc[i][4 * a + e] * scale);
+          *(bf16x4*)(op + i * 32 + 8 * a + 4 * half) = w;
+        }
+    }
   }
 }
 
@@ -630,32 +670,29 @@ bool attn_mfma_eligible(int dt, int dh, int Hq, int Hkv) { return dt == DT_BF16 
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-hipError_t attn_forward_generic(const AttnArgs& a, hipStream_t st);
-hipError_t attn_backward_generic(const AttnArgs& a, hipStream_t st);
+// the MFMA kernels move 16 bytes per lane: every tensor they touch must be 16-byte aligned
+bool attn_mfma_aligned(const AttnArgs& a, bool backward) {
+  if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o) || ((uintptr_t)a.rope_q & 7)) return false;
+  return !backward || (aligned16(a.d_o) && aligned16(a.dq) && aligned16(a.dk) && aligned16(a.dv));
+}
 
 hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st) {
   if (a.q_len == 0) return hipSuccess;
-  if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o)) { note_generic_bf16_launch(); return attn_forward_generic(a, st); }
   dim3 grid((unsigned)cdiv(a.q_len, TQ), a.Hq);
-  attn_fwd_mfma_k<<<grid, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (bf16_t*)a.o, a.lse,
-                                               a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
+  attn_fwd_mfma_k<<<grid, AT_THREADS, 0, st>>>((bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (bf16_t*)a.o, a.lse,
+                                               a.Hq, a.Hkv, a.q_start, a.q_len, a.scale, a.rope_q);
   return hipGetLastError();
 }
 
 hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st) {
   if (a.q_len == 0) return hipSuccess;
-  if (!aligned16(a.q) || !aligned16(a.k) || !aligned16(a.v) || !aligned16(a.o) || !aligned16(a.d_o) || !aligned16(a.dq) ||
-      !aligned16(a.dk) || !aligned16(a.dv)) {
-    note_generic_bf16_launch();
-    return attn_backward_generic(a, st);
-  }
   const int64_t pairs = (int64_t)a.q_len * a.Hq;
   float* lse2 = a.delta + pairs;   // second half of the [2, Hq, c] scratch
   attn_delta_mfma_k<<<(unsigned)cdiv(pairs, 4), 256, 0, st>>>((const bf16_t*)a.o, (const bf16_t*)a.d_o, a.lse, a.delta, lse2, a.Hq,
                                                               a.q_len);
   dim3 gq((unsigned)cdiv(a.q_len, TQ), a.Hq);
   attn_bwd_dq_mfma_k<<<gq, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
-                                                a.lse, a.delta, (bf16_t*)a.dq, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
+                                                a.lse, a.delta, (bf16_t*)a.dq, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale, a.rope_q);
   dim3 gk((unsigned)cdiv(a.q_start + a.q_len, KV_TILE), a.Hkv);
   attn_bwd_dkv_mfma_k<<<gk, KV_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
                                                  lse2, a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);

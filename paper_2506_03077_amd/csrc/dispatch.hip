@@ -13,6 +13,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st);
 bool gemm_mfma_eligible(const GemmArgs& g);
 bool gemm_mfma_pair_ok(const GemmArgs& g);
 bool gemm_mfma_stats_ok(const GemmArgs& g);
+bool gemm_mfma_swiglu_ok(const GemmArgs& g);
 bool gemm_mfma_group_eligible(const GemmArgs* gs, int n);
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n);
@@ -22,6 +23,7 @@ hipError_t attn_backward_generic(const AttnArgs& a, hipStream_t st);
 hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st);
 hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st);
 bool attn_mfma_eligible(int dt, int dh, int Hq, int Hkv);
+bool attn_mfma_aligned(const AttnArgs& a, bool backward);
 
 static std::atomic<bool> g_force_generic_gemm{false};
 static std::atomic<bool> g_force_generic_attn{false};
@@ -29,6 +31,9 @@ static std::atomic<bool> g_force_generic_attn{false};
 static std::atomic<long long> g_generic_bf16_launches{0};
 long long generic_bf16_launches() { return g_generic_bf16_launches.load(); }
 void note_generic_bf16_launch() { ++g_generic_bf16_launches; }
+static std::atomic<int> g_fusion_mask{FUSE_ROPE_Q};
+int fusion_mask() { return g_fusion_mask.load(); }
+void set_fusion_mask(int mask) { g_fusion_mask.store(mask); }
 
 void gemm_set_force_generic(bool on) { g_force_generic_gemm = on; }
 void attn_set_force_generic(bool on) { g_force_generic_attn = on; }
@@ -63,6 +68,12 @@ static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs 
 
 hipError_t gemm(const GemmArgs& g, hipStream_t st) {
   if (g.row_stats && !gemm_row_stats_supported(g)) return hipErrorInvalidValue;   // only the MFMA store form emits them
+  if (g.swiglu_gate && !(gemm_uses_mfma(g) && gemm_mfma_swiglu_ok(g))) {   // no fused epilogue for this problem: product, then the elementwise kernel
+    GemmArgs plain = g;
+    plain.swiglu_gate = plain.swiglu_up = plain.swiglu_act = nullptr;
+    hipError_t e = gemm(plain, st);
+    return e != hipSuccess ? e : swiglu_bwd(g.out_dt, g.swiglu_gate, g.swiglu_up, g.C, g.swiglu_act, (int64_t)g.M * g.N, st);
+  }
   if (g.A2 && !(gemm_uses_mfma(g) && gemm_mfma_pair_ok(g))) {   // two operand pairs, no single launch for them: one after the other
     GemmArgs first = g, second = g;
     first.A2 = first.B2 = nullptr;
@@ -88,18 +99,31 @@ hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st) {
 }
 hipError_t attn_forward(const AttnArgs& a, hipStream_t st) {
   prof::Scope sc(prof::ATTN_FWD, 4.0 * a.dh * causal_pairs(a), false, st);
-  if (attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv)) return attn_forward_mfma(a, st);
+  if (attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) && attn_mfma_aligned(a, false)) return attn_forward_mfma(a, st);
   if (a.dt == DT_BF16) ++g_generic_bf16_launches;
-  return attn_forward_generic(a, st);
+  AttnArgs b = a;
+  b.rope_q = nullptr;            // the shape-agnostic kernels take rotated queries: rotate in place first
+  if (a.rope_q) {
+    hipError_t e = rope_apply(a.dt, (void*)a.q, a.rope_q, a.q_len, a.Hq, a.dh, false, st);
+    if (e != hipSuccess) return e;
+  }
+  return attn_forward_generic(b, st);
 }
 hipError_t attn_backward(const AttnArgs& a, hipStream_t st) {
   prof::Scope sc(prof::ATTN_BWD, 10.0 * a.dh * causal_pairs(a), false, st);
-  if (attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv)) return attn_backward_mfma(a, st);
+  if (attn_uses_mfma(a.dt, a.dh, a.Hq, a.Hkv) && attn_mfma_aligned(a, true)) return attn_backward_mfma(a, st);
   if (a.dt == DT_BF16) ++g_generic_bf16_launches;
-  return attn_backward_generic(a, st);
+  AttnArgs b = a;
+  b.rope_q = nullptr;
+  hipError_t e = attn_backward_generic(b, st);
+  if (e != hipSuccess || !a.rope_q) return e;
+  return rope_apply(a.dt, a.dq, a.rope_q, a.q_len, a.Hq, a.dh, true, st);   // dq back through the rotation
 }
 
 }  // namespace sbp
+
+extern "C" void streambp_debug_set_fusions(int mask) { sbp::set_fusion_mask(mask); }
+extern "C" int streambp_debug_get_fusions(void) { return sbp::fusion_mask(); }
 
 extern "C" void streambp_debug_force_generic(int gemm_on, int attn_on) {
   sbp::gemm_set_force_generic(gemm_on != 0);

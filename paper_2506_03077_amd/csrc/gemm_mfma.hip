@@ -147,7 +147,10 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int n_tiles) {
 // MODE: 0 = store fp32, 1 = store bf16, 2 = accumulate fp32 (C +=), 3 = split-K partial (fp32 store, C already offset),
 //       4 = accumulate into a bf16 C (read, add in fp32, round once; weight-gradient form only),
 //       5 = store fp32 and emit per-row (max, sum of exp) pairs over the tile's columns (`stats`)
+//       6 = C is not stored: the tile is the gradient wrt act = silu(gate) * up and the epilogue writes act, d gate, d up
 constexpr bool mode_accumulates(int mode) { return mode == 2 || mode == 4; }
+constexpr bool mode_swaps_operands(int mode) { return mode == 5 || mode == 6; }   // accumulators hold C^T blocks
+struct SwigluFuse { bf16_t* gate; bf16_t* up; bf16_t* act; };
 //
 // The main loop is written so that it contains no vector ALU instructions at all: global addresses are an SGPR base
 // (advanced with scalar adds) plus per-lane offsets computed once, LDS fragment addresses are computed once per
@@ -168,7 +171,7 @@ struct KSegments {
 template <bool TA, bool TB, int MODE>
 __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restrict__ Cv, int M, int N, int64_t lda,
                                           int64_t ldb, int64_t ldc, int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES],
-                                          float2* __restrict__ stats = nullptr) {
+                                          float2* __restrict__ stats = nullptr, SwigluFuse sw = SwigluFuse{nullptr, nullptr, nullptr}) {
   static_assert(NSTAGE == 2, "the main loop is unrolled over two LDS stages");
   constexpr bool AMN = TA, BMN = !TB;     // operand kept reduction-major in LDS (B stored [N,K] is the K-contiguous case)
   const int m0 = tm * BM, n0 = tn * BN;
@@ -246,7 +249,7 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = MODE == 5 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[cur][j], a[cur][i], acc[i][j], 0, 0, 0)   // C^T blocks
+          acc[i][j] = mode_swaps_operands(MODE) ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[cur][j], a[cur][i], acc[i][j], 0, 0, 0)   // C^T blocks
                                 : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -395,6 +398,46 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
     }
     return;
   }
+  if constexpr (MODE == 6) {
+    // SwiGLU adjoint on the accumulators (Sec. 5 names fused backward operators as the way to cut the per-chunk HBM
+    // passes): the products were formed with the operands swapped, so a lane owns one row of the tile and, per column
+    // block j and register quad q, four consecutive columns - 8-byte accesses to gate / up / act.  Every element has
+    // exactly one owner, so gate and up are rewritten in place.
+    typedef bf16_t bf16x4e __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row_l = wm0 + i * 32 + (lane & 31);
+      if (m0 + row_l >= M) continue;
+      const int64_t base = (int64_t)(m0 + row_l) * ldc + n0 + wn0 + 4 * (lane >> 5);
+      bf16x4e gv[FN][4], uv[FN][4];
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          gv[j][q] = *(const bf16x4e*)(sw.gate + base + j * 32 + 8 * q);
+          uv[j][q] = *(const bf16x4e*)(sw.up + base + j * 32 + 8 * q);
+        }
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          bf16x4e a4, dg4, du4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float z = (float)gv[j][q][e], u = (float)uv[j][q][e], d = acc[i][j][4 * q + e];
+            const float sg = 1.0f / (1.0f + __expf(-z));
+            a4[e] = (bf16_t)(z * sg * u);
+            dg4[e] = (bf16_t)(d * u * sg * (1.0f + z * (1.0f - sg)));
+            du4[e] = (bf16_t)(d * z * sg);
+          }
+          const int64_t idx = base + j * 32 + 8 * q;
+          if (sw.act) *(bf16x4e*)(sw.act + idx) = a4;
+          *(bf16x4e*)(sw.gate + idx) = dg4;
+          *(bf16x4e*)(sw.up + idx) = du4;
+        }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -420,7 +463,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
                                                         int64_t ldb, int64_t ldc, int k_per_split,
                                                         const int* __restrict__ rows_dev, int xcds_per_split,
                                                         const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2,
-                                                        float2* __restrict__ row_stats) {
+                                                        float2* __restrict__ row_stats, SwigluFuse sw) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
   const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN, n_tiles = tiles_m * tiles_n;
   int tm, tn, split = 0;
@@ -455,7 +498,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
   if (k_end <= k_begin && mode_accumulates(MODE)) return;   // nothing to add
   KSegments segs;
   segs.n = 1; segs.A[0] = A; segs.B[0] = B; segs.K[0] = K; segs.k_begin[0] = k_begin; segs.k_end[0] = k_end;
-  gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem, row_stats);
+  gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem, row_stats, sw);
 }
 
 // Weight-gradient form with a segmented reduction: C += sum_s A_s^T B_s, every segment with its own run-time row
@@ -561,6 +604,12 @@ bool gemm_mfma_pair_ok(const GemmArgs& g) {
          !((uintptr_t)g.A2 & 15) && !((uintptr_t)g.B2 & 15);
 }
 
+// the fused SwiGLU adjoint exists for the store form C = A B (input-gradient layout), bf16 tensors that share C's layout
+bool gemm_mfma_swiglu_ok(const GemmArgs& g) {
+  return g.swiglu_gate && g.swiglu_up && !g.ta && !g.tb && !g.acc && !g.A2 && !g.row_stats && g.ldc % 4 == 0 &&
+         !((uintptr_t)g.swiglu_gate & 7) && !((uintptr_t)g.swiglu_up & 7) && !((uintptr_t)g.swiglu_act & 7);
+}
+
 // the row-statistics epilogue exists for the fp32 store form of C = A B^T
 bool gemm_mfma_stats_ok(const GemmArgs& g) {
   return !g.ta && g.tb && g.out_dt == DT_F32 && !g.acc && !g.A2 && !((uintptr_t)g.row_stats & 7);
@@ -587,7 +636,7 @@ size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits) {
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const int tiles_m = (int)cdiv(g.M, BM), tiles_n = g.N / BN;
   int splits = gemm_mfma_splits(g);
-  if (g.scratch == nullptr || g.ldc != g.N || g.row_stats) splits = 1;
+  if (g.scratch == nullptr || g.ldc != g.N || g.row_stats || g.swiglu_gate) splits = 1;
   while (splits > 1 && g.scratch_bytes < (size_t)splits * g.M * g.ldc * sizeof(float)) splits /= 2;   // what the scratch holds
   int k_per_split = g.K;
   int xcds_per_split = 0;
@@ -604,7 +653,8 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   const bf16_t* B = (const bf16_t*)g.B;
 #define LAUNCH(TA, TB, MODE, CPTR) \
   gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split, g.rows_dev, \
-                                                       xcds_per_split, (const bf16_t*)g.A2, (const bf16_t*)g.B2, g.row_stats)
+                                                       xcds_per_split, (const bf16_t*)g.A2, (const bf16_t*)g.B2, g.row_stats, \
+                                                       SwigluFuse{(bf16_t*)g.swiglu_gate, (bf16_t*)g.swiglu_up, (bf16_t*)g.swiglu_act})
 #define LAUNCH_LAYOUT(MODE, CPTR)                       \
   do {                                                  \
     if (!g.ta && g.tb) LAUNCH(false, true, MODE, CPTR); \
@@ -613,7 +663,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   } while (0)
   const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
   const int mode = splits > 1 ? 3 : (g.acc ? 2 : (g.out_dt == DT_BF16 ? 1 : 0));   // (both accumulate forms are timed as one kind)
-  const int kind = g.row_stats ? (int)prof::GEMM_STATS : prof::GEMM_SINGLE + layout * 4 + mode;
+  const int kind = g.row_stats ? (int)prof::GEMM_STATS : g.swiglu_gate ? (int)prof::GEMM_SWIGLU : prof::GEMM_SINGLE + layout * 4 + mode;
   const double work = 2.0 * g.M * g.N * g.K * (g.A2 ? 2 : 1);
   if (splits > 1) {
     {
@@ -632,6 +682,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   }
   prof::Scope sc(kind, work, g.rows_dev != nullptr, st);
   if (g.row_stats) LAUNCH(false, true, 5, g.C);
+  else if (g.swiglu_gate) LAUNCH(false, false, 6, g.C);
   else if (g.out_dt == DT_BF16 && g.acc) LAUNCH(true, false, 4, g.C);
   else if (g.out_dt == DT_BF16) LAUNCH_LAYOUT(1, g.C);
   else if (g.acc) LAUNCH_LAYOUT(2, g.C);

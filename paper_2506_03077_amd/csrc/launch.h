@@ -31,6 +31,14 @@ struct GemmArgs {
   // gemm_row_stats_supported first): row_stats[m * (N / GEMM_STAT_COLS) + t] = (max, sum of exp(c - max)) of row m
   // over the columns [t * GEMM_STAT_COLS, (t + 1) * GEMM_STAT_COLS), taken from the fp32 accumulators.
   float2* row_stats = nullptr;
+  // Optional fused SwiGLU adjoint (store form C = A B with the same row-major [M, N] layout and leading dimension for
+  // C, gate, up and act; bf16): the product is the gradient wrt act = silu(gate) * up and is never stored; instead the
+  // epilogue reads the tile's gate and up values and writes act (what the forward would have produced; optional),
+  // gate <- d gate and up <- d up in place.  Where the MFMA kernel cannot take the problem the dispatcher runs the
+  // plain product into C followed by the elementwise kernel - same results up to the rounding of the product to bf16.
+  void* swiglu_gate = nullptr;
+  void* swiglu_up = nullptr;
+  void* swiglu_act = nullptr;
 };
 constexpr int GEMM_STAT_COLS = 256;
 bool gemm_row_stats_supported(const GemmArgs& g);
@@ -43,6 +51,11 @@ hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_uses_mfma(const GemmArgs& g);
 // force the generic kernel (debug / A-B tests)
 void gemm_set_force_generic(bool on);
+// which of the optional fusions the entry points use (A/B measurements): bit 0 = SwiGLU adjoint in the epilogue of the
+// dact GEMM, bit 1 = rotary embedding of q / its adjoint on dq inside the attention kernels
+enum { FUSE_SWIGLU = 1, FUSE_ROPE_Q = 2 };
+int fusion_mask();
+void set_fusion_mask(int mask);
 // bf16 problems that have run on the shape-agnostic kernels since the library was loaded
 long long generic_bf16_launches();
 void note_generic_bf16_launch();
@@ -51,8 +64,8 @@ void note_generic_bf16_launch();
 namespace prof {
 // kinds 0..11: gemm_mfma_k<layout, mode> with layout NT=0, NN=1, TN=2 and mode 0..3; 12..23: the grouped kernel;
 // then the shape-agnostic GEMM, the attention forward / backward launch sequences, the segmented weight-gradient GEMM and the
-// store form with row statistics (gemm_mfma_k<NT, 5>)
-enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, GEMM_SEG = 27, GEMM_STATS = 28, N_KIND = 29 };
+// store form with row statistics (gemm_mfma_k<NT, 5>) and the input-gradient form with the fused SwiGLU adjoint (gemm_mfma_k<NN, 6>)
+enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, GEMM_SEG = 27, GEMM_STATS = 28, GEMM_SWIGLU = 29, N_KIND = 30 };
 struct Scope {
   hipStream_t st; bool active = false; int kind = 0; double work = 0; bool bounded = false; hipEvent_t e0{}, e1{};
   // bounded: `work` was computed from a host-side upper bound of a run-time row count
@@ -105,6 +118,11 @@ struct AttnArgs {
   void* o; float* lse;     // o [c,Hq,dh]; lse [Hq,c]
   const void* d_o; void* dq; float *dk, *dv;
   float* delta;            // [2,Hq,c] scratch (backward): delta, then the log2-domain log-sum-exp
+  // Optional rotary embedding of the chunk's queries folded into the attention kernels: cos/sin rows [c, dh/2] of the
+  // chunk's positions.  Forward: q arrives un-rotated, is rotated on load and written back rotated (q must then be
+  // writable); backward: q is the rotated tensor the forward left, and dq leaves the kernel already rotated back
+  // (the adjoint rotation), i.e. as the gradient wrt the un-rotated projection.
+  const float2* rope_q = nullptr;
 };
 hipError_t attn_forward(const AttnArgs& a, hipStream_t st);
 hipError_t attn_backward(const AttnArgs& a, hipStream_t st);

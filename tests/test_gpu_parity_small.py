@@ -87,6 +87,26 @@ def test_layer_backward_bf16_weight_gradients(cfg, T, chunk, batch):
     run_layer_case(cfg, T, chunk, batch=batch, grad_dtype="bf16")
 
 
+@pytest.mark.parametrize("mask", [0, 1, 2, 3])
+def test_optional_fusions_agree_with_the_oracle(mask):
+    # bit 0: SwiGLU adjoint in the epilogue of the dact GEMM; bit 1: RoPE of q and its adjoint on dq inside the attention
+    # kernels.  Every combination against the oracle, on the MFMA kernels (ragged rows, two sequences) and, for the
+    # RoPE fold, on the shape-agnostic ones (where the dispatcher rotates around the kernels).
+    old = sb.debug_set_fusions(mask)
+    try:
+        run_layer_case(BIG16, 700, 256, batch=2, seed=6)
+        run_layer_case(ODD16, 150, 64, batch=2, seed=6)
+        run_layer_case(TINY, 96, 40, seed=6, pos_offset=5)
+        for cfg, T, chunk in ((MID16, 333, 128),):
+            inp = synth.layer_inputs(cfg, seed=2, seq_len=T)
+            y_ref, _ = o_layer.layer_forward(inp["x"][0], inp["w"], oracle_cfg(cfg))
+            w = {k: dev(v, "bf16") for k, v in inp["w"].items()}
+            y = sb.streambp_layer_forward(lib_layer_cfg(cfg, T, chunk), w, dev(inp["x"], "bf16"))
+            assert_close(host(y)[0], y_ref, 1e-2, "y")
+    finally:
+        sb.debug_set_fusions(old)
+
+
 def test_layer_backward_mid_fp32():
     run_layer_case(MID32, 320, 128)
 
