@@ -16,6 +16,11 @@ out of the presentation only).  The readings taken here:
     and k before K is cached, scores scaled by 1/sqrt(head_dim), sigma := SiLU.
   * weights are stored [out, in]; y = x W^T.
 
+  * the mask M is causal by default; cfg may add the two further rules of
+    oracle/attn.py: "window" (sliding window, 0 = off) and "first_valid"
+    (positions before it are padding in front of the sequence: never visible
+    as keys; as queries they see nothing, so their attention output is zero).
+
 Shapes: x [T, d]; wq [Hq*dh, d]; wk, wv [Hkv*dh, d]; wo [d, Hq*dh];
 wgate, wup [F, d]; wdown [d, F]; g1, g2 [d].
 """
@@ -98,16 +103,23 @@ def layer_forward(x, w, cfg):
     v = (a @ W["wv"].T).reshape(T, Hkv, dh)
 
     scale = 1.0 / np.sqrt(dh)
-    future = np.triu(np.ones((T, T), dtype=bool), k=1)   # key index > query index
+    idx = np.arange(T)
+    hidden = idx[None, :] > idx[:, None]                 # key index > query index
+    window, first = cfg.get("window", 0), cfg.get("first_valid", 0)
+    if window > 0:
+        hidden |= idx[None, :] <= idx[:, None] - window  # older than the last `window` positions
+    if first > 0:
+        hidden |= idx[None, :] < first                   # padding in front of the sequence
+    empty = hidden.all(axis=1, keepdims=True)            # queries that see no key (the padding rows themselves)
     P = np.empty((Hq, T, T), F64)
     o = np.empty((T, Hq, dh), F64)
     for h in range(Hq):
         kv = h // grp
         S = (q[:, h, :] @ k[:, kv, :].T) * scale
-        S[future] = -np.inf
-        S = S - S.max(axis=1, keepdims=True)
+        S[hidden] = -np.inf
+        S = S - np.where(empty, 0.0, S.max(axis=1, keepdims=True))
         E = np.exp(S)
-        P[h] = E / E.sum(axis=1, keepdims=True)
+        P[h] = E / np.where(empty, 1.0, E.sum(axis=1, keepdims=True))
         o[:, h, :] = P[h] @ v[:, kv, :]
 
     o2 = o.reshape(T, Hq * dh)
@@ -172,16 +184,18 @@ def layer_backward(cache, dy):
     return dx, g
 
 
-def layer_forward_backward(x, w, cfg, dy):
+def layer_forward_backward(x, w, cfg, dy, first_valid=None):
     """Convenience: batch of sequences x [B, T, d], dy [B, T, d]; weight
-    gradients are summed over the batch (independent sequences)."""
+    gradients are summed over the batch (independent sequences).  first_valid:
+    optional per-sequence count of padding positions in front."""
     x = np.asarray(x, F64)
     dy = np.asarray(dy, F64)
     if x.ndim == 2:
         x, dy = x[None], dy[None]
     ys, dxs, gsum = [], [], None
     for b in range(x.shape[0]):
-        y, cache = layer_forward(x[b], w, cfg)
+        cfg_b = cfg if first_valid is None else dict(cfg, first_valid=int(first_valid[b]))
+        y, cache = layer_forward(x[b], w, cfg_b)
         dx, g = layer_backward(cache, dy[b])
         ys.append(y)
         dxs.append(dx)
