@@ -87,6 +87,15 @@ typedef struct {
                            chunks.  0 = default (8192).  More rows: fewer passes
                            over every dW, more workspace (one more copy of a
                            chunk's ten GEMM operand buffers per chunk of the group) */
+  int32_t window;       /* attention mask (Sec. 3.2.2 allows a general mask M, "padding /
+                           sliding window"): 0 = plain causal; > 0 = the token at row t
+                           attends to rows t - window < u <= t only                 */
+  const int32_t *seq_first; /* HOST array [batch] or NULL: rows of sequence b before
+                           seq_first[b] are padding in front of the sequence - never
+                           attended to; as queries they attend to nothing, so their
+                           attention output is zero (the rest of the layer still maps
+                           them row by row).  0 <= seq_first[b] <= seq_len.  Read
+                           before the call returns.                                  */
 } sbp_layer_cfg;
 
 /* wq [Hq*dh, d]; wk, wv [Hkv*dh, d]; wo [d, Hq*dh]; wgate, wup [F, d];
@@ -194,6 +203,11 @@ typedef struct {
   int32_t q_start;               /* s: global position of the chunk's row 0   */
   int32_t q_len;                 /* c                                         */
   float scale;                   /* usually 1/sqrt(head_dim); must be positive and finite */
+  int32_t window;                /* 0 = plain causal; > 0 = the query at position p sees
+                                    keys p - window < u <= p only (sliding window)   */
+  int32_t kv_first;              /* key positions before this one are padding in front of
+                                    the sequence: never visible.  A query that sees no key
+                                    gets o = 0, lse = -inf and no gradient             */
 } sbp_attn_cfg;
 
 size_t streambp_attn_workspace_bytes(const sbp_attn_cfg *cfg);

@@ -28,7 +28,8 @@ class LayerCfg(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
                 ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("mlp_width", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("pos_offset", C.c_int32),
-                ("grad_dtype", C.c_int32), ("dw_group_rows", C.c_int32)]
+                ("grad_dtype", C.c_int32), ("dw_group_rows", C.c_int32), ("window", C.c_int32),
+                ("seq_first", C.POINTER(C.c_int32))]
 
 
 class LayerWeights(C.Structure):
@@ -47,7 +48,8 @@ class HeadCfg(C.Structure):
 
 class AttnCfg(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
-                ("q_start", C.c_int32), ("q_len", C.c_int32), ("scale", C.c_float)]
+                ("q_start", C.c_int32), ("q_len", C.c_int32), ("scale", C.c_float), ("window", C.c_int32),
+                ("kv_first", C.c_int32)]
 
 
 class StackCfg(C.Structure):
@@ -177,9 +179,15 @@ def streambp_version():
 
 
 def layer_cfg(dtype, batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
-              rms_eps=1e-6, rope_theta=1e4, pos_offset=0, grad_dtype=SBP_F32, dw_group_rows=0):
-    return LayerCfg(int(dtype), batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
-                    rms_eps, rope_theta, pos_offset, int(grad_dtype), int(dw_group_rows))
+              rms_eps=1e-6, rope_theta=1e4, pos_offset=0, grad_dtype=SBP_F32, dw_group_rows=0, window=0, seq_first=None):
+    """seq_first: optional list of `batch` ints (rows of padding in front of every sequence); held by the returned struct."""
+    cfg = LayerCfg(int(dtype), batch, seq_len, chunk, hidden, n_q_heads, n_kv_heads, head_dim, mlp_width,
+                   rms_eps, rope_theta, pos_offset, int(grad_dtype), int(dw_group_rows), int(window), None)
+    if seq_first is not None:
+        assert len(seq_first) == batch
+        cfg._seq_first = (C.c_int32 * batch)(*[int(v) for v in seq_first])     # kept alive with the struct
+        cfg.seq_first = C.cast(cfg._seq_first, C.POINTER(C.c_int32))
+    return cfg
 
 
 def streambp_layer_workspace_bytes(cfg: LayerCfg) -> int:
@@ -266,8 +274,8 @@ def streambp_lmhead_ce_backward(cfg: HeadCfg, w, h, targets, old_logp=None, ref_
     return dh, dw, loss, n_active
 
 
-def attn_cfg(dtype, n_q_heads, n_kv_heads, head_dim, q_start, q_len, scale):
-    return AttnCfg(int(dtype), n_q_heads, n_kv_heads, head_dim, q_start, q_len, scale)
+def attn_cfg(dtype, n_q_heads, n_kv_heads, head_dim, q_start, q_len, scale, window=0, kv_first=0):
+    return AttnCfg(int(dtype), n_q_heads, n_kv_heads, head_dim, q_start, q_len, scale, int(window), int(kv_first))
 
 
 def streambp_attn_workspace_bytes(cfg: AttnCfg) -> int:
@@ -448,7 +456,9 @@ def debug_profile_end():
 
 def stack_cfg(layer: LayerCfg, n_layers, vocab, head_chunk, objective=SBP_OBJ_SFT, loss_scale=1.0, clip_eps=0.2,
               kl_beta=0.04, kl_mode=0, final_eps=1e-6):
-    return StackCfg(layer, n_layers, vocab, head_chunk, objective, loss_scale, clip_eps, kl_beta, kl_mode, final_eps)
+    sc = StackCfg(layer, n_layers, vocab, head_chunk, objective, loss_scale, clip_eps, kl_beta, kl_mode, final_eps)
+    sc._layer = layer            # the copy shares layer.seq_first: keep the array's owner alive
+    return sc
 
 
 def streambp_stack_workspace_bytes(cfg: StackCfg) -> int:

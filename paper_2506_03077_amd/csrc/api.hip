@@ -99,6 +99,11 @@ int32_t check_layer_cfg(const sbp_layer_cfg* c) {
   if (c->head_dim < 2 || (c->head_dim & 1) || c->head_dim > 256)
     return fail(SBP_ERR_SHAPE, "head_dim must be even and in [2, 256]");
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(SBP_ERR_SHAPE, "rms_eps must be >= 0 and rope_theta > 0");
+  if (c->window < 0) return fail(SBP_ERR_SHAPE, "window must be >= 0");
+  if (c->seq_first)
+    for (int b = 0; b < c->batch; ++b)
+      if (c->seq_first[b] < 0 || c->seq_first[b] > c->seq_len)
+        return fail(SBP_ERR_SHAPE, "seq_first[%d] = %d is outside [0, seq_len]", b, c->seq_first[b]);
   return SBP_OK;
 }
 
@@ -213,7 +218,7 @@ int32_t kv_prepass(const sbp_layer_cfg* c, const sbp_layer_weights* w, const Lay
 // Partitioned reforward of rows [r0, r0+n): fills a, q, o, lse, h1, m, gate, up, act.
 // with_act = false leaves s.act unwritten: the backward gets it from swiglu_bwd, which reads gate and up anyway
 int32_t chunk_reforward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const LayerWs& s, const char* xb,
-                        int r0, int n, bool with_act, hipStream_t st) {
+                        int r0, int n, int kv_first, bool with_act, hipStream_t st) {
   const int dt = c->dtype;
   const size_t es = dtype_size(dt);
   const int d = c->hidden, F = c->mlp_width, qd = c->n_q_heads * c->head_dim;
@@ -223,6 +228,7 @@ int32_t chunk_reforward(const sbp_layer_cfg* c, const sbp_layer_weights* w, cons
   AttnArgs aa{};
   aa.dt = dt; aa.Hq = c->n_q_heads; aa.Hkv = c->n_kv_heads; aa.dh = c->head_dim;
   aa.q_start = r0; aa.q_len = n; aa.scale = 1.0f / std::sqrt((float)c->head_dim);
+  aa.window = c->window; aa.kv_first = kv_first;
   aa.q = s.q; aa.k = s.K; aa.v = s.V; aa.o = s.o; aa.lse = s.lse;
   if (fusion_mask() & FUSE_ROPE_Q) aa.rope_q = s.rope + (size_t)r0 * (c->head_dim / 2);   // RoPE(q) inside the attention kernel, which leaves s.q rotated
   else HIPCHK(rope_apply(dt, s.q, s.rope + (size_t)r0 * (c->head_dim / 2), n, c->n_q_heads, c->head_dim, false, st));
@@ -277,6 +283,7 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
     const char* xb = at(x, (size_t)b * T, d, es);
     const char* dyb = at(dy, (size_t)b * T, d, es);
     char* dxb = at(dx, (size_t)b * T, d, es);
+    const int kv_first = c->seq_first ? c->seq_first[b] : 0;      // rows before it are padding in front of the sequence
     if ((rc = kv_prepass(c, w, s_all, xb, st))) return rc;
     HIPCHK(fill_zero(s_all.dK, (size_t)T * kd * sizeof(float), st));
     HIPCHK(fill_zero(s_all.dV, (size_t)T * kd * sizeof(float), st));
@@ -289,7 +296,7 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
     for (int ci = n_chunks - 1; ci >= 0; --ci) {
       const int r0 = ci * cm, n = std::min(cm, T - r0);
       const LayerWs s = chunk_view(s_all, ci % s_all.dw_group);
-      if ((rc = chunk_reforward(c, w, s, xb, r0, n, false, st))) return rc;
+      if ((rc = chunk_reforward(c, w, s, xb, r0, n, kv_first, false, st))) return rc;
       const char* dyc = at(dyb, r0, d, es);
       // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
       {   // dact = dy W_d with the SwiGLU adjoint in the GEMM's epilogue: gate <- dgate, up <- dup, act <- silu(gate) up;
@@ -314,6 +321,7 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       AttnArgs aa{};
       aa.dt = dt; aa.Hq = c->n_q_heads; aa.Hkv = c->n_kv_heads; aa.dh = c->head_dim;
       aa.q_start = r0; aa.q_len = n; aa.scale = 1.0f / std::sqrt((float)c->head_dim);
+      aa.window = c->window; aa.kv_first = kv_first;
       aa.q = s.q; aa.k = s.K; aa.v = s.V; aa.o = s.o; aa.lse = s.lse;
       aa.d_o = s.d_o; aa.dq = s.dq; aa.dk = s.dK; aa.dv = s.dV; aa.delta = s.delta;
       if (fusion_mask() & FUSE_ROPE_Q) aa.rope_q = s.rope + (size_t)r0 * half;   // dq leaves the kernel rotated back (RoPE's adjoint)
@@ -366,10 +374,11 @@ int32_t streambp_layer_forward(const sbp_layer_cfg* c, const sbp_layer_weights* 
   for (int b = 0; b < c->batch; ++b) {
     const char* xb = at(x, (size_t)b * T, d, es);
     char* yb = at(y, (size_t)b * T, d, es);
+    const int kv_first = c->seq_first ? c->seq_first[b] : 0;
     if ((rc = kv_prepass(c, w, s, xb, st))) return rc;
     for (int r0 = 0; r0 < T; r0 += cm) {
       const int n = std::min(cm, T - r0);
-      if ((rc = chunk_reforward(c, w, s, xb, r0, n, true, st))) return rc;
+      if ((rc = chunk_reforward(c, w, s, xb, r0, n, kv_first, true, st))) return rc;
       HIPCHK(gemm(fwd_gemm(s.act, w->wdown, s.proj, n, d, F, dt, DT_F32), st));
       HIPCHK(add_store(dt, s.h1, s.proj, at(yb, r0, d, es), (int64_t)n * d, st));
     }
@@ -512,6 +521,7 @@ static int32_t check_attn_cfg(const sbp_attn_cfg* c) {
   if ((int64_t)c->q_start + c->q_len > INT32_MAX) return fail(SBP_ERR_SHAPE, "q_start + q_len overflows");
   // the kernels take row maxima of the raw scores before scaling them, which is only right for a positive finite scale
   if (!(c->scale > 0.f) || !std::isfinite(c->scale)) return fail(SBP_ERR_SHAPE, "scale must be positive and finite");
+  if (c->window < 0 || c->kv_first < 0) return fail(SBP_ERR_SHAPE, "window and kv_first must be >= 0");
   return SBP_OK;
 }
 
@@ -528,7 +538,7 @@ int32_t streambp_attn_chunk_forward(const sbp_attn_cfg* c, const void* q, const 
   if (!q || !k || !v || !o || !lse) return fail(SBP_ERR_NULL, "q, k, v, o and lse must be non-NULL");
   AttnArgs a{};
   a.dt = c->dtype; a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads; a.dh = c->head_dim;
-  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale;
+  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale; a.window = c->window; a.kv_first = c->kv_first;
   a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
   HIPCHK(attn_forward(a, (hipStream_t)hip_stream));
   return SBP_OK;
@@ -546,7 +556,7 @@ int32_t streambp_attn_chunk_backward(const sbp_attn_cfg* c, const void* q, const
   if (workspace_bytes < streambp_attn_workspace_bytes(c)) return fail(SBP_ERR_WORKSPACE, "workspace too small");
   AttnArgs a{};
   a.dt = c->dtype; a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads; a.dh = c->head_dim;
-  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale;
+  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale; a.window = c->window; a.kv_first = c->kv_first;
   a.q = q; a.k = k; a.v = v; a.o = (void*)o; a.lse = (float*)lse;
   a.d_o = d_o; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = (float*)workspace;
   HIPCHK(attn_backward(a, (hipStream_t)hip_stream));
@@ -615,7 +625,7 @@ int32_t streambp_attn_chunk_backward_noalloc(const sbp_attn_cfg* c, const void* 
   }
   AttnArgs a{};
   a.dt = c->dtype; a.Hq = c->n_q_heads; a.Hkv = c->n_kv_heads; a.dh = c->head_dim;
-  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale;
+  a.q_start = c->q_start; a.q_len = c->q_len; a.scale = c->scale; a.window = c->window; a.kv_first = c->kv_first;
   a.q = q; a.k = k; a.v = v; a.o = (void*)o; a.lse = (float*)lse;
   a.d_o = d_o; a.dq = dq; a.dk = dk; a.dv = dv; a.delta = scratch;
   HIPCHK(attn_backward(a, (hipStream_t)hip_stream));

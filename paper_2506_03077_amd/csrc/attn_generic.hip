@@ -2,8 +2,11 @@
 // the correctness path for the fp32 configuration and for head sizes the MFMA
 // kernels do not take.  Query row t of the chunk sits at global position
 // q_start + t and sees keys 0 .. q_start + t; the causal mask is an integer
-// comparison of positions, never a stored tensor.  No atomics: every output
-// element has exactly one owner, so results are reproducible.
+// comparison of positions, never a stored tensor, and so are the two optional
+// rules: a sliding window (keys t - window < u <= t) and padding in front of the
+// sequence (keys before kv_first hidden).  A query that sees no key gets o = 0,
+// lse = -inf and sends no gradient.  No atomics: every output element has
+// exactly one owner, so results are reproducible.
 #include "launch.h"
 
 namespace sbp {
@@ -14,18 +17,19 @@ template <typename T>
 __global__ __launch_bounds__(AG_THREADS) void attn_fwd_generic_k(const T* __restrict__ q, const T* __restrict__ k,
                                                                  const T* __restrict__ v, T* __restrict__ o,
                                                                  float* __restrict__ lse, int Hq, int Hkv, int dh,
-                                                                 int q_start, int c, float scale) {
+                                                                 int q_start, int c, float scale, int window, int kv_first) {
   __shared__ float qs[256];
   __shared__ float p[AG_THREADS];
   __shared__ float red[16];
   const int t = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
   const int kvh = h / (Hq / Hkv);
   const int n_keys = q_start + t + 1;
+  const int lo = max(kv_first, window > 0 ? q_start + t - window + 1 : 0);   // first visible key
   const int64_t kv_stride = (int64_t)Hkv * dh;
   if (tid < dh) qs[tid] = ldf(q + ((int64_t)t * Hq + h) * dh + tid) * scale;
   __syncthreads();
   float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
-  for (int u0 = 0; u0 < n_keys; u0 += AG_THREADS) {
+  for (int u0 = lo; u0 < n_keys; u0 += AG_THREADS) {
     const int u = u0 + tid;
     float sc = -INFINITY;
     if (u < n_keys) {
@@ -51,8 +55,8 @@ __global__ __launch_bounds__(AG_THREADS) void attn_fwd_generic_k(const T* __rest
     m_run = m_new;
     __syncthreads();
   }
-  if (tid < dh) stf(o + ((int64_t)t * Hq + h) * dh + tid, acc / l_run);
-  if (tid == 0) lse[(int64_t)h * c + t] = m_run + logf(l_run);
+  if (tid < dh) stf(o + ((int64_t)t * Hq + h) * dh + tid, l_run > 0.f ? acc / l_run : 0.f);
+  if (tid == 0) lse[(int64_t)h * c + t] = l_run > 0.f ? m_run + logf(l_run) : -INFINITY;
 }
 
 // delta[h, t] = sum_j d_o[t,h,j] * o[t,h,j]
@@ -72,7 +76,8 @@ __global__ __launch_bounds__(AG_THREADS) void attn_dq_generic_k(const T* __restr
                                                                 const T* __restrict__ v, const T* __restrict__ d_o,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ delta, T* __restrict__ dq,
-                                                                int Hq, int Hkv, int dh, int q_start, int c, float scale) {
+                                                                int Hq, int Hkv, int dh, int q_start, int c, float scale,
+                                                                int window, int kv_first) {
   __shared__ float qs[256];
   __shared__ float dos[256];
   __shared__ float dsv[AG_THREADS];
@@ -84,8 +89,9 @@ __global__ __launch_bounds__(AG_THREADS) void attn_dq_generic_k(const T* __restr
   if (tid < dh) { qs[tid] = ldf(q + qbase + tid); dos[tid] = ldf(d_o + qbase + tid); }
   __syncthreads();
   const float L = lse[(int64_t)h * c + t], D = delta[(int64_t)h * c + t];
+  const int lo = max(kv_first, window > 0 ? q_start + t - window + 1 : 0);
   float acc = 0.f;
-  for (int u0 = 0; u0 < n_keys; u0 += AG_THREADS) {
+  for (int u0 = lo; u0 < n_keys; u0 += AG_THREADS) {
     const int u = u0 + tid;
     float ds = 0.f;
     if (u < n_keys) {
@@ -118,7 +124,8 @@ __global__ __launch_bounds__(AG_THREADS) void attn_dkv_generic_k(const T* __rest
                                                                  const float* __restrict__ lse,
                                                                  const float* __restrict__ delta,
                                                                  float* __restrict__ dk, float* __restrict__ dv,
-                                                                 int Hq, int Hkv, int dh, int q_start, int c, float scale) {
+                                                                 int Hq, int Hkv, int dh, int q_start, int c, float scale,
+                                                                 int window, int kv_first) {
   __shared__ float ks[256];
   __shared__ float vs[256];
   __shared__ float ps[AG_THREADS];
@@ -129,7 +136,10 @@ __global__ __launch_bounds__(AG_THREADS) void attn_dkv_generic_k(const T* __rest
   if (tid < dh) { ks[tid] = ldf(k + kbase + tid); vs[tid] = ldf(v + kbase + tid); }
   __syncthreads();
   const int t_min = max(0, u - q_start);
-  const int n_pairs = (c - t_min) * G;
+  int t_end = c;                                                 // rows [t_min, t_end) see key u
+  if (window > 0) t_end = min(c, u + window - q_start);         // position <= u + window - 1
+  if (u < kv_first) t_end = t_min;
+  const int n_pairs = max(0, t_end - t_min) * G;
   float acc_k = 0.f, acc_v = 0.f;
   for (int i0 = 0; i0 < n_pairs; i0 += AG_THREADS) {
     const int i = i0 + tid;
@@ -164,10 +174,12 @@ hipError_t attn_forward_generic(const AttnArgs& a, hipStream_t st) {
   dim3 grid(a.q_len, a.Hq);
   if (a.dt == DT_BF16)
     attn_fwd_generic_k<bf16_t><<<grid, AG_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v,
-                                                           (bf16_t*)a.o, a.lse, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale);
+                                                           (bf16_t*)a.o, a.lse, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale,
+                                                           a.window, a.kv_first);
   else
     attn_fwd_generic_k<float><<<grid, AG_THREADS, 0, st>>>((const float*)a.q, (const float*)a.k, (const float*)a.v,
-                                                          (float*)a.o, a.lse, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale);
+                                                          (float*)a.o, a.lse, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale,
+                                                          a.window, a.kv_first);
   return hipGetLastError();
 }
 
@@ -176,10 +188,12 @@ static hipError_t attn_backward_generic_t(const AttnArgs& a, hipStream_t st) {
   dim3 gq(a.q_len, a.Hq);
   attn_delta_k<T><<<gq, 64, 0, st>>>((const T*)a.o, (const T*)a.d_o, a.delta, a.Hq, a.dh, a.q_len);
   attn_dq_generic_k<T><<<gq, AG_THREADS, 0, st>>>((const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.d_o, a.lse,
-                                                  a.delta, (T*)a.dq, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale);
+                                                  a.delta, (T*)a.dq, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale, a.window,
+                                                  a.kv_first);
   dim3 gk(a.q_start + a.q_len, a.Hkv);
   attn_dkv_generic_k<T><<<gk, AG_THREADS, 0, st>>>((const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.d_o, a.lse,
-                                                   a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale);
+                                                   a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.dh, a.q_start, a.q_len, a.scale, a.window,
+                                                   a.kv_first);
   return hipGetLastError();
 }
 

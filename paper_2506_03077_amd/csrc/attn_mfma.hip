@@ -4,7 +4,13 @@
 // 0 .. q_start + t of the cached prefix (paper Sec. 3.2.2, partitioned attention;
 // Property 3.1).  Key tiles that lie entirely above the diagonal are skipped,
 // tiles on the diagonal are masked by an integer comparison of positions, rows
-// past q_start + q_len of K/V are never read.
+// past q_start + q_len of K/V are never read.  Two more mask rules are index
+// arithmetic of the same kind (the paper's mask M covers "padding / sliding
+// window"): window > 0 limits a query at position t to the keys t - window < u <= t,
+// and kv_first hides the key positions before it (padding in front of the
+// sequence); key tiles wholly outside a wave's range are skipped on the left edge
+// just as on the right one, and a query that sees no key gets o = 0, lse = -inf
+// and sends no gradient.
 //
 // All three kernels use the "transposed score" formulation on the 32x32x16
 // MFMA: S^T[key, query] = K Q^T.  The accumulator layout then gives every lane
@@ -174,7 +180,8 @@ __device__ __forceinline__ int acc_row(int r, int h) { return 8 * (r >> 2) + 4 *
 __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const bf16_t* __restrict__ k,
                                                                  const bf16_t* __restrict__ v, bf16_t* __restrict__ o,
                                                                  float* __restrict__ lse, int Hq, int Hkv, int q_start,
-                                                                 int c, float scale, const float2* __restrict__ rope) {
+                                                                 int c, float scale, const float2* __restrict__ rope,
+                                                                 int window, int kv_first) {
   __shared__ __attribute__((aligned(1024))) char sT[4][TILE64_BYTES];   // stage st: K = sT[2 st], V = sT[2 st + 1]
 
   const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
@@ -192,6 +199,12 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const b
   const int n_tiles = (n_keys + TK - 1) / TK;
   const int wave_last_key = q_start + min(qw0 + 32, c) - 1;           // last key any query of this wave sees
   const int wave_first_qpos = q_start + qw0;
+  // left edge of the visible range: first visible key of a query at position p
+  auto first_key = [&](int p) { return max(kv_first, window > 0 ? p - window + 1 : 0); };
+  const int lo_q = first_key(qpos);                                   // of this lane's query
+  const int wave_lo_min = first_key(wave_first_qpos);                 // lowest first key in the wave (its first query)
+  const int wave_lo_max = first_key(wave_last_key);                   // highest one (its last query)
+  const int kt0 = first_key(q_start + q0) / TK;                       // first key tile any query of the workgroup sees
 
   const uint32_t lds0 = lds_addr(&sT[0][0]);
   const FragPre fp = frag_pre(lds0);
@@ -235,19 +248,21 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const b
   auto step = [&](int kt, auto stage) {
     constexpr uint32_t oK = decltype(stage)::value * 2 * TILE64_BYTES, oV = oK + TILE64_BYTES;
     const int k0 = kt * TK;
-    if (qw0 >= c || k0 > wave_last_key) return;           // nothing visible to this wave in the tile
+    if (qw0 >= c || k0 > wave_last_key || k0 + TK - 1 < wave_lo_min) return;   // nothing visible to this wave in the tile
     f32x16 s[2];
     s[0] = zero16();
     s[1] = zero16();
     mfma_chain<16>([&](int i) { return lds_b128(fp.rows[i & 7] + oK + (i >> 3) * 32 * ROW_BYTES); },
                    [&](int i, const bf16x8& f) { s[i >> 3] = MFMA(f, bq[i & 7], s[i >> 3]); });
-    const bool diag = k0 + TK - 1 > wave_first_qpos;      // some (query, key) pair of the wave is masked
-    if (diag) {                                           // wave-uniform: only tiles on the diagonal pay for the mask
+    const bool diag = k0 + TK - 1 > wave_first_qpos || k0 < wave_lo_max;   // some (query, key) pair of the wave is masked
+    if (diag) {                                           // wave-uniform: only tiles on an edge of the visible range pay for the mask
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (k0 + b * 32 + acc_row(r, half) > qpos) s[b][r] = -INFINITY;
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + b * 32 + acc_row(r, half);
+          if (key > qpos || key < lo_q) s[b][r] = -INFINITY;
+        }
     }
     float mx = s[0][0];                                   // max of the raw scores (scale > 0 keeps the order)
 #pragma unroll
@@ -258,7 +273,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const b
     // The running max (and with it the rescale of O) only moves when some query of the wave sees a new maximum.
     if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {
       const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);   // a query that has seen no key yet keeps its zeros
       m_run = m_new;
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc_l[r] *= alpha;
@@ -267,10 +282,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const b
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
     }
+    const float m_sub = m_run == -INFINITY ? 0.0f : m_run;    // all scores so far masked: exp2(-inf - 0) = 0, not exp2(-inf + inf)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[b][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], sl, -m_run));
+      for (int r = 0; r < 16; ++r) s[b][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], sl, -m_sub));
     bf16x8 pb[4];     // P^T of the tile as four B operands: index = block * 2 + k16 step
 #pragma unroll
     for (int j = 0; j < 4; ++j) pb[j] = pack8(s[j >> 1], j & 1);
@@ -288,8 +304,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const b
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
 
-  issue(0, 0);
-  for (int kt = 0; kt < n_tiles; kt += 2) {
+  if (kt0 < n_tiles) issue(kt0, 0);
+  for (int kt = kt0; kt < n_tiles; kt += 2) {
     WAIT_VM0();
     __syncthreads();
     if (kt + 1 < n_tiles) issue(kt + 1, 1);
@@ -304,7 +320,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const b
 
   const float l_tot = acc_l[0];
   if (q_valid) {
-    const float inv = 1.0f / l_tot;
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.0f;      // a query that saw no key: o = 0, lse = -inf
     bf16_t* op = o + ((int64_t)my_q * Hq + h) * DH;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -315,7 +331,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_mfma_k(bf16_t* q, const b
         for (int e = 0; e < 4; ++e) w[e] = (bf16_t)(acc_o[i][4 * a + e] * inv);
         *(bf16x4*)(op + i * 32 + 8 * a + 4 * half) = w;
       }
-    if (half == 0) lse[(int64_t)h * c + my_q] = (m_run + log2f(l_tot)) * LN2;
+    if (half == 0) lse[(int64_t)h * c + my_q] = l_tot > 0.f ? (m_run + log2f(l_tot)) * LN2 : -INFINITY;
   }
 }
 
@@ -324,7 +340,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
                                                                     const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
                                                                     const float* __restrict__ lse, const float* __restrict__ delta,
                                                                     bf16_t* __restrict__ dq, int Hq, int Hkv, int q_start, int c,
-                                                                    float scale, const float2* __restrict__ rope) {
+                                                                    float scale, const float2* __restrict__ rope, int window,
+                                                                    int kv_first) {
   __shared__ __attribute__((aligned(1024))) char sT[4][TILE64_BYTES];   // stage st: K = sT[2 st], V = sT[2 st + 1]
 
   const int q0 = blockIdx.x * TQ, h = blockIdx.y, kvh = h / (Hq / Hkv);
@@ -342,6 +359,10 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
   const int n_tiles = (n_keys + TK - 1) / TK;
   const int wave_last_key = q_start + min(qw0 + 32, c) - 1;
   const int wave_first_qpos = q_start + qw0;
+  auto first_key = [&](int p) { return max(kv_first, window > 0 ? p - window + 1 : 0); };   // left edge of the visible range
+  const int lo_q = first_key(qpos);
+  const int wave_lo_min = first_key(wave_first_qpos), wave_lo_max = first_key(wave_last_key);
+  const int kt0 = first_key(q_start + q0) / TK;
 
   const uint32_t lds0 = lds_addr(&sT[0][0]);
   const FragPre fp = frag_pre(lds0);
@@ -353,7 +374,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) { bq[ks] = *(const bf16x8*)(q + off + ks * 16); bdo[ks] = *(const bf16x8*)(d_o + off + ks * 16); }
   }
-  const float lse2 = lse[(int64_t)h * c + q_row] * LOG2E;
+  const float lse_q = lse[(int64_t)h * c + q_row];
+  const float lse2 = lse_q == -INFINITY ? 0.0f : lse_q * LOG2E;    // a query that saw no key: every score is masked, p = exp2(-inf) = 0
   const float dlt = delta[(int64_t)h * c + q_row];
   const float sl = scale * LOG2E;
   f32x16 acc[4];
@@ -363,8 +385,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
   auto step = [&](int kt, auto stage) {
     constexpr uint32_t oK = decltype(stage)::value * 2 * TILE64_BYTES, oV = oK + TILE64_BYTES;
     const int k0 = kt * TK;
-    if (qw0 >= c || k0 > wave_last_key) return;
-    const bool diag = k0 + TK - 1 > wave_first_qpos;
+    if (qw0 >= c || k0 > wave_last_key || k0 + TK - 1 < wave_lo_min) return;
+    const bool diag = k0 + TK - 1 > wave_first_qpos || k0 < wave_lo_max;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       f32x16 s = zero16(), dp = zero16();
@@ -372,8 +394,10 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
                      [&](int i, const bf16x8& f) { if (i < 8) s = MFMA(f, bq[i], s); else dp = MFMA(f, bdo[i - 8], dp); });
       if (diag) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (k0 + b * 32 + acc_row(r, half) > qpos) s[r] = -INFINITY;     // exp2(-inf) = 0
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + b * 32 + acc_row(r, half);
+          if (key > qpos || key < lo_q) s[r] = -INFINITY;     // exp2(-inf) = 0
+        }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -395,8 +419,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_mfma_k(const bf16_t* _
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
 
-  issue(0, 0);
-  for (int kt = 0; kt < n_tiles; kt += 2) {
+  if (kt0 < n_tiles) issue(kt0, 0);
+  for (int kt = kt0; kt < n_tiles; kt += 2) {
     WAIT_VM0();
     __syncthreads();
     if (kt + 1 < n_tiles) issue(kt + 1, 1);
@@ -462,14 +486,15 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
                                                                   const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
                                                                   const float* __restrict__ lse2, const float* __restrict__ delta,
                                                                   float* __restrict__ dk, float* __restrict__ dv, int Hq, int Hkv,
-                                                                  int q_start, int c, float scale) {
+                                                                  int q_start, int c, float scale, int window, int kv_first,
+                                                                  int key_block0) {
   __shared__ __attribute__((aligned(1024))) char sQD[KV_STAGES][2][TILE64_BYTES];   // [stage][Q | dO]
   __shared__ __attribute__((aligned(16))) bf16x8 sP[2][4][4][64];   // [tile parity][key block][query block * 2 + k16 step][lane]
   __shared__ __attribute__((aligned(16))) float sL[KV_STAGES][QT];  // log2-domain log-sum-exp of the tile's queries
   __shared__ __attribute__((aligned(16))) float sDl[KV_STAGES][QT]; // delta of the tile's queries
 
   const int G = Hq / Hkv;
-  const int key0 = blockIdx.x * KV_TILE, kvh = blockIdx.y;
+  const int key0 = (key_block0 + (int)blockIdx.x) * KV_TILE, kvh = blockIdx.y;   // key blocks before key_block0 are visible to no query
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5;
   const int kb = wave & 3;
   const bool role_p = wave < 4;
@@ -500,9 +525,11 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
   const float sl = scale * LOG2E;
 
   // query tiles that can see at least one key of this workgroup: query position >= key0
+  // ... and, under a sliding window, query position <= last key of the workgroup + window - 1
   const int qt_first = max(0, key0 - q_start) / QT;
-  const int n_qt = (c + QT - 1) / QT;
-  const int n_iter = (n_qt - qt_first) * G;
+  int n_qt = (c + QT - 1) / QT;
+  if (window > 0) n_qt = min(n_qt, max(0, key0 + KV_TILE - 1 + window - 1 - q_start) / QT + 1);
+  const int n_iter = max(0, n_qt - qt_first) * G;
 
   auto issue = [&](int it, int stage) {
     const int qt = qt_first + it / G, hh = kvh * G + it % G;
@@ -517,7 +544,10 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
   };
   // One 64-query tile = two 32-query blocks.  `active`: the wave has a valid key and some query of the tile is
   // at or after its first key (the same answer for both waves of a key block).
-  auto tile_active = [&](int qbase) { return kw0 < n_total && q_start + min(qbase + QT, c) - 1 >= kw0; };
+  auto tile_active = [&](int qbase) {
+    return kw0 < n_total && q_start + min(qbase + QT, c) - 1 >= kw0 && kw0 + 31 >= kv_first &&
+           (window == 0 || q_start + qbase - window < kw0 + 31);     // the tile's first query still reaches the wave's last key
+  };
   auto lds_f4 = [](uint32_t addr) { return *(const float4*)(__attribute__((address_space(3))) const char*)(uintptr_t)addr; };
 
   auto p_step = [&](f32x16 (&acc)[4], int it, auto stage_c, int par) __attribute__((always_inline)) {
@@ -527,7 +557,8 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
     const FragPre& gt = stage < 2 ? g0 : g2;
     const int qbase = (qt_first + it / G) * QT;
     if (!tile_active(qbase)) return;
-    const bool diag = (q_start + qbase < kw0 + 31) || (qbase + QT > c);   // some pair masked, or ragged query tile
+    const bool diag = (q_start + qbase < kw0 + 31) || (qbase + QT > c) || kw0 < kv_first ||   // some pair masked, or ragged query tile
+                      (window > 0 && q_start + qbase + QT - 1 - window >= kw0);
     const uint32_t sp = sp_lane + (uint32_t)par * (uint32_t)sizeof(sP[0]);
 #pragma unroll
     for (int b = 0; b < 2; ++b) {      // one 32-query block at a time: fewer live registers
@@ -539,7 +570,8 @@ __global__ __launch_bounds__(KV_THREADS) void attn_bwd_dkv_mfma_k(const bf16_t* 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int qi = qbase + b * 32 + acc_row(r, half);
-          if (qi >= c || my_key > q_start + qi) t[r] = -INFINITY;      // exp2(-inf) = 0
+          if (qi >= c || my_key > q_start + qi || my_key < kv_first || (window > 0 && my_key <= q_start + qi - window))
+            t[r] = -INFINITY;                                          // exp2(-inf) = 0
         }
       }
 #pragma unroll
@@ -662,7 +694,8 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_k(const bf16_t* __restric
   s = wave_sum(s);
   if (lane == 0) {
     delta[(int64_t)h * c + t] = s;
-    lse2[(int64_t)h * c + t] = lse[(int64_t)h * c + t] * LOG2E;
+    const float l = lse[(int64_t)h * c + t];
+    lse2[(int64_t)h * c + t] = l == -INFINITY ? 0.0f : l * LOG2E;   // a query that saw no key: its scores are all masked anyway
   }
 }
 
@@ -680,7 +713,7 @@ hipError_t attn_forward_mfma(const AttnArgs& a, hipStream_t st) {
   if (a.q_len == 0) return hipSuccess;
   dim3 grid((unsigned)cdiv(a.q_len, TQ), a.Hq);
   attn_fwd_mfma_k<<<grid, AT_THREADS, 0, st>>>((bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (bf16_t*)a.o, a.lse,
-                                               a.Hq, a.Hkv, a.q_start, a.q_len, a.scale, a.rope_q);
+                                               a.Hq, a.Hkv, a.q_start, a.q_len, a.scale, a.rope_q, a.window, a.kv_first);
   return hipGetLastError();
 }
 
@@ -692,10 +725,18 @@ hipError_t attn_backward_mfma(const AttnArgs& a, hipStream_t st) {
                                                               a.q_len);
   dim3 gq((unsigned)cdiv(a.q_len, TQ), a.Hq);
   attn_bwd_dq_mfma_k<<<gq, AT_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
-                                                a.lse, a.delta, (bf16_t*)a.dq, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale, a.rope_q);
-  dim3 gk((unsigned)cdiv(a.q_start + a.q_len, KV_TILE), a.Hkv);
-  attn_bwd_dkv_mfma_k<<<gk, KV_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
-                                                 lse2, a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale);
+                                                a.lse, a.delta, (bf16_t*)a.dq, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale, a.rope_q,
+                                                a.window, a.kv_first);
+  // key blocks that no query of the chunk can see (before the padding ends, or older than the first query's window)
+  // are not launched: their dK/dV contribution is zero
+  const int first_visible = std::max(a.kv_first, a.window > 0 ? a.q_start - a.window + 1 : 0);
+  const int kb0 = std::max(0, first_visible) / KV_TILE, kb1 = (int)cdiv(a.q_start + a.q_len, KV_TILE);
+  if (kb1 > kb0) {
+    dim3 gk((unsigned)(kb1 - kb0), a.Hkv);
+    attn_bwd_dkv_mfma_k<<<gk, KV_THREADS, 0, st>>>((const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, (const bf16_t*)a.d_o,
+                                                   lse2, a.delta, a.dk, a.dv, a.Hq, a.Hkv, a.q_start, a.q_len, a.scale,
+                                                   a.window, a.kv_first, kb0);
+  }
   return hipGetLastError();
 }
 

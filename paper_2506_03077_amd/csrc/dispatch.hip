@@ -3,6 +3,7 @@
 #include "../../include/streambp_debug.h"
 #include "launch.h"
 
+#include <algorithm>
 #include <atomic>
 #include <vector>
 
@@ -63,7 +64,13 @@ Scope::~Scope() {
 
 static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs of the chunk, all query heads
   const double c = a.q_len, s = a.q_start;
-  return (double)a.Hq * (c * s + c * (c + 1.0) / 2.0);
+  if (a.window == 0 && a.kv_first == 0) return (double)a.Hq * (c * s + c * (c + 1.0) / 2.0);
+  double pairs = 0.0;
+  for (int t = 0; t < a.q_len; ++t) {
+    const int p = a.q_start + t, lo = std::max(a.kv_first, a.window > 0 ? p - a.window + 1 : 0);
+    pairs += std::max(0, p - lo + 1);
+  }
+  return (double)a.Hq * pairs;
 }
 
 hipError_t gemm(const GemmArgs& g, hipStream_t st) {

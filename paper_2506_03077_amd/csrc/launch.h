@@ -114,6 +114,8 @@ struct AttnArgs {
   int Hq, Hkv, dh;
   int q_start, q_len;
   float scale;
+  int window = 0;          // > 0: a query at position t sees only keys t - window < u <= t
+  int kv_first = 0;        // key positions before this one are padding: never visible
   const void *q, *k, *v;   // q [c,Hq,dh]; k,v [>=s+c,Hkv,dh]
   void* o; float* lse;     // o [c,Hq,dh]; lse [Hq,c]
   const void* d_o; void* dq; float *dk, *dv;

@@ -81,10 +81,11 @@ def assert_close(got, want, tol, name):
 def oracle_cfg(cfg):
     return dict(n_q_heads=cfg["n_q_heads"], n_kv_heads=cfg["n_kv_heads"], head_dim=cfg["head_dim"],
                 rms_eps=cfg.get("rms_eps", 1e-6), rope_theta=cfg.get("rope_theta", 1e4),
-                pos_offset=cfg.get("pos_offset", 0))
+                pos_offset=cfg.get("pos_offset", 0), window=cfg.get("window", 0))
 
 
-def lib_layer_cfg(cfg, seq_len, chunk, batch=1, grad_dtype="f32", dw_group_rows=0):
+def lib_layer_cfg(cfg, seq_len, chunk, batch=1, grad_dtype="f32", dw_group_rows=0, seq_first=None):
     return sb.layer_cfg(code(cfg["dtype"]), batch, seq_len, chunk, cfg["hidden"], cfg["n_q_heads"],
                         cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"], cfg.get("rms_eps", 1e-6),
-                        cfg.get("rope_theta", 1e4), cfg.get("pos_offset", 0), code(grad_dtype), dw_group_rows)
+                        cfg.get("rope_theta", 1e4), cfg.get("pos_offset", 0), code(grad_dtype), dw_group_rows,
+                        cfg.get("window", 0), seq_first)

@@ -168,6 +168,17 @@ def test_noalloc_backward_rejects_what_the_builtin_scratch_cannot_hold():
     assert L.streambp_attn_chunk_backward_noalloc(C.byref(ac), None, 256, 256, 256, 256, 256, 256, 256, 256, None) == -1
 
 
+def test_bad_mask_arguments_are_refused():
+    ac = sb.attn_cfg(sb.SBP_BF16, 8, 2, 128, 0, 64, 0.1, window=-1)
+    assert sb.lib().streambp_attn_chunk_forward(C.byref(ac), 256, 256, 256, 256, 256, None) == -2
+    ac = sb.attn_cfg(sb.SBP_BF16, 8, 2, 128, 0, 64, 0.1, kv_first=-3)
+    assert sb.lib().streambp_attn_chunk_forward(C.byref(ac), 256, 256, 256, 256, 256, None) == -2
+    lc = sb.layer_cfg(sb.SBP_F32, 2, 64, 16, 64, 4, 4, 16, 172, seq_first=[0, 65])
+    assert sb.streambp_layer_workspace_bytes(lc) == 0 and "seq_first" in sb.streambp_last_error()
+    assert sb.streambp_layer_workspace_bytes(sb.layer_cfg(sb.SBP_F32, 2, 64, 16, 64, 4, 4, 16, 172, window=-2)) == 0
+    assert sb.streambp_layer_workspace_bytes(sb.layer_cfg(sb.SBP_F32, 2, 64, 16, 64, 4, 4, 16, 172, window=8, seq_first=[0, 64])) > 0
+
+
 def test_fast_path_query_names_the_configs_that_leave_the_mfma_kernels():
     big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
     assert sb.streambp_layer_fast_path(good_layer_cfg(**big)) == 1
