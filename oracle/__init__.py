@@ -14,6 +14,10 @@ head     LM head + objective (SFT, GRPO, DPO) forward/backward (Sec. 3.2.1).
 attn     causal attention of a chunk of queries against the prefix keys and
          values, forward and backward (Sec. 3.2.2, partitioned attention and
          Property 3.1).
+lora     the same layer with low-rank adapters on its projection matrices and
+         the adapter gradients (App. D, experiment setup: rank-32 adapters for
+         the largest model); the masks of attn / layer beyond plain causality
+         (sliding window, padding in front) are options of those modules.
 chunked  the paper's chunk loop itself, in fp64, step by step (Sec. 3.2.1 and
          3.2.2) - used to check that per-chunk partial gradients sum to the
          full gradient and that chunk size does not matter.
