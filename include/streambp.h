@@ -133,6 +133,32 @@ int32_t streambp_layer_backward(const sbp_layer_cfg *cfg, const sbp_layer_weight
                                 const sbp_layer_grads *dw,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Adapter mode (App. D, experiment setup: the largest model is trained with rank-32 low-rank adapters and only the
+ * adapter gradients are computed).  An adapted matrix acts as y = x W^T + s (x A^T) B^T = x (W + s B A)^T with W
+ * frozen.  Matrices in the order wq, wk, wv, wo, wgate, wup, wdown; a[i] == b[i] == NULL: matrix i has no adapter. */
+typedef struct {
+  int32_t rank;          /* r, 1 .. 256                                              */
+  float scale;           /* s (usually alpha / r)                                    */
+  const void *a[7];      /* A_i [r, in_i]   device, cfg.dtype                        */
+  const void *b[7];      /* B_i [out_i, r]  device, cfg.dtype                        */
+} sbp_lora_adapters;
+typedef struct {
+  float *da[7];          /* [r, in_i]  fp32 device, +=  (NULL where not adapted)     */
+  float *db[7];          /* [out_i, r] fp32 device, +=                               */
+} sbp_lora_grads;
+
+size_t streambp_layer_lora_workspace_bytes(const sbp_layer_cfg *cfg, const sbp_lora_adapters *ad);
+
+/* StreamBP of one layer in adapter mode: the same chunk loop as streambp_layer_backward on the effective matrices
+ * W + s B A (built once per call in the workspace: one extra copy of the adapted matrices), but no gradient of W,
+ * g1 or g2 is formed; per chunk and adapted matrix the Eq. 1 summands dB += s dY^T (X A^T) and dA += s (dY B)^T X are
+ * accumulated (the chain rule through B A, without forming dW).  dx [B, T, d] out.  cfg.grad_dtype must be SBP_F32;
+ * cfg.dw_group_rows is ignored (there are no passes over weight gradients to group). */
+int32_t streambp_layer_lora_backward(const sbp_layer_cfg *cfg, const sbp_layer_weights *w,
+                                     const sbp_lora_adapters *ad, const void *x, const void *dy, void *dx,
+                                     const sbp_lora_grads *dad, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+
 /* Chunked forward of the same layer with the same kernels (used to produce the
  * per-layer checkpoints of a stack): y [B, T, d] out. */
 int32_t streambp_layer_forward(const sbp_layer_cfg *cfg, const sbp_layer_weights *w,

@@ -40,6 +40,17 @@ class LayerGrads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_NAMES]
 
 
+MATRIX_NAMES = WEIGHT_NAMES[:7]
+
+
+class LoraAdapters(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("scale", C.c_float), ("a", C.c_void_p * 7), ("b", C.c_void_p * 7)]
+
+
+class LoraGrads(C.Structure):
+    _fields_ = [("da", C.c_void_p * 7), ("db", C.c_void_p * 7)]
+
+
 class HeadCfg(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("batch", C.c_int32), ("seq_len", C.c_int32), ("chunk", C.c_int32),
                 ("hidden", C.c_int32), ("vocab", C.c_int32), ("objective", C.c_int32), ("loss_scale", C.c_float),
@@ -78,6 +89,11 @@ def lib():
         L.streambp_layer_backward.restype = i32
         L.streambp_layer_backward.argtypes = [C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp,
                                               C.POINTER(LayerGrads), vp, sz, vp]
+        L.streambp_layer_lora_workspace_bytes.restype = sz
+        L.streambp_layer_lora_workspace_bytes.argtypes = [C.POINTER(LayerCfg), C.POINTER(LoraAdapters)]
+        L.streambp_layer_lora_backward.restype = i32
+        L.streambp_layer_lora_backward.argtypes = [C.POINTER(LayerCfg), C.POINTER(LayerWeights), C.POINTER(LoraAdapters), vp, vp, vp,
+                                                   C.POINTER(LoraGrads), vp, sz, vp]
         L.streambp_layer_forward.restype = i32
         L.streambp_layer_forward.argtypes = [C.POINTER(LayerCfg), C.POINTER(LayerWeights), vp, vp, vp, sz, vp]
         L.streambp_lmhead_workspace_bytes.restype = sz
@@ -227,6 +243,39 @@ def streambp_layer_backward(cfg: LayerCfg, w, x, dy, dx=None, dw=None, workspace
     _check(lib().streambp_layer_backward(C.byref(cfg), C.byref(ws), _ptr(x), _ptr(dy), _ptr(dx), C.byref(gs),
                                          _ptr(workspace), workspace.numel(), _stream(stream)))
     return dx, dw
+
+
+def _lora_struct(adapters, rank, scale):
+    a = (C.c_void_p * 7)(*[(_ptr(adapters[n][0]) if n in adapters else None) for n in MATRIX_NAMES])
+    b = (C.c_void_p * 7)(*[(_ptr(adapters[n][1]) if n in adapters else None) for n in MATRIX_NAMES])
+    return LoraAdapters(int(rank), float(scale), a, b)
+
+
+def streambp_layer_lora_workspace_bytes(cfg: LayerCfg, adapters, rank, scale=1.0) -> int:
+    ad = _lora_struct(adapters, rank, scale)
+    return int(lib().streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(ad)))
+
+
+def streambp_layer_lora_backward(cfg: LayerCfg, w, adapters, rank, scale, x, dy, dx=None, da=None, db=None, workspace=None,
+                                 stream=None):
+    """adapters: dict matrix name -> (A [r, in], B [out, r]) device tensors; returns (dx, da, db) with da / db dicts of fp32
+    tensors (accumulated into when given)."""
+    torch = _torch()
+    if dx is None:
+        dx = torch.empty_like(x)
+    if da is None:
+        da = {n: torch.zeros(ab[0].shape, dtype=torch.float32, device=x.device) for n, ab in adapters.items()}
+    if db is None:
+        db = {n: torch.zeros(ab[1].shape, dtype=torch.float32, device=x.device) for n, ab in adapters.items()}
+    ad = _lora_struct(adapters, rank, scale)
+    if workspace is None:
+        workspace = _workspace(lib().streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(ad)), x.device)
+    gs = LoraGrads((C.c_void_p * 7)(*[(_ptr(da[n]) if n in adapters else None) for n in MATRIX_NAMES]),
+                   (C.c_void_p * 7)(*[(_ptr(db[n]) if n in adapters else None) for n in MATRIX_NAMES]))
+    ws = _weights_struct(w)
+    _check(lib().streambp_layer_lora_backward(C.byref(cfg), C.byref(ws), C.byref(ad), _ptr(x), _ptr(dy), _ptr(dx), C.byref(gs),
+                                              _ptr(workspace), workspace.numel(), _stream(stream)))
+    return dx, da, db
 
 
 def streambp_layer_forward(cfg: LayerCfg, w, x, y=None, workspace=None, stream=None):

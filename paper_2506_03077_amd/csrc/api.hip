@@ -255,28 +255,33 @@ size_t streambp_layer_workspace_bytes(const sbp_layer_cfg* cfg) {
   return carve_layer(cfg, nullptr).bytes;
 }
 
-int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const void* x, const void* dy,
-                                void* dx, const sbp_layer_grads* g, void* workspace, size_t workspace_bytes,
-                                void* hip_stream) {
-  int32_t rc = check_layer_cfg(c);
-  if (rc) return rc;
-  if ((rc = check_layer_ptrs(w))) return rc;
-  if (!x || !dy || !dx || !g || !workspace) return fail(SBP_ERR_NULL, "x, dy, dx, dw and workspace must be non-NULL");
-  {
-    const void* ps[] = {g->wq, g->wk, g->wv, g->wo, g->wgate, g->wup, g->wdown, g->g1, g->g2};
-    for (const void* p : ps) if (!p) return fail(SBP_ERR_NULL, "a gradient pointer is NULL");
-  }
-  if (dx == x || dx == dy) return fail(SBP_ERR_SHAPE, "dx may not alias x or dy");
-  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-  const LayerWs s_all = carve_layer(c, workspace);
-  if (workspace_bytes < s_all.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s_all.bytes);
+// Low-rank adapter mode of the layer backward (App. D, experiment setup: rank-32 adapters, adapter gradients only).
+// The chunk loop runs on the effective matrices W + s B A (built once per call); instead of the seven weight gradients
+// of a chunk it forms, per adapted matrix, P = X A^T, Q = dY B (chunk x rank, padded to the GEMM tile width) and
+// accumulates dB += dY^T P, dA += Q^T X - the chain rule through B A without ever forming dW.
+constexpr int LORA_PAD = 256;      // adapter rank padded to the MFMA GEMMs' tile width
+struct LoraCtx {
+  int n;                           // adapted matrices
+  int which[7];                    // index into the order wq, wk, wv, wo, wgate, wup, wdown
+  int out_dim[7], in_dim[7];
+  void *a_pad[7], *b_pad[7];       // [LORA_PAD, in], [out, LORA_PAD] in the storage type, zero beyond the rank
+  float *da_pad[7], *db_pad[7];    // fp32 accumulators of the same shapes
+  void *P[7], *Q[7];               // [chunk, LORA_PAD] per adapted matrix
+  float* dg_sink;                  // the norm gains are frozen: their gradient goes nowhere
+};
+} // extern "C"
 
-  hipStream_t st = (hipStream_t)hip_stream;
+namespace {
+int32_t layer_backward_impl(const sbp_layer_cfg* c, const sbp_layer_weights* w, const void* x, const void* dy, void* dx,
+                            const sbp_layer_grads* g, const LoraCtx* lora, const LayerWs& s_all, hipStream_t st) {
+  int32_t rc;
   t_gemm_scratch = s_all.gemm_scratch; t_gemm_scratch_bytes = s_all.gemm_scratch_bytes;
   const int dt = c->dtype, gdt = c->grad_dtype;
   const size_t es = dtype_size(dt);
   const int T = c->seq_len, cm = std::min(c->chunk, T), d = c->hidden, F = c->mlp_width;
   const int qd = c->n_q_heads * c->head_dim, kd = c->n_kv_heads * c->head_dim, half = c->head_dim / 2;
+  float* dg1 = lora ? lora->dg_sink : g->g1;
+  float* dg2 = lora ? lora->dg_sink + d : g->g2;
 
   HIPCHK(rope_table(s_all.rope, T, c->head_dim, c->rope_theta, c->pos_offset, st));
   for (int b = 0; b < c->batch; ++b) {
@@ -299,8 +304,8 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
       if ((rc = chunk_reforward(c, w, s, xb, r0, n, kv_first, false, st))) return rc;
       const char* dyc = at(dyb, r0, d, es);
       // ---- MLP backward (the weight-gradient GEMMs of the chunk are deferred to one grouped launch below)
-      {   // dact = dy W_d with the SwiGLU adjoint in the GEMM's epilogue: gate <- dgate, up <- dup, act <- silu(gate) up;
-          // dact itself is only materialised where the fused kernel cannot take the shape
+      {   // dact = dy W_d, then the SwiGLU adjoint: gate <- dgate, up <- dup, act <- silu(gate) up.  The adjoint can run as
+          // the GEMM's epilogue (dact is then never stored); measured slower than the elementwise pass, so off by default.
         GemmArgs gd = dx_gemm(dyc, w->wdown, s.dact, n, d, F, dt, dt, false);
         if (fusion_mask() & FUSE_SWIGLU) {
           gd.swiglu_gate = s.gate; gd.swiglu_up = s.up; gd.swiglu_act = s.act;
@@ -315,7 +320,7 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
         gm.A2 = s.up; gm.B2 = w->wup;
         HIPCHK(gemm(gm, st));
       }
-      HIPCHK(rmsnorm_bwd(dt, s.dm, s.h1, true, w->g2, s.rstd2, dyc, false, s.dh1, s.dh1_t, g->g2, s.partial, n, d, st));
+      HIPCHK(rmsnorm_bwd(dt, s.dm, s.h1, true, w->g2, s.rstd2, dyc, false, s.dh1, s.dh1_t, dg2, s.partial, n, d, st));
       // ---- attention-side backward
       HIPCHK(gemm(dx_gemm(s.dh1_t, w->wo, s.d_o, n, d, qd, dt, dt, false), st));
       AttnArgs aa{};
@@ -336,9 +341,9 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
                                 dx_gemm(s.dvc, w->wv, s.da, n, kd, d, dt, DT_F32, true)};
         HIPCHK(gemm_batch(kv, 2, st));
       }
-      // ---- the seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand): queued, and launched together
-      //      with those of the other chunks of the group (one pass over every dW for the group's rows)
-      {
+      if (!lora) {
+        // ---- the seven weight gradients of the chunk, dW += dY^T X (Eq. 1 summand): queued, and launched together
+        //      with those of the other chunks of the group (one pass over every dW for the group's rows)
         const GemmArgs mine[7] = {dw_gemm(dyc, s.act, g->wdown, n, d, F, dt, gdt),  dw_gemm(s.gate, s.m, g->wgate, n, F, d, dt, gdt),
                                   dw_gemm(s.up, s.m, g->wup, n, F, d, dt, gdt),    dw_gemm(s.dh1_t, s.o, g->wo, n, d, qd, dt, gdt),
                                   dw_gemm(s.dq, s.a, g->wq, n, qd, d, dt, gdt),    dw_gemm(s.dkc, s.a, g->wk, n, kd, d, dt, gdt),
@@ -348,10 +353,149 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
           HIPCHK(gemm_batch(dws, n_dws, st));
           n_dws = 0;
         }
+      } else {
+        // ---- adapter gradients of the chunk (Eq. 1 summands of dA and dB): four grouped launches of skinny GEMMs
+        const void* dYs[7] = {s.dq, s.dkc, s.dvc, s.dh1_t, s.gate, s.up, dyc};     // order wq, wk, wv, wo, wgate, wup, wdown
+        const void* Xs[7] = {s.a, s.a, s.a, s.o, s.m, s.m, s.act};
+        GemmArgs gp[7], gq[7], gb[7], ga[7];
+        for (int j = 0; j < lora->n; ++j) {
+          const int i = lora->which[j], out = lora->out_dim[j], in = lora->in_dim[j];
+          gp[j] = fwd_gemm(Xs[i], lora->a_pad[j], lora->P[j], n, LORA_PAD, in, dt, dt);                                    // P = X A^T
+          gq[j] = mk(dYs[i], lora->b_pad[j], lora->Q[j], n, LORA_PAD, out, out, LORA_PAD, LORA_PAD, false, false, dt, dt, false);   // Q = dY B
+          gb[j] = dw_gemm(dYs[i], lora->P[j], lora->db_pad[j], n, out, LORA_PAD, dt, DT_F32);                              // dB += dY^T P
+          ga[j] = dw_gemm(lora->Q[j], Xs[i], lora->da_pad[j], n, LORA_PAD, in, dt, DT_F32);                                // dA += Q^T X
+        }
+        if (lora->n == 1) {
+          HIPCHK(gemm(gp[0], st)); HIPCHK(gemm(gq[0], st)); HIPCHK(gemm(gb[0], st)); HIPCHK(gemm(ga[0], st));
+        } else {
+          HIPCHK(gemm_batch(gp, lora->n, st, true));
+          HIPCHK(gemm_batch(gq, lora->n, st, true));
+          HIPCHK(gemm_batch(gb, lora->n, st, true));
+          HIPCHK(gemm_batch(ga, lora->n, st, true));
+        }
       }
       HIPCHK(rmsnorm_bwd(dt, s.da, at(xb, r0, d, es), false, w->g1, s.rstd1, s.dh1, true, nullptr, at(dxb, r0, d, es),
-                         g->g1, s.partial, n, d, st));
+                         dg1, s.partial, n, d, st));
     }
+  }
+  return SBP_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const void* x, const void* dy,
+                                void* dx, const sbp_layer_grads* g, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  int32_t rc = check_layer_cfg(c);
+  if (rc) return rc;
+  if ((rc = check_layer_ptrs(w))) return rc;
+  if (!x || !dy || !dx || !g || !workspace) return fail(SBP_ERR_NULL, "x, dy, dx, dw and workspace must be non-NULL");
+  {
+    const void* ps[] = {g->wq, g->wk, g->wv, g->wo, g->wgate, g->wup, g->wdown, g->g1, g->g2};
+    for (const void* p : ps) if (!p) return fail(SBP_ERR_NULL, "a gradient pointer is NULL");
+  }
+  if (dx == x || dx == dy) return fail(SBP_ERR_SHAPE, "dx may not alias x or dy");
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const LayerWs s_all = carve_layer(c, workspace);
+  if (workspace_bytes < s_all.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, s_all.bytes);
+  return layer_backward_impl(c, w, x, dy, dx, g, nullptr, s_all, (hipStream_t)hip_stream);
+}
+
+// ---- adapter mode ---------------------------------------------------------------------------------------------
+namespace {
+int32_t check_lora(const sbp_layer_cfg* c, const sbp_lora_adapters* ad) {
+  if (!ad) return fail(SBP_ERR_NULL, "adapters table is NULL");
+  if (ad->rank < 1 || ad->rank > LORA_PAD) return fail(SBP_ERR_SHAPE, "adapter rank must be in [1, %d]", LORA_PAD);
+  if (!std::isfinite(ad->scale)) return fail(SBP_ERR_SHAPE, "adapter scale must be finite");
+  if (c->grad_dtype != SBP_F32) return fail(SBP_ERR_UNSUPPORTED, "adapter gradients are fp32");
+  int n = 0;
+  for (int i = 0; i < 7; ++i) {
+    if ((ad->a[i] == nullptr) != (ad->b[i] == nullptr)) return fail(SBP_ERR_NULL, "adapter %d: A and B must be given together", i);
+    n += ad->a[i] != nullptr;
+  }
+  if (n == 0) return fail(SBP_ERR_NULL, "no matrix is adapted");
+  return SBP_OK;
+}
+struct LoraWs { LoraCtx ctx; sbp_layer_weights w_eff; void* bt[7]; sbp_layer_cfg layer_cfg; void* layer_ws; size_t layer_bytes; size_t bytes; };
+LoraWs carve_lora(const sbp_layer_cfg* c, const sbp_layer_weights* w, const sbp_lora_adapters* ad, void* ws) {
+  const size_t es = dtype_size(c->dtype);
+  const int d = c->hidden, F = c->mlp_width, qd = c->n_q_heads * c->head_dim, kd = c->n_kv_heads * c->head_dim;
+  const int outs[7] = {qd, kd, kd, d, F, F, d}, ins[7] = {d, d, d, qd, d, d, F};
+  const size_t cm = (size_t)std::min(c->chunk, c->seq_len);
+  Carver cv(ws);
+  LoraWs L{};
+  if (w) L.w_eff = *w;
+  const void** eff[7] = {&L.w_eff.wq, &L.w_eff.wk, &L.w_eff.wv, &L.w_eff.wo, &L.w_eff.wgate, &L.w_eff.wup, &L.w_eff.wdown};
+  LoraCtx& x = L.ctx;
+  x.n = 0;
+  for (int i = 0; i < 7; ++i) {
+    if (!ad->a[i]) continue;
+    const int j = x.n++;
+    x.which[j] = i; x.out_dim[j] = outs[i]; x.in_dim[j] = ins[i];
+    *eff[i] = cv.take_bytes((size_t)outs[i] * ins[i] * es);                      // W + s B A
+    x.a_pad[j] = cv.take_bytes((size_t)LORA_PAD * ins[i] * es);
+    x.b_pad[j] = cv.take_bytes((size_t)outs[i] * LORA_PAD * es);
+    L.bt[j] = cv.take_bytes((size_t)ad->rank * outs[i] * es);                    // s B^T, the merge GEMM's operand
+    x.da_pad[j] = cv.take<float>((size_t)LORA_PAD * ins[i]);
+    x.db_pad[j] = cv.take<float>((size_t)outs[i] * LORA_PAD);
+    x.P[j] = cv.take_bytes(cm * LORA_PAD * es);
+    x.Q[j] = cv.take_bytes(cm * LORA_PAD * es);
+  }
+  x.dg_sink = cv.take<float>((size_t)2 * d);
+  L.layer_cfg = *c;
+  L.layer_cfg.dw_group_rows = 1;          // no weight-gradient passes to group: one set of chunk buffers
+  L.layer_ws = cv.take_bytes(0);
+  L.layer_bytes = carve_layer(&L.layer_cfg, nullptr).bytes;
+  L.bytes = cv.off + L.layer_bytes;
+  return L;
+}
+}  // namespace
+
+size_t streambp_layer_lora_workspace_bytes(const sbp_layer_cfg* cfg, const sbp_lora_adapters* ad) {
+  if (check_layer_cfg(cfg) != SBP_OK || check_lora(cfg, ad) != SBP_OK) return 0;
+  return carve_lora(cfg, nullptr, ad, nullptr).bytes;
+}
+
+int32_t streambp_layer_lora_backward(const sbp_layer_cfg* c, const sbp_layer_weights* w, const sbp_lora_adapters* ad,
+                                     const void* x, const void* dy, void* dx, const sbp_lora_grads* g, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  int32_t rc = check_layer_cfg(c);
+  if (rc) return rc;
+  if ((rc = check_layer_ptrs(w))) return rc;
+  if ((rc = check_lora(c, ad))) return rc;
+  if (!x || !dy || !dx || !g || !workspace) return fail(SBP_ERR_NULL, "x, dy, dx, the gradient table and workspace must be non-NULL");
+  for (int i = 0; i < 7; ++i)
+    if (ad->a[i] && (!g->da[i] || !g->db[i])) return fail(SBP_ERR_NULL, "adapter %d: da and db must be non-NULL", i);
+  if (dx == x || dx == dy) return fail(SBP_ERR_SHAPE, "dx may not alias x or dy");
+  if ((uintptr_t)workspace & 255) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  const LoraWs L = carve_lora(c, w, ad, workspace);
+  if (workspace_bytes < L.bytes) return fail(SBP_ERR_WORKSPACE, "workspace too small: %zu < %zu", workspace_bytes, L.bytes);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int dt = c->dtype;
+  const size_t es = dtype_size(dt);
+  const void* base[7] = {w->wq, w->wk, w->wv, w->wo, w->wgate, w->wup, w->wdown};
+  const void* eff[7] = {L.w_eff.wq, L.w_eff.wk, L.w_eff.wv, L.w_eff.wo, L.w_eff.wgate, L.w_eff.wup, L.w_eff.wdown};
+  const LoraCtx& X = L.ctx;
+  t_gemm_scratch = nullptr; t_gemm_scratch_bytes = 0;
+  for (int j = 0; j < X.n; ++j) {
+    const int i = X.which[j], out = X.out_dim[j], in = X.in_dim[j], r = ad->rank;
+    // operands padded to the GEMM tile width, and the effective matrix W + s B A: a copy of W, then one pass that reads
+    // it, adds the rank-r product in fp32 and rounds once
+    HIPCHK(pad_matrix(dt, ad->a[i], r, in, false, 1.0f, X.a_pad[j], LORA_PAD, in, st));
+    HIPCHK(pad_matrix(dt, ad->b[i], out, r, false, 1.0f, X.b_pad[j], out, LORA_PAD, st));
+    HIPCHK(pad_matrix(dt, ad->b[i], r, out, true, ad->scale, L.bt[j], r, out, st));
+    HIPCHK(copy_bytes((void*)eff[i], base[i], (size_t)out * in * es, st));
+    HIPCHK(gemm(mk(L.bt[j], X.a_pad[j], (void*)eff[i], out, in, r, out, in, in, true, false, dt, dt, true), st));
+    HIPCHK(fill_zero(X.da_pad[j], (size_t)LORA_PAD * in * sizeof(float), st));
+    HIPCHK(fill_zero(X.db_pad[j], (size_t)out * LORA_PAD * sizeof(float), st));
+  }
+  const LayerWs s_all = carve_layer(&L.layer_cfg, L.layer_ws);
+  if ((rc = layer_backward_impl(&L.layer_cfg, &L.w_eff, x, dy, dx, nullptr, &X, s_all, st))) return rc;
+  for (int j = 0; j < X.n; ++j) {
+    const int i = X.which[j];
+    HIPCHK(add_scaled_block(X.da_pad[j], X.in_dim[j], ad->scale, g->da[i], ad->rank, X.in_dim[j], st));
+    HIPCHK(add_scaled_block(X.db_pad[j], LORA_PAD, ad->scale, g->db[i], X.out_dim[j], ad->rank, st));
   }
   return SBP_OK;
 }

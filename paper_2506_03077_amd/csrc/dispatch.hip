@@ -15,7 +15,7 @@ bool gemm_mfma_eligible(const GemmArgs& g);
 bool gemm_mfma_pair_ok(const GemmArgs& g);
 bool gemm_mfma_stats_ok(const GemmArgs& g);
 bool gemm_mfma_swiglu_ok(const GemmArgs& g);
-bool gemm_mfma_group_eligible(const GemmArgs* gs, int n);
+bool gemm_mfma_group_eligible(const GemmArgs* gs, int n, bool small_ok);
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n);
 hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st);
@@ -93,9 +93,9 @@ hipError_t gemm(const GemmArgs& g, hipStream_t st) {
   prof::Scope sc(prof::GEMM_GENERIC, 2.0 * g.M * g.N * g.K, g.rows_dev != nullptr, st);
   return gemm_generic(g, st);
 }
-hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st) {
+hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st, bool group_small) {
   if (!g_force_generic_gemm && gemm_mfma_seg_eligible(gs, n)) return gemm_mfma_seg(gs, n, st);   // same C: one pass over it
-  if (!g_force_generic_gemm && gemm_mfma_group_eligible(gs, n)) {
+  if (!g_force_generic_gemm && gemm_mfma_group_eligible(gs, n, group_small)) {
     return gemm_mfma_group(gs, n, st);
   }
   for (int i = 0; i < n; ++i) {

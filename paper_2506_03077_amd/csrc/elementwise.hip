@@ -475,6 +475,52 @@ hipError_t fill_zero(void* p, size_t bytes, hipStream_t st) {
 }
 
 // An id outside [0, vocab) is never used as an index: its row of x is zero and its row of dx is dropped.
+__global__ void copy16_k(uint4* __restrict__ d, const uint4* __restrict__ s, int64_t n16) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) d[i] = s[i];
+}
+__global__ void copy1_k(unsigned char* __restrict__ d, const unsigned char* __restrict__ s, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) d[i] = s[i];
+}
+hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  size_t n16 = bytes / 16, tail = bytes - n16 * 16;
+  if ((((uintptr_t)dst | (uintptr_t)src) & 15) != 0) { n16 = 0; tail = bytes; }
+  if (n16) copy16_k<<<ew_grid((int64_t)n16), 256, 0, st>>>((uint4*)dst, (const uint4*)src, (int64_t)n16);
+  if (tail) copy1_k<<<(unsigned)cdiv((int64_t)tail, 256), 256, 0, st>>>((unsigned char*)dst + n16 * 16, (const unsigned char*)src + n16 * 16, (int64_t)tail);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void pad_matrix_k(const T* __restrict__ src, int R, int C, int transposed, float scale, T* __restrict__ dst, int R2, int C2) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)R2 * C2) return;
+  const int r = (int)(i / C2), c = (int)(i % C2);
+  float v = 0.f;
+  if (r < R && c < C) v = scale * ldf(transposed ? src + (int64_t)c * R + r : src + (int64_t)r * C + c);
+  stf(dst + i, v);
+}
+hipError_t pad_matrix(int dt, const void* src, int R, int C, bool transposed, float scale, void* dst, int R2, int C2, hipStream_t st) {
+  const int64_t n = (int64_t)R2 * C2;
+  if (n == 0) return hipSuccess;
+  DISPATCH_DT(dt, T, (pad_matrix_k<T><<<(unsigned)cdiv(n, 256), 256, 0, st>>>((const T*)src, R, C, transposed ? 1 : 0, scale, (T*)dst, R2, C2)));
+  return hipGetLastError();
+}
+__global__ void add_scaled_block_k(const float* __restrict__ src, int64_t ld, float scale, float* __restrict__ dst, int R, int C) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)R * C) return;
+  const int r = (int)(i / C), c = (int)(i % C);
+  dst[i] += scale * src[(int64_t)r * ld + c];
+}
+hipError_t add_scaled_block(const float* src, int64_t ld, float scale, float* dst, int R, int C, hipStream_t st) {
+  const int64_t n = (int64_t)R * C;
+  if (n == 0) return hipSuccess;
+  add_scaled_block_k<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(src, ld, scale, dst, R, C);
+  return hipGetLastError();
+}
+
 template <typename T>
 __global__ void embedding_fwd_k(const int32_t* __restrict__ ids, const T* __restrict__ emb, T* __restrict__ x, int d, int vocab) {
   const int64_t row = blockIdx.x;

@@ -711,7 +711,7 @@ static int group_fold(const GemmArgs* gs, int n, int* owner /* [n]: index of the
   return n_out;
 }
 constexpr int MAX_BATCH = MAX_GROUP * MAX_GSEG;
-bool gemm_mfma_group_eligible(const GemmArgs* gs, int n) {
+bool gemm_mfma_group_eligible(const GemmArgs* gs, int n, bool small_ok) {
   if (n < 2 || n > MAX_BATCH) return false;
   int64_t tiles = 0;
   int owner[MAX_BATCH], nseg[MAX_BATCH] = {0};
@@ -725,7 +725,8 @@ bool gemm_mfma_group_eligible(const GemmArgs* gs, int n) {
   }
   // few tiles: per-problem launches with split-K fill the chip better - unless problems share an output, where one
   // launch with several reduction segments replaces several passes over it
-  return (tiles >= 200 || n_out < n) && tiles < (1 << 30);
+  // (small_ok: many skinny problems, none of which could fill the chip alone either)
+  return (tiles >= 200 || n_out < n || small_ok) && tiles < (1 << 30);
 }
 
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {

@@ -46,7 +46,8 @@ bool gemm_row_stats_supported(const GemmArgs& g);
 size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits);
 hipError_t gemm(const GemmArgs& g, hipStream_t st);
 // n independent GEMMs (distinct outputs); one grouped launch when the MFMA kernel can take them all
-hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st);
+// group_small: take the grouped launch also when the problems together have few output tiles (skinny problems)
+hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t st, bool group_small = false);
 // true when the bf16 MFMA kernel can take this problem (used by tests / tile accounting)
 bool gemm_uses_mfma(const GemmArgs& g);
 // force the generic kernel (debug / A-B tests)
@@ -104,6 +105,11 @@ hipError_t add_store(int dt, const float* a, const float* b, void* y, int64_t n,
 hipError_t kv_grad_finish(int dt, const float* dK, const float* dV, const float2* tab, void* dkc, void* dvc,
                           int rows, int H, int dh, hipStream_t st);
 hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t st);     // 16-byte aligned, bytes % 16 == 0 fast path
+// dst [R2, C2] (dt, dense) = zero-padded scale * src, src [R, C] (dt, dense) or its transpose (src [C, R]) - small matrices
+hipError_t pad_matrix(int dt, const void* src, int R, int C, bool transposed, float scale, void* dst, int R2, int C2, hipStream_t st);
+// dst [R, C] fp32 (dense) += scale * src[i * ld + j]
+hipError_t add_scaled_block(const float* src, int64_t ld, float scale, float* dst, int R, int C, hipStream_t st);
 // ids outside [0, vocab) are never used as an index: their x row is zero, their dx row is dropped
 hipError_t embedding_fwd(int dt, const int32_t* ids, const void* emb, void* x, int64_t rows, int d, int vocab, hipStream_t st);
 hipError_t embedding_bwd(int dt, const int32_t* ids, const void* dx, float* demb, int64_t rows, int d, int vocab, hipStream_t st);

@@ -179,6 +179,32 @@ def test_bad_mask_arguments_are_refused():
     assert sb.streambp_layer_workspace_bytes(sb.layer_cfg(sb.SBP_F32, 2, 64, 16, 64, 4, 4, 16, 172, window=8, seq_first=[0, 64])) > 0
 
 
+def test_adapter_mode_validation_and_workspace():
+    L = sb.lib()
+    big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
+    cfg = good_layer_cfg(**big)
+    ad = sb.LoraAdapters(32, 2.0, (C.c_void_p * 7)(*[256] * 7), (C.c_void_p * 7)(*[256] * 7))
+    need = L.streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(ad))
+    plain = sb.streambp_layer_workspace_bytes(good_layer_cfg(dw_group_rows=2048, **big))
+    p_lin = 3584 * 28 * 128 * 2 + 2 * 3584 * 4 * 128 + 3 * 3584 * 18944
+    # one chunk's buffers + one copy of the adapted matrices + the padded adapter operands / accumulators (rank padded to 256: a third of that)
+    assert plain + 2 * p_lin < need < plain + 2 * p_lin * 1.4
+    only_qv = sb.LoraAdapters(32, 2.0, (C.c_void_p * 7)(256, None, 256, None, None, None, None), (C.c_void_p * 7)(256, None, 256, None, None, None, None))
+    assert L.streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(only_qv)) < plain + 2 * (3584 * 3584 + 512 * 3584) * 2.0     # only the adapted matrices are copied
+    for bad in (sb.LoraAdapters(0, 1.0, ad.a, ad.b), sb.LoraAdapters(257, 1.0, ad.a, ad.b),
+                sb.LoraAdapters(8, float("nan"), ad.a, ad.b),
+                sb.LoraAdapters(8, 1.0, (C.c_void_p * 7)(256, *[None] * 6), (C.c_void_p * 7)(*[None] * 7)),     # A without B
+                sb.LoraAdapters(8, 1.0, (C.c_void_p * 7)(*[None] * 7), (C.c_void_p * 7)(*[None] * 7))):        # nothing adapted
+        assert L.streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(bad)) == 0
+    w = sb.LayerWeights(*[256] * 9)
+    g = sb.LoraGrads((C.c_void_p * 7)(*[256] * 7), (C.c_void_p * 7)(*[256] * 7))
+    assert L.streambp_layer_lora_backward(C.byref(cfg), C.byref(w), C.byref(ad), 256, 512, 768, C.byref(g), 1024, need - 1, None) == -4
+    g0 = sb.LoraGrads((C.c_void_p * 7)(*[256] * 6, None), (C.c_void_p * 7)(*[256] * 7))
+    assert L.streambp_layer_lora_backward(C.byref(cfg), C.byref(w), C.byref(ad), 256, 512, 768, C.byref(g0), 1024, need, None) == -1
+    bf = good_layer_cfg(grad_dtype=sb.SBP_BF16, **big)
+    assert L.streambp_layer_lora_backward(C.byref(bf), C.byref(w), C.byref(ad), 256, 512, 768, C.byref(g), 1024, need, None) == -3
+
+
 def test_fast_path_query_names_the_configs_that_leave_the_mfma_kernels():
     big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
     assert sb.streambp_layer_fast_path(good_layer_cfg(**big)) == 1
