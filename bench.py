@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC = {}     # kernel symbol -> (bytes per launch, file under profiles/)
 
 
-def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=True, n_layers=1):
+def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=True, n_layers=1, lora_rank=0, window=0):
     """Work the method must do (Sec. 3.2): 6*P per token for the linear maps (reforward, dX, dW), 14*dh per
     visible causal (query, key) pair per query head (4 forward + 10 backward), 6*d*V per row of the head.
     T = tokens per sequence, batch sequences (no attention across sequences), active_rows over the whole batch."""
@@ -42,7 +42,13 @@ def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=Tru
         Hq, Hkv, dh, F = (cfg[k] for k in ("n_q_heads", "n_kv_heads", "head_dim", "mlp_width"))
         p_lin = d * Hq * dh + 2 * d * Hkv * dh + Hq * dh * d + 3 * d * F
         linear = 6.0 * p_lin * T * batch * n_layers
-        attn = 14.0 * dh * Hq * (T * (T + 1) / 2.0) * batch * n_layers
+        if lora_rank:   # adapter mode: reforward and dX at the effective matrices, no dW; four rank-r products per adapted matrix
+            dims = 2 * (d + Hq * dh) + 2 * (d + Hkv * dh) + 3 * (d + F)        # sum of (in + out) over the seven matrices
+            linear = (4.0 * p_lin + 8.0 * lora_rank * dims) * T * batch * n_layers
+        pairs = T * (T + 1) / 2.0
+        if window and window < T:                                              # visible (query, key) pairs under a sliding window
+            pairs = window * (window + 1) / 2.0 + (T - window) * float(window)
+        attn = 14.0 * dh * Hq * pairs * batch * n_layers
     if has_head:
         V = cfg["vocab"]
         head_all = 6.0 * d * V * T * batch
@@ -99,6 +105,10 @@ def main():
                     help="fraction of every sequence, from its start, whose targets are ignored (default: 0 for 7b / stack - "
                          "SFT on all positions - and 0.25 for lmhead / grpo, as their workloads say)")
     ap.add_argument("--layers", type=int, default=None, help="stack workload: number of layers (default 28)")
+    ap.add_argument("--lora-rank", type=int, default=0,
+                    help="7b / llama_layer / grpo: run the layer in adapter mode (rank-R adapters on all seven matrices, adapter "
+                         "gradients only; the paper's setting for its largest model is R = 32)")
+    ap.add_argument("--window", type=int, default=0, help="sliding-window attention in the layer (0 = plain causal)")
     ap.add_argument("--grad-dtype", choices=("f32", "bf16"), default="f32",
                     help="element type of the weight-gradient accumulators (default fp32; bf16 is the paper's own training "
                          "setting, App. D (experiment setup), and halves the read-modify-write traffic on dW)")
@@ -150,7 +160,7 @@ def main():
     prompt_frac = args.prompt_frac if args.prompt_frac is not None else (0.25 if wl in ("lmhead", "grpo") else 0.0)
     gdt = sb.SBP_BF16 if args.grad_dtype == "bf16" else sb.SBP_F32
     default_shape = (wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c and B == cfg["batch"]
-                     and prompt_frac == 0.0 and gdt == sb.SBP_F32 and args.dw_group_rows in (0, 8192))   # what the profiles cover
+                     and not args.lora_rank and not args.window and prompt_frac == 0.0 and gdt == sb.SBP_F32 and args.dw_group_rows in (0, 8192))   # what the profiles cover
     d = cfg["hidden"]
     bf = torch.bfloat16
 
@@ -176,7 +186,8 @@ def main():
 
     if has_layer:
         Hq, Hkv, dh, F = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["mlp_width"]
-        lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F, grad_dtype=gdt, dw_group_rows=args.dw_group_rows)
+        lcfg = sb.layer_cfg(sb.SBP_BF16, B, T, c, d, Hq, Hkv, dh, F, grad_dtype=gdt, dw_group_rows=args.dw_group_rows,
+                            window=args.window)
         assert sb.streambp_layer_fast_path(lcfg) == 1, sb.streambp_last_error()
         ws_bytes["layer_workspace"] = sb.streambp_layer_workspace_bytes(lcfg)
     if has_head:
@@ -225,6 +236,12 @@ def main():
         if has_layer:
             w = layer_weights()
             x = normal((B, T, d), 1.0)          # layer input (the checkpoint)
+            if args.lora_rank:
+                r = args.lora_rank
+                adapters = {n: (normal((r, w[n].shape[1]), 0.02), normal((w[n].shape[0], r), 0.02)) for n in sb.MATRIX_NAMES}
+                ws_bytes["layer_workspace"] = sb.streambp_layer_lora_workspace_bytes(lcfg, adapters, r, 2.0)
+                da = {n: torch.zeros(ab[0].shape, dtype=torch.float32, device=dev) for n, ab in adapters.items()}
+                db = {n: torch.zeros(ab[1].shape, dtype=torch.float32, device=dev) for n, ab in adapters.items()}
             ws_layer = torch.empty(ws_bytes["layer_workspace"], dtype=torch.uint8, device=dev)
             dw = sb.new_layer_grads(w, gdt)
             dx = torch.empty_like(x)
@@ -241,7 +258,10 @@ def main():
                                                loss=loss, n_active=n_active, workspace=ws_head)
             if has_layer:
                 # the head's dH is the upstream gradient of the layer (the final norm is left out of the timed step)
-                sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
+                if args.lora_rank:
+                    sb.streambp_layer_lora_backward(lcfg, w, adapters, args.lora_rank, 2.0, x, dh_out, dx=dx, da=da, db=db, workspace=ws_layer)
+                else:
+                    sb.streambp_layer_backward(lcfg, w, x, dh_out, dx=dx, dw=dw, workspace=ws_layer)
 
     if args.pmc_calibrate:   # 2^28 fp32 elements: the add kernel fetches 1 GiB and writes 1 GiB
         ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -272,7 +292,7 @@ def main():
     if has_layer:
         assert bool(torch.isfinite(dx.float()).all())
 
-    fl = algorithmic_flops(cfg, T, n_act, B, has_layer, has_head, L)
+    fl = algorithmic_flops(cfg, T, n_act, B, has_layer, has_head, L, args.lora_rank, args.window)
     names = {"7b": "7B-shaped decoder layer (d=3584, 28q/4kv x128, F=18944) + LM head (V=152064)",
              "llama_layer": "Llama-style decoder layer (d=4096, 32q/8kv x128, F=14336), upstream gradient N(0,1e-3)",
              "lmhead": "LM head + cross-entropy (d=3584, V=152064)",
@@ -288,6 +308,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{names[wl]}, T={T}, chunk={c}, head chunk={hc_rows}, batch {B}, {loss_on}, "
                                f"{args.grad_dtype} weight-gradient accumulators"
+                               + (f", layer in adapter mode (rank {args.lora_rank} on all seven matrices, adapter gradients only)" if args.lora_rank else "")
+                               + (f", sliding window {args.window}" if args.window else "")
                                + (f", weight gradients added once per {args.dw_group_rows} rows" if args.dw_group_rows else ""),
                    "algorithmic_tflop_per_step": fl["total"] / 1e12,
                    "achieved_tflops": fl["total"] / dt / 1e12,
