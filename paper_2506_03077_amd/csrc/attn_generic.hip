@@ -8,6 +8,7 @@
 // lse = -inf and sends no gradient.  No atomics: every output element has
 // exactly one owner, so results are reproducible.
 #include "launch.h"
+#include "device.h"
 
 namespace sbp {
 

@@ -36,6 +36,7 @@
 //            prefix accumulators (every element has one owner: no atomics,
 //            reproducible).
 #include "launch.h"
+#include "device.h"
 
 #include <type_traits>
 

@@ -3,6 +3,7 @@
 // All are HBM-bound: one pass over their operands, 128-bit accesses where the
 // row width allows, fp32 arithmetic with wavefront (64-lane) reductions.
 #include "launch.h"
+#include "device.h"
 #include <algorithm>
 
 namespace sbp {

@@ -3,6 +3,7 @@
 // fp32 configuration and for shapes the MFMA kernel does not take (widths that
 // are not multiples of its tile); it is not a performance path.
 #include "launch.h"
+#include "device.h"
 
 namespace sbp {
 

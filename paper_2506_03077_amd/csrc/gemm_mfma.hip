@@ -31,6 +31,7 @@
 //  * Weight gradients: C += by no-return fp32 atomic adds (one add per element per launch), or into a bf16 C by
 //    paired loads / stores; several reduction segments (operand pairs) per output tile; grouped launches.
 #include "launch.h"
+#include "device.h"
 
 #include <algorithm>
 

@@ -5,6 +5,7 @@
 // reduced every 256-column block of the row to a (max, sum of exp) pair; the label
 // gather z[target] and the ignore mask are integer-indexed and exact.
 #include "launch.h"
+#include "device.h"
 #include <algorithm>
 
 namespace sbp {
