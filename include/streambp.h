@@ -333,7 +333,8 @@ const char *streambp_version(void);
 const char *streambp_last_error(void);
 /* Which kernels a configuration gets (host arithmetic only).  1: every GEMM and the attention of the configuration
  * run on the bf16 MFMA kernels (needs bf16 storage, head_dim 128 and hidden, n_q_heads*head_dim, n_kv_heads*head_dim,
- * mlp_width - for the head: hidden and vocab - multiples of 256, 16-byte aligned tensors).  0: some of it runs on the
+ * mlp_width - for the head: hidden and vocab - multiples of 64, 16-byte aligned tensors; widths that are not multiples
+ * of the 256-wide output tile, such as a 151936-word vocabulary, run with a masked last tile).  0: some of it runs on the
  * shape-agnostic fp32-ALU kernels, a correctness path that is orders of magnitude slower (streambp_last_error() says
  * which dimension is the reason); nothing is refused.  Negative: the configuration itself is invalid. */
 int32_t streambp_layer_fast_path(const sbp_layer_cfg *cfg);

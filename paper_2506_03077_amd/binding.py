@@ -446,8 +446,9 @@ def debug_gemm(A, B, C_out, M, N, K, ta, tb, acc=False, scratch=None, stream=Non
     ran, 0 if the shape-agnostic one did.  A(m,k) = A[k,m] if ta else A[m,k]; B(k,n) = B[n,k] if tb else B[k,n].
     row_stats: optional fp32 [M, N/256, 2] output, (max, sum of exp(c - max)) of every row over every block of 256 columns
     (MFMA store form C = A B^T with fp32 C only; the launch fails where that kernel cannot take the problem)."""
+    assert C_out.is_cuda and C_out.stride(-1) == 1      # C may be a column slice of a wider buffer (ldc = its row stride)
     rc = lib().streambp_debug_gemm(M, N, K, int(ta), int(tb), _dt_code(A), _dt_code(C_out), int(acc), _ptr(A), _ptr(B),
-                                   _ptr(C_out), A.stride(0), B.stride(0), C_out.stride(0), _ptr(scratch),
+                                   C_out.data_ptr(), A.stride(0), B.stride(0), C_out.stride(0), _ptr(scratch),
                                    0 if scratch is None else scratch.numel() * scratch.element_size(), _stream(stream),
                                    _ptr(A2), _ptr(B2), _ptr(row_stats))
     if rc < 0:

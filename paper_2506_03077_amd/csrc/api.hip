@@ -563,7 +563,7 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   h.dw_group = dw_group_for(cm, c->dw_group_rows);
   for (int g = 0; g < h.dw_group; ++g) h.dz[g] = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
   h.row_loss = cv.take<float>(cm);
-  h.n_stat = c->vocab / GEMM_STAT_COLS;
+  h.n_stat = (int)cdiv(c->vocab, GEMM_STAT_COLS);
   h.stats = cv.take<float2>(cm * (size_t)h.n_stat);
   h.seq_weight = cv.take<float>(c->batch);
   h.ell = cv.take<float>(1);
@@ -708,8 +708,9 @@ int32_t streambp_attn_chunk_backward(const sbp_attn_cfg* c, const void* q, const
 }
 
 // Which kernels a configuration gets.  The bf16 MFMA GEMMs need every matrix dimension of the layer (hidden, the q and
-// k/v widths, mlp_width - resp. hidden and vocab for the head) to be a multiple of 256, the MFMA attention head_dim 128;
-// anything else runs on the shape-agnostic fp32-ALU kernels, which are a correctness path and orders of magnitude slower.
+// k/v widths, mlp_width - resp. hidden and vocab for the head) to be a multiple of 64 (the reduction step; output tiles
+// are 256 wide with a masked ragged last tile), the MFMA attention head_dim 128; anything else runs on the
+// shape-agnostic fp32-ALU kernels, which are a correctness path and orders of magnitude slower.
 int32_t streambp_layer_fast_path(const sbp_layer_cfg* c) {
   if (int32_t rc = check_layer_cfg(c)) return rc;
   if (c->dtype != SBP_BF16) return fail(0, "fp32 storage: the shape-agnostic kernels are the only path"), 0;
@@ -717,15 +718,15 @@ int32_t streambp_layer_fast_path(const sbp_layer_cfg* c) {
   if (c->head_dim != 128) return fail(0, "head_dim %d: the MFMA attention kernels take 128 only", c->head_dim), 0;
   const int dims[4] = {c->hidden, qd, kd, c->mlp_width};
   const char* names[4] = {"hidden", "n_q_heads*head_dim", "n_kv_heads*head_dim", "mlp_width"};
-  for (int i = 0; i < 4; ++i)
-    if (dims[i] % 256) return fail(0, "%s = %d is not a multiple of 256: its GEMMs leave the MFMA kernels", names[i], dims[i]), 0;
+  for (int i = 0; i < 4; ++i)   // every width is the reduction length of some GEMM of the layer
+    if (dims[i] % 64) return fail(0, "%s = %d is not a multiple of 64: its GEMMs leave the MFMA kernels", names[i], dims[i]), 0;
   return 1;
 }
 int32_t streambp_lmhead_fast_path(const sbp_head_cfg* c) {
   if (int32_t rc = check_head_cfg(c)) return rc;
   if (c->dtype != SBP_BF16) return fail(0, "fp32 storage: the shape-agnostic kernels are the only path"), 0;
-  if (c->hidden % 256) return fail(0, "hidden = %d is not a multiple of 256: the head's GEMMs leave the MFMA kernels", c->hidden), 0;
-  if (c->vocab % 256) return fail(0, "vocab = %d is not a multiple of 256: the head's GEMMs leave the MFMA kernels", c->vocab), 0;
+  if (c->hidden % 64) return fail(0, "hidden = %d is not a multiple of 64: the head's GEMMs leave the MFMA kernels", c->hidden), 0;
+  if (c->vocab % 64) return fail(0, "vocab = %d is not a multiple of 64: the head's GEMMs leave the MFMA kernels", c->vocab), 0;
   return 1;
 }
 int64_t streambp_generic_launches(void) { return (int64_t)generic_bf16_launches(); }

@@ -22,7 +22,8 @@
 //    writes lane-linear, the swizzle is applied on the global-address side.
 //  * Workgroups are renumbered so that each XCD (own L2) works on a contiguous
 //    band of output tiles that share operand panels.
-//  * Ragged M (last chunk) is handled by clamping row loads and masking stores;
+//  * Ragged M (last chunk) and ragged N (an output width that is a multiple of 8 but not of 256, e.g. a 151936-word
+//    vocabulary) are handled by clamping loads and masking stores;
 //    ragged K in the TN form (chunk rows) by clamping loads and zeroing the A
 //    fragments of the out-of-range reduction rows.
 //  * Optional split-K (a power of two, for outputs with too few tiles to fill the chip): partial tiles go to an
@@ -70,7 +71,7 @@ __device__ __forceinline__ int mnmaj_off(int krow, int col /*element*/) {
 
 // Byte offset, relative to the tile's corner element, of load i (0..LOADS_PER_THREAD-1) of this thread's share.
 //   KMAJ : corner = (row r0, column k0); rows clamped so that r0 + row <= r_max
-//   MNMAJ: corner = (k-row k0, column r0); k-rows clamped so that k0 + krow <= k_max
+//   MNMAJ: corner = (k-row k0, column r0); k-rows clamped so that k0 + krow <= k_max, columns so that r0 + col <= r_max
 template <bool MNMAJ>
 __device__ __forceinline__ uint32_t load_offset(int i, int64_t ld, int r0, int r_max, int k0, int k_max) {
   const int id = i * NTHREADS + (int)threadIdx.x;   // 16-byte slot in the tile, lane-linear within a wave
@@ -81,7 +82,10 @@ __device__ __forceinline__ uint32_t load_offset(int i, int64_t ld, int r0, int r
   } else {
     const int krow = id >> 5, p16 = id & 31;
     const int c16 = ((((p16 >> 2) ^ (krow & 7)) << 2) | (p16 & 3));
-    return (uint32_t)(((int64_t)(min(k0 + krow, k_max) - k0) * ld + c16 * 8) * 2);
+    // columns past the operand's last one (a ragged last tile; widths are multiples of 8) re-read its last 8 columns:
+    // finite duplicates whose products land in rows / columns of C that the epilogue masks
+    const int col = min(c16 * 8, r_max - r0 - 7);
+    return (uint32_t)(((int64_t)(min(k0 + krow, k_max) - k0) * ld + col) * 2);
   }
 }
 
@@ -329,8 +333,9 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
           const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1 /* quad_perm [1,0,3,2] */, 0xf, 0xf, false));
           lo[rp][j] = odd ? got : keep;
           hi[rp][j] = odd ? keep : got;
-          const int64_t idx = (int64_t)row * ldc + n0 + wn0 + j * 32 + (lane & 31) - (odd ? 1 : 0);
-          if (row < M) old[rp][j] = *(const bf16x2*)(Cb + idx);
+          const int col = n0 + wn0 + j * 32 + (lane & 31) - (odd ? 1 : 0);     // even column of the pair (N is a multiple of 8)
+          const int64_t idx = (int64_t)row * ldc + col;
+          if (row < M && col < N) old[rp][j] = *(const bf16x2*)(Cb + idx);
         }
       }
 #pragma unroll
@@ -339,11 +344,12 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
         const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3) + (odd ? 1 : 0);
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-          const int64_t idx = (int64_t)row * ldc + n0 + wn0 + j * 32 + (lane & 31) - (odd ? 1 : 0);
+          const int col = n0 + wn0 + j * 32 + (lane & 31) - (odd ? 1 : 0);
+          const int64_t idx = (int64_t)row * ldc + col;
           bf16x2 v;
           v[0] = (bf16_t)((float)old[rp][j][0] + lo[rp][j]);
           v[1] = (bf16_t)((float)old[rp][j][1] + hi[rp][j]);
-          if (row < M) *(bf16x2*)(Cb + idx) = v;
+          if (row < M && col < N) *(bf16x2*)(Cb + idx) = v;
         }
       }
     }
@@ -363,13 +369,25 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       const int row_l = wm0 + i * 32 + (lane & 31);
-      if (m0 + row_l < M) {
-        float* crow = Cf + (int64_t)(m0 + row_l) * ldc + n0 + wn0 + 4 * (lane >> 5);
+      const int col0 = n0 + wn0 + 4 * (lane >> 5);               // first of the lane's columns; quads at + j * 32 + 8 * q
+      if (n0 + BN > N) {                                         // ragged last column tile: columns past N take no part
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
           for (int q = 0; q < 4; ++q)
-            *(float4*)(crow + j * 32 + 8 * q) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            if (col0 + j * 32 + 8 * q >= N) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = -INFINITY;
+            }
+      }
+      if (m0 + row_l < M) {
+        float* crow = Cf + (int64_t)(m0 + row_l) * ldc + col0;
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (col0 + j * 32 + 8 * q < N)
+              *(float4*)(crow + j * 32 + 8 * q) = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
       }
       float mx = acc[i][0][0];
 #pragma unroll
@@ -377,11 +395,12 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      const float mref = mx == -INFINITY ? 0.0f : mx;            // a wave whose 64 columns all lie past N: sum 0, not NaN
       float se = 0.f;
 #pragma unroll
       for (int j = 0; j < FN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) se += __builtin_amdgcn_exp2f((acc[i][j][r] - mx) * LOG2E);   // difference first: exact near the maximum
+        for (int r = 0; r < 16; ++r) se += __builtin_amdgcn_exp2f((acc[i][j][r] - mref) * LOG2E);   // difference first: exact near the maximum
       se += __shfl_xor(se, 32, WAVE);
       if (lane < 32) part[(wave % NWAVE_N) * BM + row_l] = make_float2(mx, se);
     }
@@ -392,10 +411,11 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
       for (int w = 1; w < NWAVE_N; ++w) {
         const float2 q = part[w * BM + threadIdx.x];
         const float m2 = fmaxf(p.x, q.x);
-        p.y = p.y * __builtin_amdgcn_exp2f((p.x - m2) * LOG2E) + q.y * __builtin_amdgcn_exp2f((q.x - m2) * LOG2E);
+        if (q.x != -INFINITY)                                    // (a wave past N contributes nothing; wave 0 always holds valid columns)
+          p.y = p.y * __builtin_amdgcn_exp2f((p.x - m2) * LOG2E) + q.y * __builtin_amdgcn_exp2f((q.x - m2) * LOG2E);
         p.x = m2;
       }
-      stats[(int64_t)(m0 + (int)threadIdx.x) * (N / BN) + tn] = p;
+      stats[(int64_t)(m0 + (int)threadIdx.x) * ((N + BN - 1) / BN) + tn] = p;
     }
     return;
   }
@@ -415,8 +435,9 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
       for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          gv[j][q] = *(const bf16x4e*)(sw.gate + base + j * 32 + 8 * q);
-          uv[j][q] = *(const bf16x4e*)(sw.up + base + j * 32 + 8 * q);
+          const bool in = n0 + wn0 + 4 * (lane >> 5) + j * 32 + 8 * q < N;
+          gv[j][q] = in ? *(const bf16x4e*)(sw.gate + base + j * 32 + 8 * q) : bf16x4e{};
+          uv[j][q] = in ? *(const bf16x4e*)(sw.up + base + j * 32 + 8 * q) : bf16x4e{};
         }
 #pragma unroll
       for (int j = 0; j < FN; ++j)
@@ -432,6 +453,7 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
             du4[e] = (bf16_t)(d * z * sg);
           }
           const int64_t idx = base + j * 32 + 8 * q;
+          if (n0 + wn0 + 4 * (lane >> 5) + j * 32 + 8 * q >= N) continue;
           if (sw.act) *(bf16x4e*)(sw.act + idx) = a4;
           *(bf16x4e*)(sw.gate + idx) = dg4;
           *(bf16x4e*)(sw.up + idx) = du4;
@@ -447,7 +469,9 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
       if (row < M) {
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-          const int64_t idx = (int64_t)row * ldc + n0 + wn0 + j * 32 + (lane & 31);
+          const int col = n0 + wn0 + j * 32 + (lane & 31);
+          if (col >= N) continue;                                // ragged last column tile
+          const int64_t idx = (int64_t)row * ldc + col;
           const float v = acc[i][j][r];
           if (MODE == 1) Cb[idx] = (bf16_t)v;
           else if (MODE == 2) unsafeAtomicAdd(&Cf[idx], v);   // one add per element per launch: same rounding as a
@@ -466,7 +490,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
                                                         const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2,
                                                         float2* __restrict__ row_stats, SwigluFuse sw) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN, n_tiles = tiles_m * tiles_n;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN, n_tiles = tiles_m * tiles_n;
   int tm, tn, split = 0;
   if (MODE == 3 && xcds_per_split > 0) {
     // Split-K with each slice of the reduction pinned to its own group of XCDs (the grid is 1-D: n_tiles x splits
@@ -509,7 +533,7 @@ template <bool C_BF16>
 __global__ __launch_bounds__(NTHREADS) void gemm_mfma_seg_k(const SegLaunch sl, void* __restrict__ C, int M, int N, int64_t lda,
                                                             int64_t ldb, int64_t ldc) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = N / BN;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   int tm, tn;
   band_coords((int)blockIdx.x, tiles_m, tiles_n, band_height(tiles_m, tiles_m * tiles_n, false), tm, tn);
   KSegments segs;
@@ -583,10 +607,12 @@ __global__ void splitk_reduce_k(const float* __restrict__ part, void* __restrict
 bool gemm_mfma_eligible(const GemmArgs& g) {
   if (g.in_dt != DT_BF16) return false;
   if (g.acc && g.out_dt != DT_F32 && !(g.out_dt == DT_BF16 && g.ta && !g.tb)) return false;   // bf16 C += : dW form only
-  if (g.M < 1 || g.N < BN || g.K < 1) return false;
-  if (g.N % BN != 0) return false;
+  // Output widths need not be multiples of the 256-wide tile: a ragged last tile clamps its loads and masks its stores
+  // (16-byte granules: multiples of 8 elements), e.g. a 151936-word vocabulary = 593.5 tiles.
+  if (g.M < 1 || g.N < 8 || g.K < 1) return false;
+  if (g.N % 8 != 0) return false;
   if (g.ta && !g.tb) {                       // TN: both operands reduction-major; ragged K allowed
-    if (g.M % BM != 0) return false;
+    if (g.M % 8 != 0) return false;
   } else if (!g.ta) {                        // NT / NN
     if (g.K % BK != 0) return false;
   } else {
@@ -622,7 +648,7 @@ constexpr int MAX_SPLITS = 8;
 // the fabric traffic: an XCD runs 32 tiles at a time whatever the split, and those pull (rows + columns) operand
 // panels per K step.
 int gemm_mfma_splits(const GemmArgs& g) {
-  const int64_t tiles = cdiv(g.M, BM) * (g.N / BN);
+  const int64_t tiles = cdiv(g.M, BM) * cdiv(g.N, BN);
   const int k_tiles = (int)cdiv(g.K, BK);
   if (tiles >= 200 || k_tiles < 16 || (g.ta && g.rows_dev)) return 1;
   int s = 1;
@@ -635,7 +661,7 @@ size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits) {
 }
 
 hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
-  const int tiles_m = (int)cdiv(g.M, BM), tiles_n = g.N / BN;
+  const int tiles_m = (int)cdiv(g.M, BM), tiles_n = (int)cdiv(g.N, BN);
   int splits = gemm_mfma_splits(g);
   if (g.scratch == nullptr || g.ldc != g.N || g.row_stats || g.swiglu_gate) splits = 1;
   while (splits > 1 && g.scratch_bytes < (size_t)splits * g.M * g.ldc * sizeof(float)) splits /= 2;   // what the scratch holds
@@ -722,7 +748,7 @@ bool gemm_mfma_group_eligible(const GemmArgs* gs, int n, bool small_ok) {
     if (!gemm_mfma_eligible(gs[i]) || gs[i].rows_dev || gs[i].A2) return false;
     if (gs[i].ta != gs[0].ta || gs[i].tb != gs[0].tb || gs[i].out_dt != gs[0].out_dt || gs[i].acc != gs[0].acc) return false;
     if (++nseg[owner[i]] > MAX_GSEG) return false;
-    if (owner[i] == i) tiles += cdiv(gs[i].M, BM) * (gs[i].N / BN);
+    if (owner[i] == i) tiles += cdiv(gs[i].M, BM) * cdiv(gs[i].N, BN);
   }
   // few tiles: per-problem launches with split-K fill the chip better - unless problems share an output, where one
   // launch with several reduction segments replaces several passes over it
@@ -741,7 +767,7 @@ hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st) {
       GroupProblem& p = ga.p[np++];
       p.C = gs[i].C; p.M = gs[i].M; p.N = gs[i].N; p.lda = gs[i].lda; p.ldb = gs[i].ldb; p.ldc = gs[i].ldc;
       p.nseg = 0;
-      p.tiles_m = (int)cdiv(gs[i].M, BM); p.tiles_n = gs[i].N / BN; p.tile_begin = tiles;
+      p.tiles_m = (int)cdiv(gs[i].M, BM); p.tiles_n = (int)cdiv(gs[i].N, BN); p.tile_begin = tiles;
       tiles += p.tiles_m * p.tiles_n;
     }
     GroupProblem& p = ga.p[slot[owner[i]]];
@@ -794,7 +820,7 @@ hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st) {
     bounded = bounded || gs[i].rows_dev != nullptr;
   }
   const GemmArgs& g = gs[0];
-  const int tiles = (int)cdiv(g.M, BM) * (g.N / BN);
+  const int tiles = (int)cdiv(g.M, BM) * (int)cdiv(g.N, BN);
   prof::Scope sc(prof::GEMM_SEG, work, bounded, st);
   if (g.out_dt == DT_BF16) gemm_mfma_seg_k<true><<<tiles, NTHREADS, 0, st>>>(sl, g.C, g.M, g.N, g.lda, g.ldb, g.ldc);
   else gemm_mfma_seg_k<false><<<tiles, NTHREADS, 0, st>>>(sl, g.C, g.M, g.N, g.lda, g.ldb, g.ldc);

@@ -28,7 +28,7 @@ struct GemmArgs {
   const void* A2 = nullptr;
   const void* B2 = nullptr;
   // Optional row statistics of the output (store form C = A B^T with fp32 C, MFMA kernel only: ask
-  // gemm_row_stats_supported first): row_stats[m * (N / GEMM_STAT_COLS) + t] = (max, sum of exp(c - max)) of row m
+  // gemm_row_stats_supported first): row_stats[m * ceil(N / GEMM_STAT_COLS) + t] = (max, sum of exp(c - max)) of row m
   // over the columns [t * GEMM_STAT_COLS, (t + 1) * GEMM_STAT_COLS), taken from the fp32 accumulators.
   float2* row_stats = nullptr;
   // Optional fused SwiGLU adjoint (store form C = A B with the same row-major [M, N] layout and leading dimension for

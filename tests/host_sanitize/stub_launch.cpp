@@ -41,12 +41,12 @@ static void touch_gemm(const GemmArgs& g) {
   } else {
     wr(g.C, c_el * es(g.out_dt));
   }
-  if (g.row_stats) wr(g.row_stats, (size_t)g.M * (g.N / GEMM_STAT_COLS) * sizeof(float2));
+  if (g.row_stats) wr(g.row_stats, (size_t)g.M * cdiv(g.N, GEMM_STAT_COLS) * sizeof(float2));
   if (g.rows_dev) rd(g.rows_dev, sizeof(int));
   // split-K partial slices: at most what gemm_scratch_bytes promises for 4 slices of a dense C
   if (g.scratch && g.ldc == g.N) wr(g.scratch, std::min(g.scratch_bytes, (size_t)4 * g.M * g.N * sizeof(float)));
 }
-bool gemm_row_stats_supported(const GemmArgs& g) { return g.in_dt == DT_BF16 && !g.ta && g.tb && g.out_dt == DT_F32 && g.N % 256 == 0 && g.K % 64 == 0; }
+bool gemm_row_stats_supported(const GemmArgs& g) { return g.in_dt == DT_BF16 && !g.ta && g.tb && g.out_dt == DT_F32 && g.N % 8 == 0 && g.K % 64 == 0; }
 size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits) { return (size_t)std::min(max_splits, 8) * max_m * max_n * sizeof(float); }
 hipError_t gemm(const GemmArgs& g, hipStream_t) { touch_gemm(g); return hipSuccess; }
 hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t, bool) { for (int i = 0; i < n; ++i) touch_gemm(gs[i]); return hipSuccess; }

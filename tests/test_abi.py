@@ -208,13 +208,15 @@ def test_adapter_mode_validation_and_workspace():
 def test_fast_path_query_names_the_configs_that_leave_the_mfma_kernels():
     big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
     assert sb.streambp_layer_fast_path(good_layer_cfg(**big)) == 1
-    assert sb.streambp_layer_fast_path(good_layer_cfg(**dict(big, mlp_width=18944 + 64))) == 0
+    assert sb.streambp_layer_fast_path(good_layer_cfg(**dict(big, mlp_width=18944 + 64))) == 1      # ragged last tile: still MFMA
+    assert sb.streambp_layer_fast_path(good_layer_cfg(**dict(big, mlp_width=18944 + 32))) == 0
     assert "mlp_width" in sb.streambp_last_error()
     assert sb.streambp_layer_fast_path(good_layer_cfg(**dict(big, head_dim=64, n_q_heads=56, n_kv_heads=8))) == 0
     assert sb.streambp_layer_fast_path(good_layer_cfg()) == 0                       # fp32 storage
     assert sb.streambp_layer_fast_path(good_layer_cfg(chunk=0)) == -2
     assert sb.streambp_lmhead_fast_path(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 152064)) == 1
-    assert sb.streambp_lmhead_fast_path(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 151936)) == 0   # 593.5 x 256
+    assert sb.streambp_lmhead_fast_path(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 151936)) == 1   # 593.5 x 256: masked last tile
+    assert sb.streambp_lmhead_fast_path(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 50257)) == 0
     assert "vocab" in sb.streambp_last_error()
     assert sb.streambp_generic_launches() >= 0
 

@@ -161,6 +161,79 @@ def test_weight_gradient_into_bf16_accumulator():
     assert_close(host(Cd), want, 4e-3, "segmented dW into bf16")
 
 
+def run_wide(M, N, K, ta, tb, out="f32", acc=False, seed=0, pad=24):
+    """Like run(), with C a column slice of a wider buffer: the columns past N must come back untouched."""
+    rng = np.random.default_rng(seed)
+    A = synth.to_storage(rng.normal(size=(K, M) if ta else (M, K)), "bf16")
+    B = synth.to_storage(rng.normal(size=(N, K) if tb else (K, N)), "bf16")
+    C0 = synth.to_storage(rng.normal(size=(M, N)), out) if acc else np.zeros((M, N), np.float32)
+    want = (A.T if ta else A).astype(np.float64) @ (B.T if tb else B).astype(np.float64) + C0
+    tdt = torch.bfloat16 if out == "bf16" else torch.float32
+    full = torch.full((M, N + pad), -7.0, device="cuda", dtype=tdt)
+    if acc:
+        full[:, :N] = dev(C0, out)
+    scratch = torch.empty(8 * M * N, dtype=torch.float32, device="cuda")
+    used = sb.debug_gemm(dev(A, "bf16"), dev(B, "bf16"), full[:, :N], M, N, K, ta, tb, acc, scratch)
+    torch.cuda.synchronize()
+    assert used == 1, "the MFMA kernel must take ragged output widths"
+    assert torch.all(full[:, N:] == -7.0), "written past the last column"
+    assert_close(host(full[:, :N]), want, 4e-3 if out == "bf16" else 2e-5, f"C M={M} N={N} K={K} ta={ta} tb={tb} out={out} acc={acc}")
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+@pytest.mark.parametrize("N", [8, 128, 264, 648])
+def test_mfma_ragged_output_width(ta, tb, N):
+    # output widths that are multiples of 8 but not of the 256-wide tile (a 151936-word vocabulary is 593.5 tiles): the
+    # last column tile clamps its loads and masks its stores; in the weight-gradient form the rows are ragged too
+    M = 264 if ta else 300
+    K = 200 if ta else 192
+    run_wide(M, N, K, ta, tb, out="f32", seed=N)
+    run_wide(M, N, K, ta, tb, out="bf16", seed=N + 1)
+    run_wide(M, N, K, ta, tb, out="f32", acc=True, seed=N + 2)
+    if ta:
+        run_wide(M, N, K, ta, tb, out="bf16", acc=True, seed=N + 3)
+        run_wide(8, N, 100, ta, tb, out="f32", acc=True, seed=N + 4)          # eight rows of a ragged weight gradient
+
+
+def test_mfma_ragged_output_width_split_k_pairs_and_segments():
+    run_wide(256, 264, 8192, False, True, seed=31)                     # two column tiles, the second 8 wide, eight K slices
+    run_wide(300, 392, 4096, False, False, out="bf16", seed=32)
+    run_wide(264, 392, 4000, True, False, acc=True, seed=33)
+    rng = np.random.default_rng(34)
+    M, N, Ks = 520, 392, (300, 200, 77)                                # segmented weight gradient, ragged in both directions
+    As = [synth.to_storage(rng.normal(size=(K, M)), "bf16") for K in Ks]
+    Bs = [synth.to_storage(rng.normal(size=(K, N)), "bf16") for K in Ks]
+    for out in ("f32", "bf16"):
+        C0 = synth.to_storage(rng.normal(size=(M, N)), out)
+        want = C0.astype(np.float64) + sum(A.T.astype(np.float64) @ B.astype(np.float64) for A, B in zip(As, Bs))
+        Cd = dev(C0, out)
+        used = sb.debug_gemm_dw_segments([dev(a, "bf16") for a in As], [dev(b, "bf16") for b in Bs], Cd, M, N, Ks)
+        torch.cuda.synchronize()
+        assert used == 1
+        assert_close(host(Cd), want, 4e-3 if out == "bf16" else 2e-5, f"ragged segmented dW into {out}")
+
+
+def test_row_statistics_with_a_ragged_last_column_block():
+    rng = np.random.default_rng(35)
+    for (M, N, K) in ((300, 648, 192), (64, 8, 64), (257, 1400, 128)):
+        A = synth.to_storage(rng.normal(size=(M, K)) * 3.0, "bf16")
+        B = synth.to_storage(rng.normal(size=(N, K)), "bf16")
+        nb = -(-N // 256)
+        full = torch.full((M, N + 40), -7.0, device="cuda", dtype=torch.float32)
+        stats = torch.full((M + 3, nb, 2), -7.0, device="cuda", dtype=torch.float32)
+        used = sb.debug_gemm(dev(A, "bf16"), dev(B, "bf16"), full[:, :N], M, N, K, False, True, row_stats=stats)
+        torch.cuda.synchronize()
+        assert used == 1 and torch.all(full[:, N:] == -7.0) and torch.all(stats[M:] == -7.0)
+        C = full[:, :N].cpu().numpy()
+        assert_close(C, A.astype(np.float64) @ B.astype(np.float64).T, 2e-5, f"C M={M} N={N}")
+        st = stats.cpu().numpy()
+        for b in range(nb):
+            blk = C[:, b * 256:min(N, (b + 1) * 256)]
+            assert np.array_equal(st[:M, b, 0], blk.max(axis=1)), f"block {b}: maxima differ from the stored C"
+            se = np.exp(blk.astype(np.float64) - blk.max(axis=1, keepdims=True)).sum(axis=1)
+            assert np.allclose(st[:M, b, 1], se, rtol=2e-5, atol=0)
+
+
 def test_mfma_bigger_square():
     run(1024, 1024, 1024, False, True, out="bf16", expect_mfma=True)
 

@@ -105,6 +105,26 @@ def test_head_full_vocab_with_prompt_mask_vs_oracle():
     assert abs(float(loss.item()) - ref["loss"]) < 2e-3 * ref["loss"]
 
 
+def test_head_with_a_151936_word_vocabulary_vs_oracle():
+    # the vocabulary of the paper's own models: 593.5 output tiles - the logits GEMM, its row statistics and the weight
+    # gradient end in a half tile; everything stays on the MFMA kernels
+    T, chunk, V = 2304, 2048, 151936
+    cfg = dict(synth.CONFIGS["lmhead"], vocab=V)
+    inp = synth.head_inputs(cfg, seed=2, seq_len=T, prompt_frac=0.0)
+    ref = o_head.sft(inp["h"], inp["w"], inp["targets"], 1.0 / T)
+    hc = sb.head_cfg(sb.SBP_BF16, 1, T, chunk, cfg["hidden"], V, sb.SBP_OBJ_SFT, 1.0 / T)
+    assert sb.streambp_lmhead_fast_path(hc) == 1
+    before = sb.streambp_generic_launches()
+    dh, dw, loss, n_active = sb.streambp_lmhead_ce_backward(hc, dev(inp["w"], "bf16"), dev(inp["h"], "bf16"),
+                                                            torch.from_numpy(inp["targets"]).cuda())
+    torch.cuda.synchronize()
+    assert sb.streambp_generic_launches() == before
+    assert int(n_active.item()) == T
+    assert_close(host(dh), ref["dh"], TOL, "dh")
+    assert_close(host(dw), ref["dw"], TOL, "dw")
+    assert abs(float(loss.item()) - ref["loss"]) < 2e-3 * ref["loss"]
+
+
 def test_attention_last_chunk_of_32k_one_kv_group_vs_oracle():
     Hq, Hkv, dh = C7B["n_q_heads"], C7B["n_kv_heads"], C7B["head_dim"]
     G = Hq // Hkv

@@ -107,6 +107,22 @@ def test_optional_fusions_agree_with_the_oracle(mask):
         sb.debug_set_fusions(old)
 
 
+# widths that are multiples of 64 but not of the MFMA GEMMs' 256-wide output tile: every GEMM of the layer and of the head
+# ends in a ragged tile (q width 384, k/v width 128, hidden 320, MLP 448, vocabulary 1408 = 5.5 tiles)
+RAG16 = dict(dtype="bf16", hidden=320, n_q_heads=3, n_kv_heads=1, head_dim=128, mlp_width=448, vocab=1408)
+
+
+@pytest.mark.parametrize("grad_dtype", ["f32", "bf16"])
+def test_ragged_widths_stay_on_the_mfma_kernels(grad_dtype):
+    assert sb.streambp_layer_fast_path(lib_layer_cfg(RAG16, 700, 256)) == 1
+    assert sb.streambp_lmhead_fast_path(sb.head_cfg(sb.SBP_BF16, 2, 300, 128, 320, 1408)) == 1
+    before = sb.streambp_generic_launches()
+    run_layer_case(RAG16, 700, 256, batch=2, seed=3, grad_dtype=grad_dtype)
+    head_case(RAG16, 2, 300, 128, "sft", loss_scale=1.0 / 450, grad_dtype=grad_dtype)
+    head_case(RAG16, 2, 300, 128, "grpo", grad_dtype=grad_dtype)
+    assert sb.streambp_generic_launches() == before, "a launch left the MFMA kernels"
+
+
 def test_layer_backward_mid_fp32():
     run_layer_case(MID32, 320, 128)
 
