@@ -365,11 +365,24 @@ int32_t layer_backward_impl(const sbp_layer_cfg* c, const sbp_layer_weights* w, 
           gb[j] = dw_gemm(dYs[i], lora->P[j], lora->db_pad[j], n, out, LORA_PAD, dt, DT_F32);                              // dB += dY^T P
           ga[j] = dw_gemm(lora->Q[j], Xs[i], lora->da_pad[j], n, LORA_PAD, in, dt, DT_F32);                                // dA += Q^T X
         }
+        // P and Q are chunk x rank: a handful of output tiles each.  Those with a long reduction (the MLP width) go out
+        // alone, where the dispatcher splits the reduction over the chip; the short ones share one grouped launch.
+        auto launch_skinny = [&](const GemmArgs* gs, int cnt) -> int32_t {
+          GemmArgs shortk[7];
+          int n_short = 0;
+          for (int j = 0; j < cnt; ++j) {
+            if (gs[j].K >= 8192) HIPCHK(gemm(gs[j], st));
+            else shortk[n_short++] = gs[j];
+          }
+          if (n_short == 1) HIPCHK(gemm(shortk[0], st));
+          else if (n_short > 1) HIPCHK(gemm_batch(shortk, n_short, st, true));
+          return SBP_OK;
+        };
+        if ((rc = launch_skinny(gp, lora->n))) return rc;
+        if ((rc = launch_skinny(gq, lora->n))) return rc;
         if (lora->n == 1) {
-          HIPCHK(gemm(gp[0], st)); HIPCHK(gemm(gq[0], st)); HIPCHK(gemm(gb[0], st)); HIPCHK(gemm(ga[0], st));
+          HIPCHK(gemm(gb[0], st)); HIPCHK(gemm(ga[0], st));
         } else {
-          HIPCHK(gemm_batch(gp, lora->n, st, true));
-          HIPCHK(gemm_batch(gq, lora->n, st, true));
           HIPCHK(gemm_batch(gb, lora->n, st, true));
           HIPCHK(gemm_batch(ga, lora->n, st, true));
         }
