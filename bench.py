@@ -29,7 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # the timed process: the figure is the one two rocprofv3 --pmc runs of this script measured (FETCH_SIZE, WRITE_SIZE, scaled
 # by a 1 GiB copy-like kernel) and is reported together with the file under profiles/ that holds those runs; for any
 # other kernel or shape the field is null.
-MEASURED_TRAFFIC = {}     # kernel symbol -> (bytes per launch, file under profiles/)
+MEASURED_TRAFFIC = {      # kernel symbol -> (bytes per launch, file under profiles/)
+    "gemm_mfma_k<false, false, 3>": (1.373e9, "profiles/bench_7b_layer_lmhead_32k_hbm_traffic.txt"),
+}
 
 
 def algorithmic_flops(cfg, T, active_rows, batch=1, has_layer=True, has_head=True, n_layers=1, lora_rank=0, window=0):
