@@ -11,7 +11,7 @@ import ctypes as C
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libstreambp.so")
+LIB_PATH = os.environ.get("STREAMBP_LIB") or os.path.join(_PKG, "libstreambp.so")   # (the override serves A/B runs of two builds)
 
 SBP_F32, SBP_BF16 = 0, 1
 SBP_OBJ_SFT, SBP_OBJ_GRPO, SBP_OBJ_DPO = 0, 1, 2
