@@ -308,13 +308,6 @@ def test_attn_bf16_dh128(s, c):
     attn_case("bf16", 8, 2, 128, s, c, extra_rows=3)
 
 
-# Peaked softmax rows (one probability ~1): dS = P (dP - delta) is then a difference of two nearly equal numbers for the
-# dominant key, and delta = rowsum(dO * O) is formed from the bf16-rounded O (relative 2^-9): the rounding of O is
-# amplified by |dP| / |dP - delta|.  This is a property of any backward that keeps O in bf16, not of the tiling; the
-# bound for this one adversarial case is therefore 1.5x the general bf16 bound.
-PEAKED_TOL = 3e-2
-
-
 def test_large_magnitudes_do_not_overflow():
     # Scores / logits far outside the range where exp would survive without the running-max shift: peaked softmax rows
     # (probabilities 0 and 1 to rounding), results must stay finite and match the oracle.
@@ -336,8 +329,8 @@ def test_large_magnitudes_do_not_overflow():
     print("large-magnitude attention: norm-wise errors",
           {n: f"{e:.2e}" for n, e in (("dq", relerr(host(dq), dq_ref)), ("dk", relerr(host(dk)[:s + c], dk_ref)),
                                       ("dv", relerr(host(dv)[:s + c], dv_ref)))})
-    assert_close(host(dq), dq_ref, PEAKED_TOL, "dq")
-    assert_close(host(dk)[:s + c], dk_ref, PEAKED_TOL, "dk")
+    assert_close(host(dq), dq_ref, 2e-2, "dq")
+    assert_close(host(dk)[:s + c], dk_ref, 2e-2, "dk")
     assert_close(host(dv)[:s + c], dv_ref, 2e-2, "dv")
     # head: hidden states x 40 -> logits ~ N(0, 48^2) at the tiny shape, far beyond exp's fp32 range unshifted
     hin = synth.head_inputs(TINY, seed=5, seq_len=64, batch=2, vocab=TINY["vocab"])
