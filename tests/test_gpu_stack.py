@@ -35,11 +35,13 @@ def oracle_stack(ids, emb, layers, g_final, w_head, targets, cfg, loss_scale):
                 n_active=hd["n_active"])
 
 
-@pytest.mark.parametrize("name,L,T,chunk,head_chunk,grad_dtype", [("tiny", 3, 256, 64, 100, "f32"), ("mid16", 2, 300, 128, 128, "f32"),
-                                                                   ("mid16", 2, 300, 128, 128, "bf16")])
-def test_stack_forward_backward(name, L, T, chunk, head_chunk, grad_dtype):
+@pytest.mark.parametrize("name,L,T,chunk,head_chunk,grad_dtype,window", [("tiny", 3, 256, 64, 100, "f32", 0), ("mid16", 2, 300, 128, 128, "f32", 0),
+                                                                          ("mid16", 2, 300, 128, 128, "bf16", 0), ("tiny", 2, 200, 64, 64, "f32", 50),
+                                                                          ("mid16", 2, 300, 128, 128, "f32", 90)])
+def test_stack_forward_backward(name, L, T, chunk, head_chunk, grad_dtype, window):
     cfg = dict(synth.CONFIGS["tiny"]) if name == "tiny" else dict(dtype="bf16", hidden=256, n_q_heads=4, n_kv_heads=2,
                                                                   head_dim=128, mlp_width=512, vocab=1024)
+    cfg["window"] = window            # sliding-window attention in every layer of the stack
     dt = cfg["dtype"]
     tok = synth.token_stream(cfg, seed=1, seq_len=T)
     layers = [synth.layer_weights(cfg, seed=10 + l) for l in range(L)]
