@@ -257,16 +257,18 @@ size_t streambp_layer_workspace_bytes(const sbp_layer_cfg* cfg) {
 
 // Low-rank adapter mode of the layer backward (App. D, experiment setup: rank-32 adapters, adapter gradients only).
 // The chunk loop runs on the effective matrices W + s B A (built once per call); instead of the seven weight gradients
-// of a chunk it forms, per adapted matrix, P = X A^T, Q = dY B (chunk x rank, padded to the GEMM tile width) and
+// of a chunk it forms, per adapted matrix, P = X A^T, Q = dY B (chunk x rank, the rank rounded up to a multiple of 8) and
 // accumulates dB += dY^T P, dA += Q^T X - the chain rule through B A without ever forming dW.
-constexpr int LORA_PAD = 256;      // adapter rank padded to the MFMA GEMMs' tile width
+constexpr int LORA_MAX_RANK = 256;
 struct LoraCtx {
   int n;                           // adapted matrices
+  int pad;                         // adapter rank rounded up to a multiple of 8 (the GEMMs' 16-byte granule); the
+                                   // MFMA GEMMs take such widths with a masked ragged tile
   int which[7];                    // index into the order wq, wk, wv, wo, wgate, wup, wdown
   int out_dim[7], in_dim[7];
-  void *a_pad[7], *b_pad[7];       // [LORA_PAD, in], [out, LORA_PAD] in the storage type, zero beyond the rank
+  void *a_pad[7], *b_pad[7];       // [pad, in], [out, pad] in the storage type, zero beyond the rank
   float *da_pad[7], *db_pad[7];    // fp32 accumulators of the same shapes
-  void *P[7], *Q[7];               // [chunk, LORA_PAD] per adapted matrix
+  void *P[7], *Q[7];               // [chunk, pad] per adapted matrix
   float* dg_sink;                  // the norm gains are frozen: their gradient goes nowhere
 };
 } // extern "C"
@@ -358,12 +360,13 @@ int32_t layer_backward_impl(const sbp_layer_cfg* c, const sbp_layer_weights* w, 
         const void* dYs[7] = {s.dq, s.dkc, s.dvc, s.dh1_t, s.gate, s.up, dyc};     // order wq, wk, wv, wo, wgate, wup, wdown
         const void* Xs[7] = {s.a, s.a, s.a, s.o, s.m, s.m, s.act};
         GemmArgs gp[7], gq[7], gb[7], ga[7];
+        const int rp = lora->pad;
         for (int j = 0; j < lora->n; ++j) {
           const int i = lora->which[j], out = lora->out_dim[j], in = lora->in_dim[j];
-          gp[j] = fwd_gemm(Xs[i], lora->a_pad[j], lora->P[j], n, LORA_PAD, in, dt, dt);                                    // P = X A^T
-          gq[j] = mk(dYs[i], lora->b_pad[j], lora->Q[j], n, LORA_PAD, out, out, LORA_PAD, LORA_PAD, false, false, dt, dt, false);   // Q = dY B
-          gb[j] = dw_gemm(dYs[i], lora->P[j], lora->db_pad[j], n, out, LORA_PAD, dt, DT_F32);                              // dB += dY^T P
-          ga[j] = dw_gemm(lora->Q[j], Xs[i], lora->da_pad[j], n, LORA_PAD, in, dt, DT_F32);                                // dA += Q^T X
+          gp[j] = fwd_gemm(Xs[i], lora->a_pad[j], lora->P[j], n, rp, in, dt, dt);                                   // P = X A^T
+          gq[j] = mk(dYs[i], lora->b_pad[j], lora->Q[j], n, rp, out, out, rp, rp, false, false, dt, dt, false);    // Q = dY B
+          gb[j] = dw_gemm(dYs[i], lora->P[j], lora->db_pad[j], n, out, rp, dt, DT_F32);                             // dB += dY^T P
+          ga[j] = dw_gemm(lora->Q[j], Xs[i], lora->da_pad[j], n, rp, in, dt, DT_F32);                               // dA += Q^T X
         }
         // P and Q are chunk x rank: a handful of output tiles each.  Those with a long reduction (the MLP width) go out
         // alone, where the dispatcher splits the reduction over the chip; the short ones share one grouped launch.
@@ -419,7 +422,7 @@ int32_t streambp_layer_backward(const sbp_layer_cfg* c, const sbp_layer_weights*
 namespace {
 int32_t check_lora(const sbp_layer_cfg* c, const sbp_lora_adapters* ad) {
   if (!ad) return fail(SBP_ERR_NULL, "adapters table is NULL");
-  if (ad->rank < 1 || ad->rank > LORA_PAD) return fail(SBP_ERR_SHAPE, "adapter rank must be in [1, %d]", LORA_PAD);
+  if (ad->rank < 1 || ad->rank > LORA_MAX_RANK) return fail(SBP_ERR_SHAPE, "adapter rank must be in [1, %d]", LORA_MAX_RANK);
   if (!std::isfinite(ad->scale)) return fail(SBP_ERR_SHAPE, "adapter scale must be finite");
   if (c->grad_dtype != SBP_F32) return fail(SBP_ERR_UNSUPPORTED, "adapter gradients are fp32");
   int n = 0;
@@ -442,18 +445,20 @@ LoraWs carve_lora(const sbp_layer_cfg* c, const sbp_layer_weights* w, const sbp_
   const void** eff[7] = {&L.w_eff.wq, &L.w_eff.wk, &L.w_eff.wv, &L.w_eff.wo, &L.w_eff.wgate, &L.w_eff.wup, &L.w_eff.wdown};
   LoraCtx& x = L.ctx;
   x.n = 0;
+  x.pad = (ad->rank + 7) & ~7;
+  const size_t rp = (size_t)x.pad;
   for (int i = 0; i < 7; ++i) {
     if (!ad->a[i]) continue;
     const int j = x.n++;
     x.which[j] = i; x.out_dim[j] = outs[i]; x.in_dim[j] = ins[i];
     *eff[i] = cv.take_bytes((size_t)outs[i] * ins[i] * es);                      // W + s B A
-    x.a_pad[j] = cv.take_bytes((size_t)LORA_PAD * ins[i] * es);
-    x.b_pad[j] = cv.take_bytes((size_t)outs[i] * LORA_PAD * es);
+    x.a_pad[j] = cv.take_bytes(rp * ins[i] * es);
+    x.b_pad[j] = cv.take_bytes((size_t)outs[i] * rp * es);
     L.bt[j] = cv.take_bytes((size_t)ad->rank * outs[i] * es);                    // s B^T, the merge GEMM's operand
-    x.da_pad[j] = cv.take<float>((size_t)LORA_PAD * ins[i]);
-    x.db_pad[j] = cv.take<float>((size_t)outs[i] * LORA_PAD);
-    x.P[j] = cv.take_bytes(cm * LORA_PAD * es);
-    x.Q[j] = cv.take_bytes(cm * LORA_PAD * es);
+    x.da_pad[j] = cv.take<float>(rp * ins[i]);
+    x.db_pad[j] = cv.take<float>((size_t)outs[i] * rp);
+    x.P[j] = cv.take_bytes(cm * rp * es);
+    x.Q[j] = cv.take_bytes(cm * rp * es);
   }
   x.dg_sink = cv.take<float>((size_t)2 * d);
   L.layer_cfg = *c;
@@ -493,22 +498,22 @@ int32_t streambp_layer_lora_backward(const sbp_layer_cfg* c, const sbp_layer_wei
   t_gemm_scratch = nullptr; t_gemm_scratch_bytes = 0;
   for (int j = 0; j < X.n; ++j) {
     const int i = X.which[j], out = X.out_dim[j], in = X.in_dim[j], r = ad->rank;
-    // operands padded to the GEMM tile width, and the effective matrix W + s B A: a copy of W, then one pass that reads
+    // operands with the rank rounded up to a multiple of 8, and the effective matrix W + s B A: a copy of W, then one pass that reads
     // it, adds the rank-r product in fp32 and rounds once
-    HIPCHK(pad_matrix(dt, ad->a[i], r, in, false, 1.0f, X.a_pad[j], LORA_PAD, in, st));
-    HIPCHK(pad_matrix(dt, ad->b[i], out, r, false, 1.0f, X.b_pad[j], out, LORA_PAD, st));
+    HIPCHK(pad_matrix(dt, ad->a[i], r, in, false, 1.0f, X.a_pad[j], X.pad, in, st));
+    HIPCHK(pad_matrix(dt, ad->b[i], out, r, false, 1.0f, X.b_pad[j], out, X.pad, st));
     HIPCHK(pad_matrix(dt, ad->b[i], r, out, true, ad->scale, L.bt[j], r, out, st));
     HIPCHK(copy_bytes((void*)eff[i], base[i], (size_t)out * in * es, st));
     HIPCHK(gemm(mk(L.bt[j], X.a_pad[j], (void*)eff[i], out, in, r, out, in, in, true, false, dt, dt, true), st));
-    HIPCHK(fill_zero(X.da_pad[j], (size_t)LORA_PAD * in * sizeof(float), st));
-    HIPCHK(fill_zero(X.db_pad[j], (size_t)out * LORA_PAD * sizeof(float), st));
+    HIPCHK(fill_zero(X.da_pad[j], (size_t)X.pad * in * sizeof(float), st));
+    HIPCHK(fill_zero(X.db_pad[j], (size_t)out * X.pad * sizeof(float), st));
   }
   const LayerWs s_all = carve_layer(&L.layer_cfg, L.layer_ws);
   if ((rc = layer_backward_impl(&L.layer_cfg, &L.w_eff, x, dy, dx, nullptr, &X, s_all, st))) return rc;
   for (int j = 0; j < X.n; ++j) {
     const int i = X.which[j];
     HIPCHK(add_scaled_block(X.da_pad[j], X.in_dim[j], ad->scale, g->da[i], ad->rank, X.in_dim[j], st));
-    HIPCHK(add_scaled_block(X.db_pad[j], LORA_PAD, ad->scale, g->db[i], X.out_dim[j], ad->rank, st));
+    HIPCHK(add_scaled_block(X.db_pad[j], X.pad, ad->scale, g->db[i], X.out_dim[j], ad->rank, st));
   }
   return SBP_OK;
 }

@@ -187,10 +187,10 @@ def test_adapter_mode_validation_and_workspace():
     need = L.streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(ad))
     plain = sb.streambp_layer_workspace_bytes(good_layer_cfg(dw_group_rows=2048, **big))
     p_lin = 3584 * 28 * 128 * 2 + 2 * 3584 * 4 * 128 + 3 * 3584 * 18944
-    # one chunk's buffers + one copy of the adapted matrices + the padded adapter operands / accumulators (rank padded to 256: a third of that)
-    assert plain + 2 * p_lin < need < plain + 2 * p_lin * 1.4
+    # one chunk's buffers + one copy of the adapted matrices + the padded adapter operands / accumulators (rank 32: a few % of that)
+    assert plain + 2 * p_lin < need < plain + 2 * p_lin * 1.06
     only_qv = sb.LoraAdapters(32, 2.0, (C.c_void_p * 7)(256, None, 256, None, None, None, None), (C.c_void_p * 7)(256, None, 256, None, None, None, None))
-    assert L.streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(only_qv)) < plain + 2 * (3584 * 3584 + 512 * 3584) * 2.0     # only the adapted matrices are copied
+    assert L.streambp_layer_lora_workspace_bytes(C.byref(cfg), C.byref(only_qv)) < plain + 2 * (3584 * 3584 + 512 * 3584) * 1.2     # only the adapted matrices are copied
     for bad in (sb.LoraAdapters(0, 1.0, ad.a, ad.b), sb.LoraAdapters(257, 1.0, ad.a, ad.b),
                 sb.LoraAdapters(8, float("nan"), ad.a, ad.b),
                 sb.LoraAdapters(8, 1.0, (C.c_void_p * 7)(256, *[None] * 6), (C.c_void_p * 7)(*[None] * 7)),     # A without B
