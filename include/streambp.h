@@ -83,8 +83,8 @@ typedef struct {
   int32_t dw_group_rows; /* rows of chunk operands kept alive so that one pass over
                            the weight gradients adds several chunks' products
                            (Eq. 1: the summands may be added in any grouping):
-                           the group is min(4, max(1, dw_group_rows / chunk))
-                           chunks.  0 = default (8192).  More rows: fewer passes
+                           the group is min(8, max(1, dw_group_rows / chunk))
+                           chunks.  0 = default (16384).  More rows: fewer passes
                            over every dW, more workspace (one more copy of a
                            chunk's ten GEMM operand buffers per chunk of the group) */
   int32_t window;       /* attention mask (Sec. 3.2.2 allows a general mask M, "padding /
@@ -184,8 +184,8 @@ typedef struct {
   int32_t grad_dtype;   /* element type of dw: SBP_F32 (0, default) or SBP_BF16
                            (needs dtype == SBP_BF16)                            */
   int32_t dw_group_rows; /* as in sbp_layer_cfg: dz and the gathered h rows of
-                           min(4, max(1, dw_group_rows / chunk)) chunks stay alive
-                           and dw is added to once per group.  0 = default (8192) */
+                           min(8, max(1, dw_group_rows / chunk)) chunks stay alive
+                           and dw is added to once per group.  0 = default (16384) */
 } sbp_head_cfg;
 
 size_t streambp_lmhead_workspace_bytes(const sbp_head_cfg *cfg);

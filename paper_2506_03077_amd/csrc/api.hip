@@ -53,9 +53,9 @@ int32_t check_grad_dtype(int32_t dt, int32_t grad_dt) {
 
 // Weight gradients are added once per group of chunks (one read-modify-write pass over every dW per group instead of
 // one per chunk): as many chunks as it takes to reach DW_GROUP_ROWS rows, at most MAX_DW_GROUP (the GEMM kernels take
-// up to four reduction segments per output).  The operands of the group's chunks stay alive until the launch.
-constexpr int MAX_DW_GROUP = 4;
-constexpr int DW_GROUP_ROWS = 8192;
+// up to eight reduction segments per output).  The operands of the group's chunks stay alive until the launch.
+constexpr int MAX_DW_GROUP = 8;
+constexpr int DW_GROUP_ROWS = 16384;
 int dw_group_for(size_t chunk_rows, int32_t cfg_rows) {   // cfg_rows: the config's dw_group_rows (0 = default)
   const size_t rows = cfg_rows > 0 ? (size_t)cfg_rows : (size_t)DW_GROUP_ROWS;
   return (int)std::max<size_t>(1, std::min<size_t>(MAX_DW_GROUP, rows / std::max<size_t>(chunk_rows, 1)));

@@ -163,7 +163,7 @@ struct SwigluFuse { bf16_t* gate; bf16_t* up; bf16_t* act; };
 // reduction (weight-gradient form) takes a slower path with clamped addresses and zeroed fragments.
 // The reduction may come in several segments (operand pairs of the same shape and leading dimensions whose products
 // are summed into the same output tile): one accumulator, one epilogue.
-constexpr int MAX_SEG = 4;
+constexpr int MAX_SEG = 8;
 struct KSegments {
   const bf16_t* A[MAX_SEG];
   const bf16_t* B[MAX_SEG];

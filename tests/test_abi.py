@@ -84,27 +84,32 @@ def test_head_workspace_is_per_chunk():
     b = sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_BF16, 1, 65536, 2048, 3584, 152064))
     # the only term that grows with T is the int32 list of active rows (+ one count per chunk); no T*V or T*d term
     assert 0 < b - a <= 32768 * 4 + 16 * 4 + 512
-    # chunk logits fp32 + dz bf16 of the four chunks (8192 rows) whose weight gradient is added in one pass + gathered h / dh rows
-    # + split-K scratch + the (max, sum of exp) pair per row and block of 256 logits
-    assert a < 2048 * 152064 * (4 + 4 * 2) + 5 * 2048 * 3584 * 2 + 4 * 2048 * 3584 * 4 + 2048 * (152064 // 256) * 8 + (1 << 20)
-    assert a < 32768 * 152064 * 4 / 5        # a fifth of the full-sequence fp32 logits alone
+    # chunk logits fp32 + dz bf16 of the eight chunks (16384 rows) whose weight gradient is added in one pass + gathered h / dh
+    # rows + split-K scratch + the (max, sum of exp) pair per row and block of 256 logits
+    assert a < 2048 * 152064 * (4 + 8 * 2) + 9 * 2048 * 3584 * 2 + 4 * 2048 * 3584 * 4 + 2048 * (152064 // 256) * 8 + (1 << 20)
+    assert a < 32768 * 152064 * 4 / 3        # a third of the full-sequence fp32 logits alone
+    mid = sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 152064, dw_group_rows=8192))
+    assert mid < 32768 * 152064 * 4 / 5      # four chunks per pass: a fifth
     lean = sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 152064, dw_group_rows=2048))
     assert lean < 32768 * 152064 * 4 / 9     # with the weight gradient added chunk by chunk: a ninth
 
 
 def test_weight_gradient_group_rows_only_change_the_workspace():
-    # dw_group_rows = 0 is the default of 8192 rows; more rows keep more chunks' GEMM operands alive (at most four chunks)
+    # dw_group_rows = 0 is the default of 16384 rows; more rows keep more chunks' GEMM operands alive (at most eight chunks)
     big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
-    ws = {r: sb.streambp_layer_workspace_bytes(good_layer_cfg(dw_group_rows=r, **big)) for r in (0, 1, 2048, 4096, 6144, 8192, 10 ** 6)}
-    assert ws[0] == ws[8192] and ws[1] == ws[2048] and ws[8192] == ws[10 ** 6]
-    assert ws[2048] < ws[4096] < ws[6144] < ws[8192]
+    ws = {r: sb.streambp_layer_workspace_bytes(good_layer_cfg(dw_group_rows=r, **big))
+          for r in (0, 1, 2048, 4096, 6144, 8192, 16384, 10 ** 6)}
+    assert ws[0] == ws[16384] and ws[1] == ws[2048] and ws[16384] == ws[10 ** 6]
+    assert ws[2048] < ws[4096] < ws[6144] < ws[8192] < ws[16384]
     per_chunk = ws[4096] - ws[2048]
     assert ws[8192] - ws[2048] == 3 * per_chunk                     # one copy of the ten operand buffers per further chunk
+    assert ws[16384] - ws[2048] == 7 * per_chunk
     assert per_chunk <= 2048 * (3 * 18944 + 7 * 3584) * 2 + 16 * 256
     hw = {r: sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_BF16, 1, 32768, 2048, 3584, 152064, dw_group_rows=r))
-          for r in (0, 2048, 4096, 8192)}
-    assert hw[0] == hw[8192] and hw[2048] < hw[4096] < hw[8192]
+          for r in (0, 2048, 4096, 8192, 16384, 10 ** 6)}
+    assert hw[0] == hw[16384] == hw[10 ** 6] and hw[2048] < hw[4096] < hw[8192] < hw[16384]
     assert hw[8192] - hw[4096] == 2 * (hw[4096] - hw[2048])         # dz + gathered h rows per further chunk
+    assert hw[16384] - hw[8192] == 4 * (hw[4096] - hw[2048])
     assert sb.streambp_layer_workspace_bytes(good_layer_cfg(dw_group_rows=-1)) == 0
     assert sb.streambp_lmhead_workspace_bytes(sb.head_cfg(sb.SBP_F32, 1, 8, 4, 8, 16, dw_group_rows=-5)) == 0
 

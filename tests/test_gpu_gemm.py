@@ -121,7 +121,7 @@ def test_row_statistics_from_the_store_epilogue():
 def test_mfma_segmented_weight_gradient():
     # C += sum_s A_s^T B_s in one launch; segments of different length, two of them cut short by a device row count
     rng = np.random.default_rng(5)
-    M, N, Ks, limits = 512, 256, (300, 1000, 64, 128), (250, None, 0, None)
+    M, N, Ks, limits = 512, 256, (300, 1000, 64, 128, 192, 77, 256, 500), (250, None, 0, None, None, 70, None, 499)
     As = [synth.to_storage(rng.normal(size=(K, M)), "bf16") for K in Ks]
     Bs = [synth.to_storage(rng.normal(size=(K, N)), "bf16") for K in Ks]
     C0 = rng.normal(size=(M, N)).astype(np.float32)
@@ -129,7 +129,7 @@ def test_mfma_segmented_weight_gradient():
     for A, B, K, lim in zip(As, Bs, Ks, limits):
         k = K if lim is None else lim
         want = want + A[:k].T.astype(np.float64) @ B[:k].astype(np.float64)
-    for n in (2, 4):
+    for n in (2, 4, 7, 8):
         Cd = dev(C0, "f32")
         rows = [None if lim is None else torch.tensor([lim], dtype=torch.int32, device="cuda") for lim in limits[:n]]
         used = sb.debug_gemm_dw_segments([dev(a, "bf16") for a in As[:n]], [dev(b, "bf16") for b in Bs[:n]], Cd, M, N, Ks[:n], rows)

@@ -47,7 +47,7 @@ def test_layer_7b_widths_vs_oracle(chunk):
     # 7B widths, T = 4608 = 2.25 chunks of 2048 (the chunk bench.py times; the last chunk ragged).  At chunk 2048 the layer
     # runs what the bench runs: the two-way XCD-pinned split-K input-gradient GEMMs over 112 output tiles, the operand-pair
     # dm GEMM, and ONE grouped weight-gradient launch with three reduction segments of 2048, 2048 and 512 rows; chunk 512
-    # takes the 8-way split-K and groups of four chunks, chunk = T no partition at all.
+    # takes the 8-way split-K and a group of eight chunks plus a ragged ninth, chunk = T no partition at all.
     T = 4608
     assert sb.streambp_layer_fast_path(lib_layer_cfg(C7B, T, chunk)) == 1
     inp, dx_ref, g_ref = layer_reference(C7B, T, 0)
@@ -61,17 +61,24 @@ def test_layer_7b_widths_vs_oracle(chunk):
         assert_close(host(dw[n]), g_ref[n], TOL, f"d{n} (chunk {chunk})")
 
 
-def test_head_full_vocab_vs_oracle():
-    # V = 152064 at the bench's chunk of 2048 rows with 8792 active rows: four full chunks, whose weight gradient is one
-    # four-segment pass over dW, then a ragged fifth chunk (600 rows) that is a pass of its own; every row of dh and every
-    # 256 x 256 tile of dW (8316 of them) is compared with the oracle.
+_HEAD_REF = {}
+
+
+@pytest.mark.parametrize("dw_group_rows", [0, 8192])
+def test_head_full_vocab_vs_oracle(dw_group_rows):
+    # V = 152064 at the bench's chunk of 2048 rows with 8792 active rows = four full chunks and a ragged fifth (600 rows).
+    # Default grouping: their weight gradient is ONE five-segment pass over dW; with 8192 rows per pass a four-segment pass
+    # and the ragged chunk as a pass of its own.  Every row of dh and every 256 x 256 tile of dW (8316 of them) is compared
+    # with the oracle.
     T, chunk = 8792, 2048
     cfg = synth.CONFIGS["lmhead"]
     inp = synth.head_inputs(cfg, seed=0, seq_len=T, prompt_frac=0.0)
     n_act = int((inp["targets"] >= 0).sum())
     assert n_act == T
-    ref = o_head.sft(inp["h"], inp["w"], inp["targets"], 1.0 / n_act)
-    hc = sb.head_cfg(sb.SBP_BF16, 1, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, 1.0 / n_act)
+    if "ref" not in _HEAD_REF:
+        _HEAD_REF["ref"] = o_head.sft(inp["h"], inp["w"], inp["targets"], 1.0 / n_act)
+    ref = _HEAD_REF["ref"]
+    hc = sb.head_cfg(sb.SBP_BF16, 1, T, chunk, cfg["hidden"], cfg["vocab"], sb.SBP_OBJ_SFT, 1.0 / n_act, dw_group_rows=dw_group_rows)
     assert sb.streambp_lmhead_fast_path(hc) == 1
     before = sb.streambp_generic_launches()
     dh, dw, loss, n_active = sb.streambp_lmhead_ce_backward(hc, dev(inp["w"], "bf16"), dev(inp["h"], "bf16"),
@@ -185,6 +192,15 @@ def test_head_32k_structure_and_sampled_rows():
     col = dw.sum(dim=0).abs().max().item()                                 # rows of dz sum to zero
     assert col < 1e-3 * dw.abs().max().item() * np.sqrt(V)
     assert abs(float(loss.item()) - (np.log(V) + 0.5 * 0.02 ** 2 * d)) < 0.1
+    # Eq. 1: the grouping of the per-chunk summands of dW is free.  The default adds eight chunks' worth (8 x 2048 rows) per
+    # pass; chunk by chunk (the form compared with the oracle tile by tile above) must give the same dW up to fp32 rounding order
+    lean = sb.head_cfg(sb.SBP_BF16, 1, T, 2048, d, V, sb.SBP_OBJ_SFT, 1.0 / n_act, dw_group_rows=2048)
+    dh1, dw1, _, _ = sb.streambp_lmhead_ce_backward(lean, w, h, tg)
+    torch.cuda.synchronize()
+    assert torch.equal(dh1, dh)
+    err = (dw1 - dw).abs().max().item()
+    assert err < 1e-4 * dw.abs().max().item(), err
+    del dh1, dw1
     # sampled rows, one by one with the oracle (dh_t needs only row t of h and W)
     w64 = w.double().cpu().numpy()
     rows = [T // 4, T // 4 + 1, 20000, T - 1]

@@ -69,10 +69,10 @@ def test_layer_backward_grouped_weight_gradients(grad_dtype):
     run_layer_case(BIG16, 512, 128, grad_dtype=grad_dtype)
 
 
-@pytest.mark.parametrize("rows", [1, 128, 256, 384, 512, 100000])
+@pytest.mark.parametrize("rows", [1, 128, 256, 384, 512, 640, 768, 896, 100000])
 def test_weight_gradient_group_size_is_a_free_choice(rows):
     # Eq. 1: the per-chunk summands of a weight gradient may be added in any grouping.  dw_group_rows picks how many chunks'
-    # operands stay alive for one pass over every dW: 1 chunk (rows <= chunk), 2, 3, 4 (the cap); 9 chunks of 128 rows, the
+    # operands stay alive for one pass over every dW: 1 chunk (rows <= chunk), 2, ..., 7, 8 (the cap); 9 chunks of 128 rows, the
     # last one ragged, so groups of every size end on a partial group.  Layer and head, fp32 and bf16 accumulators.
     run_layer_case(BIG16, 1100, 128, dw_group_rows=rows)
     run_layer_case(MID16, 1100, 128, grad_dtype="bf16", dw_group_rows=rows)
