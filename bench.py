@@ -115,7 +115,7 @@ def main():
                     help="element type of the weight-gradient accumulators (default fp32; bf16 is the paper's own training "
                          "setting, App. D (experiment setup), and halves the read-modify-write traffic on dW)")
     ap.add_argument("--dw-group-rows", type=int, default=0,
-                    help="rows of chunk operands kept alive per pass over the weight gradients (0 = the library's default, 16384)")
+                    help="rows of chunk operands kept alive per pass over the weight gradients (0 = the library's defaults: 8192 for the layer, 16384 for the head)")
     ap.add_argument("--batch", type=int, default=None, help="sequences per call (default: the workload's own)")
     ap.add_argument("--seq-len", type=int, default=None)
     ap.add_argument("--chunk", type=int, default=None)
@@ -162,7 +162,7 @@ def main():
     prompt_frac = args.prompt_frac if args.prompt_frac is not None else (0.25 if wl in ("lmhead", "grpo") else 0.0)
     gdt = sb.SBP_BF16 if args.grad_dtype == "bf16" else sb.SBP_F32
     default_shape = (wl == "7b" and T == cfg["seq_len"] and c == cfg["chunk"] and hc_rows == c and B == cfg["batch"]
-                     and not args.lora_rank and not args.window and prompt_frac == 0.0 and gdt == sb.SBP_F32 and args.dw_group_rows in (0, 16384))   # what the profiles cover
+                     and not args.lora_rank and not args.window and prompt_frac == 0.0 and gdt == sb.SBP_F32 and args.dw_group_rows == 0)   # what the profiles cover
     d = cfg["hidden"]
     bf = torch.bfloat16
 

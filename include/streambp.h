@@ -84,7 +84,7 @@ typedef struct {
                            the weight gradients adds several chunks' products
                            (Eq. 1: the summands may be added in any grouping):
                            the group is min(8, max(1, dw_group_rows / chunk))
-                           chunks.  0 = default (16384).  More rows: fewer passes
+                           chunks.  0 = default (8192).  More rows: fewer passes
                            over every dW, more workspace (one more copy of a
                            chunk's ten GEMM operand buffers per chunk of the group) */
   int32_t window;       /* attention mask (Sec. 3.2.2 allows a general mask M, "padding /

@@ -52,12 +52,15 @@ int32_t check_grad_dtype(int32_t dt, int32_t grad_dt) {
 }
 
 // Weight gradients are added once per group of chunks (one read-modify-write pass over every dW per group instead of
-// one per chunk): as many chunks as it takes to reach DW_GROUP_ROWS rows, at most MAX_DW_GROUP (the GEMM kernels take
+// one per chunk): as many chunks as it takes to reach dw_group_rows rows, at most MAX_DW_GROUP (the GEMM kernels take
 // up to eight reduction segments per output).  The operands of the group's chunks stay alive until the launch.
 constexpr int MAX_DW_GROUP = 8;
-constexpr int DW_GROUP_ROWS = 16384;
-int dw_group_for(size_t chunk_rows, int32_t cfg_rows) {   // cfg_rows: the config's dw_group_rows (0 = default)
-  const size_t rows = cfg_rows > 0 ? (size_t)cfg_rows : (size_t)DW_GROUP_ROWS;
+// Defaults (dw_group_rows == 0).  Measured at 7B widths, chunk 2048: the head's dW pass (2.2 GB read-modify-written) still
+// gains from eight chunks per pass over four; the layer's seven dW (0.93 GB) do not, so the layer keeps four.
+constexpr int DW_GROUP_ROWS_LAYER = 8192;
+constexpr int DW_GROUP_ROWS_HEAD = 16384;
+int dw_group_for(size_t chunk_rows, int32_t cfg_rows, int default_rows) {   // cfg_rows: the config's dw_group_rows (0 = default)
+  const size_t rows = cfg_rows > 0 ? (size_t)cfg_rows : (size_t)default_rows;
   return (int)std::max<size_t>(1, std::min<size_t>(MAX_DW_GROUP, rows / std::max<size_t>(chunk_rows, 1)));
 }
 
@@ -146,7 +149,7 @@ LayerWs carve_layer(const sbp_layer_cfg* c, void* ws) {
   {
     const size_t sizes[10] = {cm * d * es, cm * qd * es, cm * d * es, cm * F * es, cm * F * es, cm * F * es,
                               cm * d * es, cm * qd * es, cm * kd * es, cm * kd * es};   // a, o, m, gate, up, act, dh1_t, dq, dkc, dvc
-    w.dw_group = dw_group_for(cm, c->dw_group_rows);
+    w.dw_group = dw_group_for(cm, c->dw_group_rows, DW_GROUP_ROWS_LAYER);
     for (int g = 1; g < w.dw_group; ++g)
       for (int i = 0; i < 10; ++i) w.alt[g - 1][i] = cv.take_bytes(sizes[i]);
   }
@@ -578,7 +581,7 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   Carver cv(ws);
   HeadWs h;
   h.z = cv.take<float>(cm * c->vocab);
-  h.dw_group = dw_group_for(cm, c->dw_group_rows);
+  h.dw_group = dw_group_for(cm, c->dw_group_rows, DW_GROUP_ROWS_HEAD);
   for (int g = 0; g < h.dw_group; ++g) h.dz[g] = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
   h.row_loss = cv.take<float>(cm);
   h.n_stat = (int)cdiv(c->vocab, GEMM_STAT_COLS);

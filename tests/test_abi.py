@@ -95,11 +95,11 @@ def test_head_workspace_is_per_chunk():
 
 
 def test_weight_gradient_group_rows_only_change_the_workspace():
-    # dw_group_rows = 0 is the default of 16384 rows; more rows keep more chunks' GEMM operands alive (at most eight chunks)
+    # dw_group_rows = 0 is the default (layer: 8192 rows, head: 16384); more rows keep more chunks' GEMM operands alive (at most eight chunks)
     big = dict(dtype=sb.SBP_BF16, hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, mlp_width=18944, chunk=2048, seq_len=32768)
     ws = {r: sb.streambp_layer_workspace_bytes(good_layer_cfg(dw_group_rows=r, **big))
           for r in (0, 1, 2048, 4096, 6144, 8192, 16384, 10 ** 6)}
-    assert ws[0] == ws[16384] and ws[1] == ws[2048] and ws[16384] == ws[10 ** 6]
+    assert ws[0] == ws[8192] and ws[1] == ws[2048] and ws[16384] == ws[10 ** 6]
     assert ws[2048] < ws[4096] < ws[6144] < ws[8192] < ws[16384]
     per_chunk = ws[4096] - ws[2048]
     assert ws[8192] - ws[2048] == 3 * per_chunk                     # one copy of the ten operand buffers per further chunk

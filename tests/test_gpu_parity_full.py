@@ -47,7 +47,7 @@ def test_layer_7b_widths_vs_oracle(chunk):
     # 7B widths, T = 4608 = 2.25 chunks of 2048 (the chunk bench.py times; the last chunk ragged).  At chunk 2048 the layer
     # runs what the bench runs: the two-way XCD-pinned split-K input-gradient GEMMs over 112 output tiles, the operand-pair
     # dm GEMM, and ONE grouped weight-gradient launch with three reduction segments of 2048, 2048 and 512 rows; chunk 512
-    # takes the 8-way split-K and a group of eight chunks plus a ragged ninth, chunk = T no partition at all.
+    # takes the 8-way split-K and groups of four chunks, chunk = T no partition at all.
     T = 4608
     assert sb.streambp_layer_fast_path(lib_layer_cfg(C7B, T, chunk)) == 1
     inp, dx_ref, g_ref = layer_reference(C7B, T, 0)
