@@ -149,6 +149,8 @@ def lib():
         L.streambp_debug_profile_end.argtypes = [C.POINTER(C.c_longlong), C.POINTER(C.c_double), C.POINTER(C.c_double),
                                                  C.POINTER(C.c_double)]
         L.streambp_debug_profile_kinds.restype = C.c_int
+        L.streambp_debug_mfma_rate.restype = C.c_int
+        L.streambp_debug_mfma_rate.argtypes = [vp, vp, C.c_int, C.c_int, vp]
         _lib = L
     return _lib
 
@@ -469,6 +471,27 @@ def debug_gemm_dw_segments(As, Bs, C_out, M, N, Ks, rows_dev=None, stream=None):
     if rc < 0:
         raise StreamBPError(rc, "debug_gemm_dw_segments launch failed")
     return rc
+
+
+def debug_mfma_rate(operands, workgroups=512, iters=10000, repeats=12, stream=None):
+    """TFLOP/s the matrix pipe sustains on fragments taken from `operands` (a bf16 device tensor of 32768 values: the rate
+    depends on the values) with no memory traffic: streambp_debug_mfma_rate timed with events on the launch stream.  The
+    default launches keep the chip busy for 0.1-0.15 s: the power management settles within the first tens of milliseconds."""
+    import torch
+    assert operands.dtype == torch.bfloat16 and operands.numel() == 32768 and operands.is_contiguous()
+    sink = torch.empty(workgroups * 512, dtype=torch.float32, device=operands.device)
+    launch = lambda n: lib().streambp_debug_mfma_rate(_ptr(operands), _ptr(sink), workgroups, n, _stream(stream))
+    if launch(max(1, iters // 10)) != 0:
+        raise StreamBPError(-5, "debug_mfma_rate launch failed")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(repeats):
+        if launch(iters) != 0:
+            raise StreamBPError(-5, "debug_mfma_rate launch failed")
+    e1.record()
+    e1.synchronize()
+    flops = 2.0 * 32 * 32 * 16 * 8 * iters * 8 * workgroups * repeats
+    return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
 def _profile_kind_names():

@@ -168,6 +168,11 @@ extern "C" int streambp_debug_gemm_dw_segments(int n, int M, int N, const int* K
   return e == hipSuccess ? (seg ? 1 : 0) : -5;
 }
 
+extern "C" int streambp_debug_mfma_rate(const void* operands, float* sink, int workgroups, int iters, void* stream) {
+  if (!operands || !sink) return -1;
+  return sbp::mfma_rate_probe(operands, sink, workgroups, iters, (hipStream_t)stream) == hipSuccess ? 0 : -5;
+}
+
 // Per-launch timing with HIP events recorded on the launch stream around each GEMM kernel / attention launch
 // sequence.  begin: creates 2*max_records events and switches recording on.  end: synchronises the events and
 // returns per kind (see prof:: in launch.h; N_KIND entries) the launch count, the summed duration in ms, the

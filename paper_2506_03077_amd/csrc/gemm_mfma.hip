@@ -827,4 +827,41 @@ hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ---- what the matrix pipe sustains on its own -------------------------------------------------------------
+// Eight independent 32x32x16 products per round on fragments that never change: no LDS, no memory traffic, two waves
+// per SIMD.  The rate depends on the VALUES of the fragments (power management), which is why the caller supplies them.
+__global__ __launch_bounds__(NTHREADS) void mfma_rate_probe_k(const bf16x8* __restrict__ operands, float* __restrict__ sink, int iters) {
+  bf16x8 a[FM], b[FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) a[i] = operands[(threadIdx.x + i * NTHREADS) % 4096];
+#pragma unroll
+  for (int j = 0; j < FN; ++j) b[j] = operands[(threadIdx.x + (FM + j) * NTHREADS) % 4096];
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += acc[i][j][r];
+  sink[(int64_t)blockIdx.x * NTHREADS + threadIdx.x] = s;
+}
+hipError_t mfma_rate_probe(const void* operands, float* sink, int workgroups, int iters, hipStream_t st) {
+  if (workgroups <= 0 || iters < 0) return hipErrorInvalidValue;
+  mfma_rate_probe_k<<<workgroups, NTHREADS, 0, st>>>((const bf16x8*)operands, sink, iters);
+  return hipGetLastError();
+}
+
 }  // namespace sbp
