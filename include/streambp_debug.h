@@ -20,7 +20,10 @@ void streambp_debug_force_generic(int gemm_on, int attn_on);
 
 /* Which optional fusions the layer entry points use (process-wide switch, for A/B timing; results agree to rounding):
  * bit 0: SwiGLU adjoint in the epilogue of the dact = dy W_down GEMM instead of an elementwise pass;
- * bit 1: rotary embedding of q, and its adjoint on dq, inside the attention kernels instead of two elementwise passes.
+ * bit 1: rotary embedding of q, and its adjoint on dq, inside the attention kernels instead of two elementwise passes;
+ * bit 2: the LM head's logits GEMM stores bf16 softmax numerators exp(z - max of the 256-column block) straight into the
+ *        chunk's dz buffer (plus the block statistics and the target logits) instead of fp32 logits, and the row kernel
+ *        finishes dz in place (bf16 heads whose shapes the MFMA kernel takes; otherwise ignored).
  * The default is what measured fastest on MI355X. */
 void streambp_debug_set_fusions(int mask);
 int streambp_debug_get_fusions(void);
@@ -34,6 +37,15 @@ int streambp_debug_get_fusions(void);
 int streambp_debug_gemm(int M, int N, int K, int ta, int tb, int in_dt, int out_dt, int acc, const void *A, const void *B,
                         void *C, long long lda, long long ldb, long long ldc, void *scratch, size_t scratch_bytes,
                         void *hip_stream, const void *A2, const void *B2, void *row_stats);
+
+/* The softmax-numerator form of the store C = A B^T (A [M,K], B [N,K], bf16): E[m,n] (bf16, leading dimension lde) =
+ * exp(c[m,n] - max of row m over the 256-column block of n), stats [M, ceil(N/256)] = (that max, sum of the block's
+ * exponentials) and target_value[m] = c[m, targets[row_index ? row_index[m] : m]] in fp32 (entries whose target lies
+ * outside [0, N) are left untouched).  Device pointers; row_index may be NULL.  Returns 1 if the MFMA kernel ran it, 0 if
+ * it cannot take the problem (nothing is written then), -5 on a launch error. */
+int streambp_debug_gemm_numerators(int M, int N, int K, const void *A, const void *B, void *E, long long lda, long long ldb,
+                                   long long lde, void *stats, const int32_t *targets, const int32_t *row_index,
+                                   float *target_value, void *hip_stream);
 
 /* Weight-gradient form over n <= 8 reduction segments: C[M,N] += sum_s A_s^T B_s with A_s [K_s, M], B_s [K_s, N];
  * A, B, rows_dev are host arrays of n device pointers (rows_dev, optional, and its entries, optional: device int32

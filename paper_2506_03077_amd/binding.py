@@ -149,6 +149,9 @@ def lib():
         L.streambp_debug_profile_end.argtypes = [C.POINTER(C.c_longlong), C.POINTER(C.c_double), C.POINTER(C.c_double),
                                                  C.POINTER(C.c_double)]
         L.streambp_debug_profile_kinds.restype = C.c_int
+        L.streambp_debug_gemm_numerators.restype = C.c_int
+        L.streambp_debug_gemm_numerators.argtypes = [C.c_int, C.c_int, C.c_int, vp, vp, vp, C.c_longlong, C.c_longlong, C.c_longlong,
+                                                     vp, vp, vp, vp, vp]
         L.streambp_debug_mfma_rate.restype = C.c_int
         L.streambp_debug_mfma_rate.argtypes = [vp, vp, C.c_int, C.c_int, vp]
         _lib = L
@@ -431,8 +434,8 @@ def streambp_attn_tile_pairs(q_start, q_len):
 
 
 def debug_set_fusions(mask):
-    """Optional fusions of the layer path (bit 0: SwiGLU adjoint in the dact GEMM's epilogue; bit 1: RoPE of q / dq inside
-    the attention kernels); returns the previous mask."""
+    """Optional fusions (bit 0: SwiGLU adjoint in the dact GEMM's epilogue; bit 1: RoPE of q / dq inside the attention
+    kernels; bit 2: the LM head's logits GEMM stores bf16 softmax numerators instead of fp32 logits); returns the previous mask."""
     old = lib().streambp_debug_get_fusions()
     lib().streambp_debug_set_fusions(int(mask))
     return old
@@ -473,6 +476,19 @@ def debug_gemm_dw_segments(As, Bs, C_out, M, N, Ks, rows_dev=None, stream=None):
     return rc
 
 
+def debug_gemm_numerators(A, B, E, stats, targets, target_value, row_index=None, stream=None):
+    """E (bf16 [M,N]) = exp(A B^T - block max), stats [M, ceil(N/256), 2], target_value [M] (see streambp_debug.h).  Returns 1
+    if the MFMA kernel ran."""
+    M, K = A.shape
+    N = B.shape[0]
+    rc = lib().streambp_debug_gemm_numerators(M, N, K, _ptr(A), _ptr(B), _ptr(E), A.stride(0), B.stride(0), E.stride(0), _ptr(stats),
+                                              _ptr(targets), _ptr(row_index) if row_index is not None else None, _ptr(target_value),
+                                              _stream(stream))
+    if rc < 0:
+        raise StreamBPError(rc, "debug_gemm_numerators launch failed")
+    return rc
+
+
 def debug_mfma_rate(operands, workgroups=512, iters=10000, repeats=12, stream=None):
     """TFLOP/s the matrix pipe sustains on fragments taken from `operands` (a bf16 device tensor of 32768 values: the rate
     depends on the values) with no memory traffic: streambp_debug_mfma_rate timed with events on the launch stream.  The
@@ -499,7 +515,7 @@ def _profile_kind_names():
     names = [f"gemm_mfma_k<{t}, {m}>" for t, _ in lay for m in range(4)]
     names += [f"gemm_mfma_group_k<{t}, {m}>" for t, _ in lay for m in range(4)]
     names += ["gemm_generic_k", "attn_fwd (launch sequence)", "attn_bwd (delta + dq + dkv launch sequence)", "gemm_mfma_seg_k",
-              "gemm_mfma_k<false, true, 5>", "gemm_mfma_k<false, false, 6>"]
+              "gemm_mfma_k<false, true, 5>", "gemm_mfma_k<false, false, 6>", "gemm_mfma_k<false, true, 7>"]
     return tuple(names)
 
 

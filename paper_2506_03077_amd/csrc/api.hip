@@ -570,7 +570,7 @@ static int32_t check_head_cfg(const sbp_head_cfg* c) {
 // chunk.  The fp32 logits - the dominant term - still exist for one chunk only.
 struct HeadWs {
   int dw_group;
-  float* z; void* dz[MAX_DW_GROUP]; float *row_loss, *seq_weight, *ell;
+  float* z; void* dz[MAX_DW_GROUP]; float *row_loss, *target_logit, *seq_weight, *ell;
   float2* stats; int n_stat;          // per row and 256-column block of the chunk's logits: (max, sum of exp), written by the logits GEMM
   int32_t *index, *chunk_rows; void *hc[MAX_DW_GROUP], *dhc;   // active-row compaction: row list, rows per chunk, gathered h / dh rows
   float* gemm_scratch; size_t gemm_scratch_bytes; size_t bytes;
@@ -584,6 +584,7 @@ static HeadWs carve_head(const sbp_head_cfg* c, void* ws) {
   h.dw_group = dw_group_for(cm, c->dw_group_rows, DW_GROUP_ROWS_HEAD);
   for (int g = 0; g < h.dw_group; ++g) h.dz[g] = cv.take_bytes(cm * c->vocab * dtype_size(c->dtype));
   h.row_loss = cv.take<float>(cm);
+  h.target_logit = cv.take<float>(cm);
   h.n_stat = (int)cdiv(c->vocab, GEMM_STAT_COLS);
   h.stats = cv.take<float2>(cm * (size_t)h.n_stat);
   h.seq_weight = cv.take<float>(c->batch);
@@ -643,14 +644,25 @@ int32_t streambp_lmhead_ce_backward(const sbp_head_cfg* c, const void* w, const 
     void* hc = s.hc[n_pending];
     void* dz = s.dz[n_pending];
     HIPCHK(gather_rows(dt, h, idx, n_dev, hc, n, d, st));
+    // The logits: fp32 with (max, sum of exp) per row and 256-column block out of the GEMM's epilogue where the MFMA kernel
+    // takes the problem - or, better, never as logits at all: the numerator form leaves exp(z - block max) in bf16 directly in
+    // the chunk's dz buffer plus the target logits, and the row kernel finishes dz in place.
     GemmArgs gz = fwd_gemm(hc, w, s.z, n, V, d, dt, DT_F32);
     gz.rows_dev = n_dev;
     gz.row_stats = s.stats;
-    const bool stats = s.n_stat > 0 && gemm_row_stats_supported(gz);   // the LSE statistics come out of the GEMM's epilogue
+    bool numer = false;
+    if ((fusion_mask() & FUSE_NUMERATORS) && dt == DT_BF16 && s.n_stat > 0) {
+      GemmArgs gn = fwd_gemm(hc, w, dz, n, V, d, dt, DT_BF16);
+      gn.rows_dev = n_dev; gn.row_stats = s.stats;
+      gn.numer_targets = targets; gn.numer_row_index = idx; gn.numer_target_value = s.target_logit;
+      if (gemm_numerators_supported(gn)) { gz = gn; numer = true; }
+    }
+    const bool stats = numer || (s.n_stat > 0 && gemm_row_stats_supported(gz));   // the LSE statistics come out of the GEMM's epilogue
     if (!stats) gz.row_stats = nullptr;
     HIPCHK(gemm(gz, st));
     HeadRowArgs a{};
     a.stats = stats ? s.stats : nullptr; a.n_stat = s.n_stat;
+    a.target_logit = numer ? s.target_logit : nullptr;
     a.dt = dt; a.objective = c->objective; a.z = s.z; a.dz = dz; a.targets = targets;
     a.old_logp = old_logp; a.ref_logp = ref_logp;
     a.advantages = advantages; a.seq_weight = s.seq_weight; a.row0 = 0; a.row_index = idx; a.rows_dev = n_dev;

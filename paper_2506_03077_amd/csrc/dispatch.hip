@@ -15,6 +15,7 @@ bool gemm_mfma_eligible(const GemmArgs& g);
 bool gemm_mfma_pair_ok(const GemmArgs& g);
 bool gemm_mfma_stats_ok(const GemmArgs& g);
 bool gemm_mfma_swiglu_ok(const GemmArgs& g);
+bool gemm_mfma_numer_ok(const GemmArgs& g);
 bool gemm_mfma_group_eligible(const GemmArgs* gs, int n, bool small_ok);
 hipError_t gemm_mfma_group(const GemmArgs* gs, int n, hipStream_t st);
 bool gemm_mfma_seg_eligible(const GemmArgs* gs, int n);
@@ -32,7 +33,7 @@ static std::atomic<bool> g_force_generic_attn{false};
 static std::atomic<long long> g_generic_bf16_launches{0};
 long long generic_bf16_launches() { return g_generic_bf16_launches.load(); }
 void note_generic_bf16_launch() { ++g_generic_bf16_launches; }
-static std::atomic<int> g_fusion_mask{FUSE_ROPE_Q};
+static std::atomic<int> g_fusion_mask{FUSE_ROPE_Q | FUSE_NUMERATORS};
 int fusion_mask() { return g_fusion_mask.load(); }
 void set_fusion_mask(int mask) { g_fusion_mask.store(mask); }
 
@@ -41,6 +42,7 @@ void attn_set_force_generic(bool on) { g_force_generic_attn = on; }
 
 bool gemm_uses_mfma(const GemmArgs& g) { return !g_force_generic_gemm && gemm_mfma_eligible(g); }
 bool gemm_row_stats_supported(const GemmArgs& g) { return gemm_uses_mfma(g) && gemm_mfma_stats_ok(g); }
+bool gemm_numerators_supported(const GemmArgs& g) { return gemm_uses_mfma(g) && gemm_mfma_numer_ok(g); }
 bool attn_uses_mfma(int dt, int dh, int Hq, int Hkv) { return !g_force_generic_attn && attn_mfma_eligible(dt, dh, Hq, Hkv); }
 
 // ---- optional per-launch timing (off by default; events are created when profiling is switched on,
@@ -74,7 +76,9 @@ static double causal_pairs(const AttnArgs& a) {   // visible (query, key) pairs 
 }
 
 hipError_t gemm(const GemmArgs& g, hipStream_t st) {
-  if (g.row_stats && !gemm_row_stats_supported(g)) return hipErrorInvalidValue;   // only the MFMA store form emits them
+  if (g.numer_targets) {
+    if (!gemm_numerators_supported(g)) return hipErrorInvalidValue;               // only the MFMA store form has them
+  } else if (g.row_stats && !gemm_row_stats_supported(g)) return hipErrorInvalidValue;   // only the MFMA store form emits them
   if (g.swiglu_gate && !(gemm_uses_mfma(g) && gemm_mfma_swiglu_ok(g))) {   // no fused epilogue for this problem: product, then the elementwise kernel
     GemmArgs plain = g;
     plain.swiglu_gate = plain.swiglu_up = plain.swiglu_act = nullptr;
@@ -166,6 +170,16 @@ extern "C" int streambp_debug_gemm_dw_segments(int n, int M, int N, const int* K
   const bool seg = !sbp::g_force_generic_gemm.load() && sbp::gemm_mfma_seg_eligible(gs, n);
   hipError_t e = sbp::gemm_batch(gs, n, (hipStream_t)stream);
   return e == hipSuccess ? (seg ? 1 : 0) : -5;
+}
+
+extern "C" int streambp_debug_gemm_numerators(int M, int N, int K, const void* A, const void* B, void* E, long long lda, long long ldb,
+                                              long long lde, void* stats, const int32_t* targets, const int32_t* row_index,
+                                              float* target_value, void* stream) {
+  sbp::GemmArgs g{A, B, E, M, N, K, lda, ldb, lde, false, true, sbp::DT_BF16, sbp::DT_BF16, false};
+  g.row_stats = (float2*)stats;
+  g.numer_targets = targets; g.numer_row_index = row_index; g.numer_target_value = target_value;
+  if (!sbp::gemm_numerators_supported(g)) return 0;
+  return sbp::gemm(g, (hipStream_t)stream) == hipSuccess ? 1 : -5;
 }
 
 extern "C" int streambp_debug_mfma_rate(const void* operands, float* sink, int workgroups, int iters, void* stream) {

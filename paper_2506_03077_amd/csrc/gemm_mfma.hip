@@ -153,9 +153,11 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int n_tiles) {
 //       4 = accumulate into a bf16 C (read, add in fp32, round once; weight-gradient form only),
 //       5 = store fp32 and emit per-row (max, sum of exp) pairs over the tile's columns (`stats`)
 //       6 = C is not stored: the tile is the gradient wrt act = silu(gate) * up and the epilogue writes act, d gate, d up
+//       7 = like 5, but C (bf16) receives exp(c - block max) instead of c, and the value of each row's target column is kept
 constexpr bool mode_accumulates(int mode) { return mode == 2 || mode == 4; }
-constexpr bool mode_swaps_operands(int mode) { return mode == 5 || mode == 6; }   // accumulators hold C^T blocks
+constexpr bool mode_swaps_operands(int mode) { return mode == 5 || mode == 6 || mode == 7; }   // accumulators hold C^T blocks
 struct SwigluFuse { bf16_t* gate; bf16_t* up; bf16_t* act; };
+struct NumerFuse { const int32_t* targets; const int32_t* row_index; float* target_value; };
 //
 // The main loop is written so that it contains no vector ALU instructions at all: global addresses are an SGPR base
 // (advanced with scalar adds) plus per-lane offsets computed once, LDS fragment addresses are computed once per
@@ -176,7 +178,8 @@ struct KSegments {
 template <bool TA, bool TB, int MODE>
 __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restrict__ Cv, int M, int N, int64_t lda,
                                           int64_t ldb, int64_t ldc, int tm, int tn, char (&smem)[NSTAGE][2][TILE_BYTES],
-                                          float2* __restrict__ stats = nullptr, SwigluFuse sw = SwigluFuse{nullptr, nullptr, nullptr}) {
+                                          float2* __restrict__ stats = nullptr, SwigluFuse sw = SwigluFuse{nullptr, nullptr, nullptr},
+                                          NumerFuse nf = NumerFuse{nullptr, nullptr, nullptr}) {
   static_assert(NSTAGE == 2, "the main loop is unrolled over two LDS stages");
   constexpr bool AMN = TA, BMN = !TB;     // operand kept reduction-major in LDS (B stored [N,K] is the K-contiguous case)
   const int m0 = tm * BM, n0 = tn * BN;
@@ -419,6 +422,92 @@ __device__ __forceinline__ void gemm_tile(const KSegments& segs, void* __restric
     }
     return;
   }
+  if constexpr (MODE == 7) {
+    // Softmax numerators (Sec. 5 names fused backward operators as the way to cut the per-chunk HBM passes): what the row
+    // kernel after the logits GEMM needs of a row is exp(c - lse), and exp(c - max of the 256-column block) differs from it
+    // by one factor per block - so the tile stores that, in bf16 (half the bytes of the fp32 logits, and the exponentials
+    // are the ones the block's sum needs anyway), next to the block's (max, sum) pair; the sum is taken from the
+    // unrounded values.  The logit of each row's target column, which the loss needs exactly, is kept in fp32 on the side.
+    // Same accumulator layout as MODE 5 (C^T blocks: a lane owns one row and 32 of its columns).  The four waves that
+    // share a row exchange their maxima before the exponentials and their sums after them.
+    static_assert(FN == 2, "two column blocks per wave");
+    typedef bf16_t bf16x4e __attribute__((ext_vector_type(4)));
+    __syncthreads();
+    float* pmax = (float*)&smem[0][0][0];      // [NWAVE_N][BM]
+    float* psum = pmax + NWAVE_N * BM;         // [NWAVE_N][BM]
+    constexpr float LOG2E = 1.4426950408889634f;
+    const int wn = wave % NWAVE_N;
+    const int col0 = n0 + wn0 + 4 * (lane >> 5);                 // first of the lane's columns; quads at + j * 32 + 8 * q
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row_l = wm0 + i * 32 + (lane & 31);
+      if (n0 + BN > N) {                                         // ragged last column tile: columns past N take no part
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (col0 + j * 32 + 8 * q >= N) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = -INFINITY;
+            }
+      }
+      if (m0 + row_l < M) {                                      // the target's logit, if it lies among the lane's columns
+        const int r = nf.row_index ? nf.row_index[m0 + row_l] : m0 + row_l;
+        const int d = nf.targets[r] - col0;
+        if (d >= 0 && d < 64 && (d & 4) == 0) {
+          float zt = 0.f;
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (d == j * 32 + 8 * q + e) zt = acc[i][j][4 * q + e];
+          if (zt != -INFINITY) nf.target_value[m0 + row_l] = zt;   // (-inf: a masked column past N, i.e. an invalid target)
+        }
+      }
+      float mx = acc[i][0][0];
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[i][j][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      if (lane < 32) pmax[wn * BM + row_l] = mx;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row_l = wm0 + i * 32 + (lane & 31);
+      float m = pmax[row_l];
+#pragma unroll
+      for (int w = 1; w < NWAVE_N; ++w) m = fmaxf(m, pmax[w * BM + row_l]);   // finite: wave 0 always holds valid columns
+      bf16_t* crow = Cb + (int64_t)(m0 + row_l) * ldc + col0;
+      float se = 0.f;
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          bf16x4e o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float ex = __builtin_amdgcn_exp2f((acc[i][j][4 * q + e] - m) * LOG2E);   // difference first: exact near the maximum
+            se += ex;
+            o[e] = (bf16_t)ex;
+          }
+          if (m0 + row_l < M && col0 + j * 32 + 8 * q < N) *(bf16x4e*)(crow + j * 32 + 8 * q) = o;
+        }
+      se += __shfl_xor(se, 32, WAVE);
+      if (lane < 32) psum[wn * BM + row_l] = se;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < BM && m0 + (int)threadIdx.x < M) {
+      float m = pmax[threadIdx.x], sum = psum[threadIdx.x];
+#pragma unroll
+      for (int w = 1; w < NWAVE_N; ++w) { m = fmaxf(m, pmax[w * BM + threadIdx.x]); sum += psum[w * BM + threadIdx.x]; }
+      stats[(int64_t)(m0 + (int)threadIdx.x) * ((N + BN - 1) / BN) + tn] = make_float2(m, sum);
+    }
+    return;
+  }
   if constexpr (MODE == 6) {
     // SwiGLU adjoint on the accumulators (Sec. 5 names fused backward operators as the way to cut the per-chunk HBM
     // passes): the products were formed with the operands swapped, so a lane owns one row of the tile and, per column
@@ -488,7 +577,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
                                                         int64_t ldb, int64_t ldc, int k_per_split,
                                                         const int* __restrict__ rows_dev, int xcds_per_split,
                                                         const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2,
-                                                        float2* __restrict__ row_stats, SwigluFuse sw) {
+                                                        float2* __restrict__ row_stats, SwigluFuse sw, NumerFuse nf) {
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE][2][TILE_BYTES];   // [stage][A|B]
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN, n_tiles = tiles_m * tiles_n;
   int tm, tn, split = 0;
@@ -523,7 +612,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_mfma_k(const bf16_t* __restrict
   if (k_end <= k_begin && mode_accumulates(MODE)) return;   // nothing to add
   KSegments segs;
   segs.n = 1; segs.A[0] = A; segs.B[0] = B; segs.K[0] = K; segs.k_begin[0] = k_begin; segs.k_end[0] = k_end;
-  gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem, row_stats, sw);
+  gemm_tile<TA, TB, MODE>(segs, Cv, M, N, lda, ldb, ldc, tm, tn, smem, row_stats, sw, nf);
 }
 
 // Weight-gradient form with a segmented reduction: C += sum_s A_s^T B_s, every segment with its own run-time row
@@ -639,7 +728,13 @@ bool gemm_mfma_swiglu_ok(const GemmArgs& g) {
 
 // the row-statistics epilogue exists for the fp32 store form of C = A B^T
 bool gemm_mfma_stats_ok(const GemmArgs& g) {
-  return !g.ta && g.tb && g.out_dt == DT_F32 && !g.acc && !g.A2 && !((uintptr_t)g.row_stats & 7);
+  return !g.ta && g.tb && g.out_dt == DT_F32 && !g.acc && !g.A2 && !((uintptr_t)g.row_stats & 7) && !g.numer_targets;
+}
+
+// ... and its softmax-numerator variant for a bf16 C
+bool gemm_mfma_numer_ok(const GemmArgs& g) {
+  return !g.ta && g.tb && g.out_dt == DT_BF16 && !g.acc && !g.A2 && g.row_stats && !((uintptr_t)g.row_stats & 7) &&
+         g.numer_targets && g.numer_target_value && !g.swiglu_gate;
 }
 
 constexpr int MAX_SPLITS = 8;
@@ -681,7 +776,8 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
 #define LAUNCH(TA, TB, MODE, CPTR) \
   gemm_mfma_k<TA, TB, MODE><<<grid, NTHREADS, 0, st>>>(A, B, CPTR, g.M, g.N, g.K, g.lda, g.ldb, g.ldc, k_per_split, g.rows_dev, \
                                                        xcds_per_split, (const bf16_t*)g.A2, (const bf16_t*)g.B2, g.row_stats, \
-                                                       SwigluFuse{(bf16_t*)g.swiglu_gate, (bf16_t*)g.swiglu_up, (bf16_t*)g.swiglu_act})
+                                                       SwigluFuse{(bf16_t*)g.swiglu_gate, (bf16_t*)g.swiglu_up, (bf16_t*)g.swiglu_act}, \
+                                                       NumerFuse{g.numer_targets, g.numer_row_index, g.numer_target_value})
 #define LAUNCH_LAYOUT(MODE, CPTR)                       \
   do {                                                  \
     if (!g.ta && g.tb) LAUNCH(false, true, MODE, CPTR); \
@@ -690,7 +786,7 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
   } while (0)
   const int layout = g.ta ? 2 : (g.tb ? 0 : 1);
   const int mode = splits > 1 ? 3 : (g.acc ? 2 : (g.out_dt == DT_BF16 ? 1 : 0));   // (both accumulate forms are timed as one kind)
-  const int kind = g.row_stats ? (int)prof::GEMM_STATS : g.swiglu_gate ? (int)prof::GEMM_SWIGLU : prof::GEMM_SINGLE + layout * 4 + mode;
+  const int kind = g.numer_targets ? (int)prof::GEMM_NUMER : g.row_stats ? (int)prof::GEMM_STATS : g.swiglu_gate ? (int)prof::GEMM_SWIGLU : prof::GEMM_SINGLE + layout * 4 + mode;
   const double work = 2.0 * g.M * g.N * g.K * (g.A2 ? 2 : 1);
   if (splits > 1) {
     {
@@ -708,7 +804,8 @@ hipError_t gemm_mfma(const GemmArgs& g, hipStream_t st) {
     return hipGetLastError();
   }
   prof::Scope sc(kind, work, g.rows_dev != nullptr, st);
-  if (g.row_stats) LAUNCH(false, true, 5, g.C);
+  if (g.numer_targets) LAUNCH(false, true, 7, g.C);
+  else if (g.row_stats) LAUNCH(false, true, 5, g.C);
   else if (g.swiglu_gate) LAUNCH(false, false, 6, g.C);
   else if (g.out_dt == DT_BF16 && g.acc) LAUNCH(true, false, 4, g.C);
   else if (g.out_dt == DT_BF16) LAUNCH_LAYOUT(1, g.C);

@@ -12,6 +12,34 @@ namespace sbp {
 
 constexpr int HR_THREADS = 512;
 
+// Per-token coefficient of (onehot - softmax) in dz and the row's loss term, from the log-probability of the target
+// (Sec. 3.2.1: SFT, GRPO; DPO before its final correction).
+__device__ __forceinline__ void objective_terms(const HeadRowArgs& a, float logp, int64_t orig, int64_t aux, float& coef, float& loss_term) {
+  if (a.objective == 0) {                     // SFT: L = -scale * sum logp
+    coef = -a.loss_scale;
+    loss_term = -a.loss_scale * logp;
+  } else if (a.objective == 1) {              // GRPO
+    const int64_t seq = orig / a.T;
+    const float wgt = a.seq_weight[seq], adv = a.advantages[seq];
+    const float r = a.old_logp ? expf(logp - a.old_logp[aux]) : 1.0f;
+    const float unclipped = r * adv;
+    const float clipped = fminf(fmaxf(r, 1.0f - a.clip_eps), 1.0f + a.clip_eps) * adv;
+    const float surr = fminf(unclipped, clipped);
+    const float dsurr = (unclipped <= clipped) ? unclipped : 0.0f;
+    const float ref = a.ref_logp[aux];
+    float kl, dkl;
+    if (a.kl_mode == 0) { kl = logp - ref; dkl = 1.0f; }
+    else { const float e = expf(ref - logp); kl = e - (ref - logp) - 1.0f; dkl = 1.0f - e; }
+    loss_term = -wgt * (surr - a.kl_beta * kl);
+    coef = -wgt * (dsurr - a.kl_beta * dkl);
+  } else {                                    // DPO, before the final in-place correction
+    const int64_t seq = orig / a.T;
+    const float sign = (seq == 0) ? 1.0f : -1.0f;
+    coef = a.kl_beta * sign;
+    loss_term = sign * (logp - a.ref_logp[aux]);   // summand of ell
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
   __shared__ float red[16];
@@ -69,29 +97,7 @@ __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
   const float logp = z[tgt] - lse;
 
   float coef, loss_term;
-  if (a.objective == 0) {                     // SFT: L = -scale * sum logp
-    coef = -a.loss_scale;
-    loss_term = -a.loss_scale * logp;
-  } else if (a.objective == 1) {              // GRPO
-    const int64_t seq = orig / a.T;
-    const float wgt = a.seq_weight[seq], adv = a.advantages[seq];
-    const float r = a.old_logp ? expf(logp - a.old_logp[aux]) : 1.0f;
-    const float unclipped = r * adv;
-    const float clipped = fminf(fmaxf(r, 1.0f - a.clip_eps), 1.0f + a.clip_eps) * adv;
-    const float surr = fminf(unclipped, clipped);
-    const float dsurr = (unclipped <= clipped) ? unclipped : 0.0f;
-    const float ref = a.ref_logp[aux];
-    float kl, dkl;
-    if (a.kl_mode == 0) { kl = logp - ref; dkl = 1.0f; }
-    else { const float e = expf(ref - logp); kl = e - (ref - logp) - 1.0f; dkl = 1.0f - e; }
-    loss_term = -wgt * (surr - a.kl_beta * kl);
-    coef = -wgt * (dsurr - a.kl_beta * dkl);
-  } else {                                    // DPO, before the final in-place correction
-    const int64_t seq = orig / a.T;
-    const float sign = (seq == 0) ? 1.0f : -1.0f;
-    coef = a.kl_beta * sign;
-    loss_term = sign * (logp - a.ref_logp[aux]);   // summand of ell
-  }
+  objective_terms(a, logp, orig, aux, coef, loss_term);
   if (tid == 0) a.row_loss[row] = loss_term;
   if (vec && sizeof(T) == 2) {
     typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
@@ -115,8 +121,63 @@ __global__ __launch_bounds__(HR_THREADS) void head_rows_k(HeadRowArgs a) {
   }
 }
 
+// Numerator form: the logits GEMM left exp(z - block max) in dz (bf16), the (max, sum) pair of every 256-column block in
+// stats and z[target] in target_logit.  One pass, in place: dz = coef * (onehot - numerator * exp(block max - lse)) -
+// one multiply per element, the factor changes once per block.
+typedef bf16_t bf16x8h __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(HR_THREADS) void head_rows_numer_k(HeadRowArgs a) {
+  __shared__ float red[16];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  if (a.rows_dev && row >= *a.rows_dev) return;
+  bf16x8h* dz8 = (bf16x8h*)((bf16_t*)a.dz + (int64_t)row * a.V);
+  const int64_t orig = a.row_index ? (int64_t)a.row_index[row] : a.row0 + row;
+  const int64_t aux = a.row_index ? orig : (int64_t)row;
+  const int tgt = a.targets[aux];
+  const int n8 = a.V / 8;
+  if (tgt < 0 || tgt >= a.V) {   // ignored row: exact zeros, no loss term
+    bf16x8h zero;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) zero[k] = (bf16_t)0.0f;
+    for (int v = tid; v < n8; v += HR_THREADS) dz8[v] = zero;
+    if (tid == 0) a.row_loss[row] = 0.f;
+    return;
+  }
+  const float2* ps = a.stats + (int64_t)row * a.n_stat;
+  float mx = -INFINITY, se = 0.f;
+  for (int t = tid; t < a.n_stat; t += HR_THREADS) {
+    const float2 p = ps[t];
+    const float m2 = fmaxf(mx, p.x);
+    se = se * __expf(mx - m2) + p.y * __expf(p.x - m2);
+    mx = m2;
+  }
+  {
+    const float gmx = block_max(mx, red);
+    se = block_sum(mx == -INFINITY ? 0.f : se * __expf(mx - gmx), red);
+    mx = gmx;
+  }
+  const float lse = mx + logf(se);
+  const float logp = a.target_logit[row] - lse;
+  float coef, loss_term;
+  objective_terms(a, logp, orig, aux, coef, loss_term);
+  if (tid == 0) a.row_loss[row] = loss_term;
+  for (int v = tid; v < n8; v += HR_THREADS) {
+    const int v0 = v * 8;
+    const float f = coef * __expf(ps[v0 / GEMM_STAT_COLS].x - lse);   // 8 | 256: the eight elements share a block
+    const bf16x8h e = dz8[v];
+    bf16x8h o;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = (bf16_t)((v0 + k == tgt ? coef : 0.0f) - (float)e[k] * f);
+    dz8[v] = o;
+  }
+}
+
 hipError_t head_rows(const HeadRowArgs& a, hipStream_t st) {
   if (a.rows == 0) return hipSuccess;
+  if (a.target_logit) {
+    if (a.dt != DT_BF16 || !a.stats || a.V % 8 != 0 || ((uintptr_t)a.dz & 15)) return hipErrorInvalidValue;
+    head_rows_numer_k<<<a.rows, HR_THREADS, 0, st>>>(a);
+    return hipGetLastError();
+  }
   if (a.dt == DT_BF16) head_rows_k<bf16_t><<<a.rows, HR_THREADS, 0, st>>>(a);
   else head_rows_k<float><<<a.rows, HR_THREADS, 0, st>>>(a);
   return hipGetLastError();

@@ -31,6 +31,16 @@ struct GemmArgs {
   // gemm_row_stats_supported first): row_stats[m * ceil(N / GEMM_STAT_COLS) + t] = (max, sum of exp(c - max)) of row m
   // over the columns [t * GEMM_STAT_COLS, (t + 1) * GEMM_STAT_COLS), taken from the fp32 accumulators.
   float2* row_stats = nullptr;
+  // Optional "softmax numerators" form of the row-statistics store (C bf16, MFMA kernel only: ask
+  // gemm_numerators_supported first).  C does not receive the product c but exp(c - max), max being the row's maximum
+  // over the element's block of GEMM_STAT_COLS columns - the same (max, sum of exp) pairs go to row_stats, the sums
+  // taken from the unrounded fp32 values - and the product's value in column numer_targets[r] of row m goes to
+  // numer_target_value[m] (fp32), r = numer_row_index ? numer_row_index[m] : m; a target outside [0, N) matches no
+  // column and leaves the entry untouched.  What a softmax over the row needs is then all there in half the bytes:
+  // softmax(c)[n] = C[m, n] * exp(max_block(n) - lse(m)).
+  const int32_t* numer_targets = nullptr;
+  const int32_t* numer_row_index = nullptr;
+  float* numer_target_value = nullptr;
   // Optional fused SwiGLU adjoint (store form C = A B with the same row-major [M, N] layout and leading dimension for
   // C, gate, up and act; bf16): the product is the gradient wrt act = silu(gate) * up and is never stored; instead the
   // epilogue reads the tile's gate and up values and writes act (what the forward would have produced; optional),
@@ -42,6 +52,7 @@ struct GemmArgs {
 };
 constexpr int GEMM_STAT_COLS = 256;
 bool gemm_row_stats_supported(const GemmArgs& g);
+bool gemm_numerators_supported(const GemmArgs& g);
 // upper bound of the scratch a GEMM with M <= max_m rows and N <= max_n columns may use
 size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits);
 hipError_t gemm(const GemmArgs& g, hipStream_t st);
@@ -53,8 +64,9 @@ bool gemm_uses_mfma(const GemmArgs& g);
 // force the generic kernel (debug / A-B tests)
 void gemm_set_force_generic(bool on);
 // which of the optional fusions the entry points use (A/B measurements): bit 0 = SwiGLU adjoint in the epilogue of the
-// dact GEMM, bit 1 = rotary embedding of q / its adjoint on dq inside the attention kernels
-enum { FUSE_SWIGLU = 1, FUSE_ROPE_Q = 2 };
+// dact GEMM, bit 1 = rotary embedding of q / its adjoint on dq inside the attention kernels, bit 2 = the LM head's logits
+// GEMM stores bf16 softmax numerators (and the target logits) instead of fp32 logits
+enum { FUSE_SWIGLU = 1, FUSE_ROPE_Q = 2, FUSE_NUMERATORS = 4 };
 int fusion_mask();
 void set_fusion_mask(int mask);
 // bf16 problems that have run on the shape-agnostic kernels since the library was loaded
@@ -65,8 +77,10 @@ void note_generic_bf16_launch();
 namespace prof {
 // kinds 0..11: gemm_mfma_k<layout, mode> with layout NT=0, NN=1, TN=2 and mode 0..3; 12..23: the grouped kernel;
 // then the shape-agnostic GEMM, the attention forward / backward launch sequences, the segmented weight-gradient GEMM and the
-// store form with row statistics (gemm_mfma_k<NT, 5>) and the input-gradient form with the fused SwiGLU adjoint (gemm_mfma_k<NN, 6>)
-enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, GEMM_SEG = 27, GEMM_STATS = 28, GEMM_SWIGLU = 29, N_KIND = 30 };
+// store form with row statistics (gemm_mfma_k<NT, 5>), the input-gradient form with the fused SwiGLU adjoint (gemm_mfma_k<NN, 6>)
+// and the softmax-numerator store (gemm_mfma_k<NT, 7>)
+enum { GEMM_SINGLE = 0, GEMM_GROUP = 12, GEMM_GENERIC = 24, ATTN_FWD = 25, ATTN_BWD = 26, GEMM_SEG = 27, GEMM_STATS = 28, GEMM_SWIGLU = 29,
+       GEMM_NUMER = 30, N_KIND = 31 };
 struct Scope {
   hipStream_t st; bool active = false; int kind = 0; double work = 0; bool bounded = false; hipEvent_t e0{}, e1{};
   // bounded: `work` was computed from a host-side upper bound of a run-time row count
@@ -146,8 +160,8 @@ constexpr int ATTN_TILE_K = 64;    // keys per inner step
 struct HeadRowArgs {
   int dt;                   // type of dz
   int objective;            // 0 SFT, 1 GRPO, 2 DPO
-  const float* z;           // [rows, V] fp32 logits of the chunk
-  void* dz;                 // [rows, V] dt
+  const float* z;           // [rows, V] fp32 logits of the chunk (unused in the numerator form)
+  void* dz;                 // [rows, V] dt; numerator form (target_logit != NULL): holds exp(z - block max) on entry
   const int32_t* targets;   // [rows] (already offset to the chunk)
   const float* old_logp;    // [rows] or NULL
   const float* ref_logp;    // [rows] or NULL
@@ -159,6 +173,7 @@ struct HeadRowArgs {
   const int* rows_dev;      // optional device-side count of valid chunk rows (<= rows)
   const float2* stats;      // optional [rows, n_stat]: per row and column block (max, sum of exp(z - max)) from the logits
   int n_stat;               // GEMM; the kernel then reads z once instead of twice
+  const float* target_logit; // optional [rows]: z[row, target] from the logits GEMM's numerator form (needs stats, bf16 dz)
   int rows, V, T;
   float loss_scale, clip_eps, kl_beta; int kl_mode;
   float* row_loss;          // [rows] scratch: per-row loss term (DPO: per-row signed log-ratio)

@@ -42,18 +42,23 @@ static void touch_gemm(const GemmArgs& g) {
     wr(g.C, c_el * es(g.out_dt));
   }
   if (g.row_stats) wr(g.row_stats, (size_t)g.M * cdiv(g.N, GEMM_STAT_COLS) * sizeof(float2));
+  if (g.numer_targets) { wr(g.numer_target_value, (size_t)g.M * 4); if (g.numer_row_index) rd(g.numer_row_index, (size_t)g.M * 4); }
   if (g.rows_dev) rd(g.rows_dev, sizeof(int));
   // split-K partial slices: at most what gemm_scratch_bytes promises for 4 slices of a dense C
   if (g.scratch && g.ldc == g.N) wr(g.scratch, std::min(g.scratch_bytes, (size_t)4 * g.M * g.N * sizeof(float)));
 }
 bool gemm_row_stats_supported(const GemmArgs& g) { return g.in_dt == DT_BF16 && !g.ta && g.tb && g.out_dt == DT_F32 && g.N % 8 == 0 && g.K % 64 == 0; }
+bool gemm_numerators_supported(const GemmArgs& g) {
+  return g.in_dt == DT_BF16 && !g.ta && g.tb && g.out_dt == DT_BF16 && g.N % 8 == 0 && g.K % 64 == 0 && g.row_stats && g.numer_targets && g.numer_target_value;
+}
 size_t gemm_scratch_bytes(int max_m, int max_n, int max_splits) { return (size_t)std::min(max_splits, 8) * max_m * max_n * sizeof(float); }
 hipError_t gemm(const GemmArgs& g, hipStream_t) { touch_gemm(g); return hipSuccess; }
 hipError_t gemm_batch(const GemmArgs* gs, int n, hipStream_t, bool) { for (int i = 0; i < n; ++i) touch_gemm(gs[i]); return hipSuccess; }
 bool gemm_uses_mfma(const GemmArgs& g) { return g.in_dt == DT_BF16; }
 void gemm_set_force_generic(bool) {}
-int fusion_mask() { return FUSE_ROPE_Q; }
-void set_fusion_mask(int) {}
+static int g_mask = FUSE_ROPE_Q | FUSE_NUMERATORS;
+int fusion_mask() { return g_mask; }
+void set_fusion_mask(int m) { g_mask = m; }
 long long generic_bf16_launches() { return 0; }
 void note_generic_bf16_launch() {}
 namespace prof { Scope::Scope(int, double, bool, hipStream_t s) : st(s) {} Scope::~Scope() {} }
@@ -126,7 +131,8 @@ void attn_set_force_generic(bool) {}
 
 hipError_t head_rows(const HeadRowArgs& a, hipStream_t) {
   const size_t n = (size_t)a.rows * a.V;
-  rd(a.z, n * 4); wr(a.dz, n * es(a.dt)); wr(a.row_loss, (size_t)a.rows * 4);
+  if (a.target_logit) { rd(a.target_logit, (size_t)a.rows * 4); rd(a.dz, n * es(a.dt)); } else rd(a.z, n * 4);
+  wr(a.dz, n * es(a.dt)); wr(a.row_loss, (size_t)a.rows * 4);
   if (a.stats) rd(a.stats, (size_t)a.rows * a.n_stat * sizeof(float2));
   if (a.row_index) rd(a.row_index, (size_t)a.rows * 4);
   if (a.rows_dev) rd(a.rows_dev, 4);

@@ -273,3 +273,68 @@ def test_linear_example_closed_form():
     want_dW2 = np.repeat((X64 @ W164).sum(axis=0)[:, None], k, axis=1)     # Y^T 1
     assert_close(host(dW1), want_dW1, 5e-3, "dW1")
     assert_close(host(dW2), want_dW2, 5e-3, "dW2")
+
+
+def test_mfma_rate_probe_counts_what_it_claims():
+    # the benchmark's pure-MFMA probe: with all-one fragments every accumulator element grows by 16 per product, so each
+    # thread's sum over its 8 x 16 accumulator registers after n rounds is exactly 8 * 16 * 16 * n (the flop count it is
+    # credited with: 2 * 32*32*16 * 8 products per wave and round)
+    ones = torch.ones(32768, dtype=torch.bfloat16, device="cuda")
+    sink = torch.full((4 * 512,), -1.0, dtype=torch.float32, device="cuda")
+    for n in (0, 1, 37):
+        rc = sb.lib().streambp_debug_mfma_rate(ones.data_ptr(), sink.data_ptr(), 4, n, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert rc == 0
+        assert torch.all(sink == 8 * 16 * 16 * n), n
+    assert sb.lib().streambp_debug_mfma_rate(None, sink.data_ptr(), 4, 1, None) == -1
+    assert sb.debug_mfma_rate(ones, workgroups=64, iters=100, repeats=1) > 0
+
+
+def test_softmax_numerators_from_the_store_epilogue():
+    # The LM head's fused store (Sec. 5 names fused backward operators as future work): instead of the fp32 logits c the GEMM
+    # leaves E = exp(c - max of the row's 256-column block) in bf16, the block's (max, sum) pair and the fp32 logit of each
+    # row's target column.  Against fp64 products of the same bf16 inputs: the maxima and target logits to fp32 GEMM
+    # rounding, the sums likewise (they are taken from the unrounded exponentials), E to one bf16 rounding; a ragged last
+    # column block (N = 1416 = 5.53 blocks), ragged rows, a row-index indirection, targets outside [0, N) (entry untouched),
+    # and nothing written past row M.
+    rng = np.random.default_rng(31)
+    for (M, N, K, scale, indirect) in ((256, 256, 64, 1.0, False), (300, 1416, 192, 1.0, True), (37, 512, 128, 6.0, False)):
+        A = synth.to_storage(rng.normal(size=(M, K)) * scale, "bf16")
+        B = synth.to_storage(rng.normal(size=(N, K)), "bf16")
+        nb = (N + 255) // 256
+        n_src = M + 50
+        perm = rng.permutation(n_src)[:M].astype(np.int32) if indirect else None
+        tg_src = rng.integers(0, N, size=n_src if indirect else M).astype(np.int32)
+        tg_src[rng.integers(0, len(tg_src), size=3)] = [-1, N, N + 7]           # never used as an index
+        tgt = tg_src[perm] if indirect else tg_src
+        E = torch.full((M + 2, N), 3.0, device="cuda", dtype=torch.bfloat16)
+        stats = torch.full((M + 3, nb, 2), -7.0, device="cuda", dtype=torch.float32)
+        zt = torch.full((M + 3,), -5.0, device="cuda", dtype=torch.float32)
+        used = sb.debug_gemm_numerators(dev(A, "bf16"), dev(B, "bf16"), E[:M], stats, torch.from_numpy(tg_src).cuda(), zt,
+                                        row_index=None if perm is None else torch.from_numpy(perm).cuda())
+        torch.cuda.synchronize()
+        assert used == 1
+        c = A.astype(np.float64) @ B.astype(np.float64).T
+        cpad = np.full((M, nb * 256), -np.inf)
+        cpad[:, :N] = c
+        blocks = cpad.reshape(M, nb, 256)
+        bmax = blocks.max(axis=2)
+        bsum = np.exp(blocks - bmax[:, :, None]).sum(axis=2)
+        st = stats.cpu().numpy()
+        tol_c = 2e-5 * np.abs(c).max()
+        assert np.abs(st[:M, :, 0] - bmax).max() <= tol_c
+        assert np.allclose(st[:M, :, 1], bsum, rtol=1e-4 + 2 * tol_c, atol=0), np.abs(st[:M, :, 1] / bsum - 1).max()
+        assert np.all(st[M:] == -7.0), "statistics written past the last row"
+        want_e = np.exp(blocks - bmax[:, :, None]).reshape(M, nb * 256)[:, :N]
+        got_e = E[:M].float().cpu().numpy()
+        assert np.all(np.abs(got_e - want_e) <= 2.0 ** -8 * want_e + 2 * tol_c * want_e + 1e-30), np.abs(got_e - want_e).max()
+        assert torch.all(E[M:] == 3.0), "E written past the last row"
+        valid = (tgt >= 0) & (tgt < N)
+        got_zt = zt.cpu().numpy()
+        assert np.abs(got_zt[:M][valid] - c[np.arange(M)[valid], tgt[valid]]).max() <= tol_c
+        assert np.all(got_zt[:M][~valid] == -5.0) and np.all(got_zt[M:] == -5.0)
+    # a problem the MFMA kernel cannot take is refused (nothing written)
+    A = torch.zeros((64, 96), device="cuda", dtype=torch.bfloat16)
+    B = torch.zeros((104, 96), device="cuda", dtype=torch.bfloat16)
+    assert sb.debug_gemm_numerators(A, B, torch.zeros((64, 104), device="cuda", dtype=torch.bfloat16), torch.zeros((64, 1, 2), device="cuda"),
+                                    torch.zeros(64, dtype=torch.int32, device="cuda"), torch.zeros(64, device="cuda")) == 0

@@ -107,6 +107,22 @@ def test_optional_fusions_agree_with_the_oracle(mask):
         sb.debug_set_fusions(old)
 
 
+@pytest.mark.parametrize("mask", [2, 6])
+def test_head_with_and_without_softmax_numerators_from_the_logits_gemm(mask):
+    # fusion bit 2: the logits GEMM stores bf16 softmax numerators into the dz buffer (+ block statistics + target logits)
+    # and the row kernel finishes dz in place - against the oracle, every objective, fp32 and bf16 weight gradients, ragged
+    # chunks, ignored rows (compacted away), a vocabulary that ends in a ragged column block, and large-magnitude logits
+    old = sb.debug_set_fusions(mask)
+    try:
+        head_case(BIG16, 2, 300, 128, "sft", loss_scale=1.0 / 450)
+        head_case(MID16, 2, 600, 128, "grpo", grad_dtype="bf16")
+        head_case(MID16, 2, 333, 100, "grpo", kl_mode=1, old=synth.grpo_extras(2, 333, 0)["ref_logp"] + 0.3)
+        head_case(MID16, 2, 300, 256, "dpo")
+        head_case(RAG16, 1, 700, 256, "sft", loss_scale=1.0 / 525)
+    finally:
+        sb.debug_set_fusions(old)
+
+
 # widths that are multiples of 64 but not of the MFMA GEMMs' 256-wide output tile: every GEMM of the layer and of the head
 # ends in a ragged tile (q width 384, k/v width 128, hidden 320, MLP 448, vocabulary 1408 = 5.5 tiles)
 RAG16 = dict(dtype="bf16", hidden=320, n_q_heads=3, n_kv_heads=1, head_dim=128, mlp_width=448, vocab=1408)
