@@ -369,15 +369,19 @@ def main():
         out["config"]["same_step_with_first_25pct_of_positions_ignored"] = dict(
             ms_per_step=dt2 * 1e3, tokens_per_s=B * T / dt2, algorithmic_tflop_per_step=fl2["total"] / 1e12,
             achieved_tflops=fl2["total"] / dt2 / 1e12, frac_of_bf16_mfma_peak=fl2["total"] / dt2 / 1e12 / PEAK_BF16_TFLOPS)
-    # ---- context for the roofline fractions: what the matrix pipe sustains with NO memory traffic at all (eight independent
-    # MFMAs per wave and round on fixed fragments, two waves per SIMD).  The chip is power-managed, so the rate depends on the
-    # operand values: all-zero fragments reach the nominal peak, random ones (what every GEMM of the path multiplies) do not.
+    # ---- context for the roofline fractions: what the matrix pipe sustains with NO global memory traffic at all (eight
+    # independent MFMAs per wave and round, two waves per SIMD).  The chip is power-managed, so the rate depends on the operand
+    # values: all-zero fragments reach the nominal peak, random ones (what every GEMM of the path multiplies) do not - and
+    # less again when the fragments come from LDS the way the kernels' main loops fetch them (6 reads of 1 KB per 8 products
+    # in the GEMMs, 8 in the attention backward).
     if not args.no_profile and not args.no_mfma_probe:
         zeros = torch.zeros(32768, dtype=torch.bfloat16, device=dev)
         rnd = normal((32768,), 1.0)
         out["config"]["mfma_only_sustained_tflops"] = {
             "zero_operands": sb.debug_mfma_rate(zeros), "random_operands": sb.debug_mfma_rate(rnd),
-            "how": "streambp_debug_mfma_rate: 12 launches of 512 workgroups x 8 waves x 10000 rounds of 8 v_mfma_f32_32x32x16_bf16, no loads"}
+            "random_operands_6_lds_fragment_reads_per_8_mfma": sb.debug_mfma_rate(rnd, lds_reads=6),
+            "random_operands_8_lds_fragment_reads_per_8_mfma": sb.debug_mfma_rate(rnd, lds_reads=8),
+            "how": "streambp_debug_mfma_rate: 12 launches of 512 workgroups x 8 waves x 10000 rounds of 8 v_mfma_f32_32x32x16_bf16, no global loads"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(dict(synth.CONFIGS["7b"]))
     print(json.dumps(out))

@@ -63,13 +63,15 @@ int streambp_debug_profile_kinds(void);
 int streambp_debug_profile_begin(int max_records);
 int streambp_debug_profile_end(long long *count, double *ms, double *work, double *work_bounded);
 
-/* What the matrix pipe sustains with no memory traffic at all: `workgroups` workgroups of 8 wavefronts (two per SIMD) each
- * issue `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16 on operand fragments read once from `operands`
- * (device, 32768 bf16 values the caller filled: zeros, ones, random ...); the sums of the accumulators go to `sink`
- * (device, workgroups * 512 floats) so that nothing is optimised away.  2 * 32*32*16 * 8 * iters * 8 * workgroups flops
- * per launch.  On MI355X the rate depends on the operand VALUES (the chip is power-managed): the benchmark reports it
- * next to the GEMM rates as the ceiling real data leaves.  Returns 0, or -5 on a launch error. */
-int streambp_debug_mfma_rate(const void *operands, float *sink, int workgroups, int iters, void *hip_stream);
+/* What the matrix pipe sustains without global memory traffic: `workgroups` workgroups of 8 wavefronts (two per SIMD) each
+ * issue `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16 on operand fragments taken from `operands` (device,
+ * 32768 bf16 values the caller filled: zeros, ones, random ...); `lds_reads` (0, 6 or 8) of the eight A fragments of a round
+ * are re-read from LDS every round (1 KB per wave and read, conflict-free) - the GEMM main loop reads 6 fragments per 8
+ * products, the attention backward 8 - the rest stay in registers.  The sums of the accumulators go to `sink` (device,
+ * workgroups * 512 floats) so that nothing is optimised away.  2 * 32*32*16 * 8 * iters * 8 * workgroups flops per launch.
+ * On MI355X the rate depends on the operand VALUES (the chip is power-managed): the benchmark reports it next to the GEMM
+ * rates as the ceiling real data leaves.  Returns 0, -1 / -2 on a bad argument, -5 on a launch error. */
+int streambp_debug_mfma_rate(const void *operands, float *sink, int workgroups, int iters, int lds_reads, void *hip_stream);
 
 #ifdef __cplusplus
 }

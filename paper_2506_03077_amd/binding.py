@@ -153,7 +153,7 @@ def lib():
         L.streambp_debug_gemm_numerators.argtypes = [C.c_int, C.c_int, C.c_int, vp, vp, vp, C.c_longlong, C.c_longlong, C.c_longlong,
                                                      vp, vp, vp, vp, vp]
         L.streambp_debug_mfma_rate.restype = C.c_int
-        L.streambp_debug_mfma_rate.argtypes = [vp, vp, C.c_int, C.c_int, vp]
+        L.streambp_debug_mfma_rate.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, vp]
         _lib = L
     return _lib
 
@@ -489,14 +489,15 @@ def debug_gemm_numerators(A, B, E, stats, targets, target_value, row_index=None,
     return rc
 
 
-def debug_mfma_rate(operands, workgroups=512, iters=10000, repeats=12, stream=None):
+def debug_mfma_rate(operands, workgroups=512, iters=10000, repeats=12, lds_reads=0, stream=None):
     """TFLOP/s the matrix pipe sustains on fragments taken from `operands` (a bf16 device tensor of 32768 values: the rate
-    depends on the values) with no memory traffic: streambp_debug_mfma_rate timed with events on the launch stream.  The
+    depends on the values) with no global memory traffic, `lds_reads` (0, 6, 8) of every eight A fragments re-read from LDS:
+    streambp_debug_mfma_rate timed with events on the launch stream.  The
     default launches keep the chip busy for 0.1-0.15 s: the power management settles within the first tens of milliseconds."""
     import torch
     assert operands.dtype == torch.bfloat16 and operands.numel() == 32768 and operands.is_contiguous()
     sink = torch.empty(workgroups * 512, dtype=torch.float32, device=operands.device)
-    launch = lambda n: lib().streambp_debug_mfma_rate(_ptr(operands), _ptr(sink), workgroups, n, _stream(stream))
+    launch = lambda n: lib().streambp_debug_mfma_rate(_ptr(operands), _ptr(sink), workgroups, n, lds_reads, _stream(stream))
     if launch(max(1, iters // 10)) != 0:
         raise StreamBPError(-5, "debug_mfma_rate launch failed")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

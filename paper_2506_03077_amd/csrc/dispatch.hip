@@ -182,9 +182,10 @@ extern "C" int streambp_debug_gemm_numerators(int M, int N, int K, const void* A
   return sbp::gemm(g, (hipStream_t)stream) == hipSuccess ? 1 : -5;
 }
 
-extern "C" int streambp_debug_mfma_rate(const void* operands, float* sink, int workgroups, int iters, void* stream) {
+extern "C" int streambp_debug_mfma_rate(const void* operands, float* sink, int workgroups, int iters, int lds_reads, void* stream) {
   if (!operands || !sink) return -1;
-  return sbp::mfma_rate_probe(operands, sink, workgroups, iters, (hipStream_t)stream) == hipSuccess ? 0 : -5;
+  if (lds_reads != 0 && lds_reads != 6 && lds_reads != 8) return -2;
+  return sbp::mfma_rate_probe(operands, sink, workgroups, iters, lds_reads, (hipStream_t)stream) == hipSuccess ? 0 : -5;
 }
 
 // Per-launch timing with HIP events recorded on the launch stream around each GEMM kernel / attention launch

@@ -925,39 +925,49 @@ hipError_t gemm_mfma_seg(const GemmArgs* gs, int n, hipStream_t st) {
 }
 
 // ---- what the matrix pipe sustains on its own -------------------------------------------------------------
-// Eight independent 32x32x16 products per round on fragments that never change: no LDS, no memory traffic, two waves
-// per SIMD.  The rate depends on the VALUES of the fragments (power management), which is why the caller supplies them.
+// Eight independent 32x32x16 products per round, two waves per SIMD, no global memory traffic.  R of the eight A fragments
+// of a round are re-read from LDS (one conflict-free ds_read_b128 = 1 KB per wave each, the way the GEMM and attention
+// kernels feed their MFMAs: the GEMM main loop reads 6 fragments per 8 products, the attention backward 8); the others
+// and the B fragments never change.  The rate depends on the VALUES of the fragments (power management), which is why
+// the caller supplies them.
+template <int R>
 __global__ __launch_bounds__(NTHREADS) void mfma_rate_probe_k(const bf16x8* __restrict__ operands, float* __restrict__ sink, int iters) {
-  bf16x8 a[FM], b[FN];
+  __shared__ __attribute__((aligned(1024))) bf16x8 frag[R > 0 ? 2 * NTHREADS * 8 : 1];   // two rounds' worth: 128 KB
+  if (R > 0) {
+    for (int i = threadIdx.x; i < 2 * NTHREADS * 8; i += NTHREADS) frag[i] = operands[i % 4096];
+    __syncthreads();
+  }
+  const uint32_t base = lds_addr(&frag[0]) + (threadIdx.x & 63) * 16 + (threadIdx.x >> 6) * 8 * 1024;
+  bf16x8 a[8], b[2];
 #pragma unroll
-  for (int i = 0; i < FM; ++i) a[i] = operands[(threadIdx.x + i * NTHREADS) % 4096];
+  for (int i = 0; i < 8; ++i) a[i] = operands[(threadIdx.x + i * NTHREADS) % 4096];
 #pragma unroll
-  for (int j = 0; j < FN; ++j) b[j] = operands[(threadIdx.x + (FM + j) * NTHREADS) % 4096];
-  f32x16 acc[FM][FN];
+  for (int j = 0; j < 2; ++j) b[j] = operands[(threadIdx.x + (8 + j) * NTHREADS) % 4096];
+  f32x16 acc[8];
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
   for (int it = 0; it < iters; ++it) {
+    const uint32_t off = (uint32_t)(it & 1) * (NTHREADS * 8 * 16);
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < R; ++i) a[i] = lds_read_b128(base + off + i * 1024);
 #pragma unroll
-      for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[i & 1], acc[i], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s += acc[i][j][r];
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
   sink[(int64_t)blockIdx.x * NTHREADS + threadIdx.x] = s;
 }
-hipError_t mfma_rate_probe(const void* operands, float* sink, int workgroups, int iters, hipStream_t st) {
+hipError_t mfma_rate_probe(const void* operands, float* sink, int workgroups, int iters, int lds_reads, hipStream_t st) {
   if (workgroups <= 0 || iters < 0) return hipErrorInvalidValue;
-  mfma_rate_probe_k<<<workgroups, NTHREADS, 0, st>>>((const bf16x8*)operands, sink, iters);
+  if (lds_reads == 0) mfma_rate_probe_k<0><<<workgroups, NTHREADS, 0, st>>>((const bf16x8*)operands, sink, iters);
+  else if (lds_reads == 6) mfma_rate_probe_k<6><<<workgroups, NTHREADS, 0, st>>>((const bf16x8*)operands, sink, iters);
+  else if (lds_reads == 8) mfma_rate_probe_k<8><<<workgroups, NTHREADS, 0, st>>>((const bf16x8*)operands, sink, iters);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -119,8 +119,9 @@ hipError_t add_store(int dt, const float* a, const float* b, void* y, int64_t n,
 hipError_t kv_grad_finish(int dt, const float* dK, const float* dV, const float2* tab, void* dkc, void* dvc,
                           int rows, int H, int dh, hipStream_t st);
 hipError_t fill_zero(void* p, size_t bytes, hipStream_t st);
-// pure-MFMA rate probe: operands = 32768 bf16 values on the device, sink = workgroups * 512 floats
-hipError_t mfma_rate_probe(const void* operands, float* sink, int workgroups, int iters, hipStream_t st);
+// MFMA rate probe: operands = 32768 bf16 values on the device, sink = workgroups * 512 floats; lds_reads = 0, 6 or 8 of the
+// eight A fragments of a round re-read from LDS
+hipError_t mfma_rate_probe(const void* operands, float* sink, int workgroups, int iters, int lds_reads, hipStream_t st);
 hipError_t copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t st);     // 16-byte aligned, bytes % 16 == 0 fast path
 // dst [R2, C2] (dt, dense) = zero-padded scale * src, src [R, C] (dt, dense) or its transpose (src [C, R]) - small matrices
 hipError_t pad_matrix(int dt, const void* src, int R, int C, bool transposed, float scale, void* dst, int R2, int C2, hipStream_t st);

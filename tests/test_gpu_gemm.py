@@ -281,13 +281,15 @@ def test_mfma_rate_probe_counts_what_it_claims():
     # credited with: 2 * 32*32*16 * 8 products per wave and round)
     ones = torch.ones(32768, dtype=torch.bfloat16, device="cuda")
     sink = torch.full((4 * 512,), -1.0, dtype=torch.float32, device="cuda")
-    for n in (0, 1, 37):
-        rc = sb.lib().streambp_debug_mfma_rate(ones.data_ptr(), sink.data_ptr(), 4, n, torch.cuda.current_stream().cuda_stream)
+    for n, reads in ((0, 0), (1, 0), (37, 0), (37, 6), (37, 8)):     # fragments re-read from LDS hold the same ones
+        rc = sb.lib().streambp_debug_mfma_rate(ones.data_ptr(), sink.data_ptr(), 4, n, reads, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         assert rc == 0
-        assert torch.all(sink == 8 * 16 * 16 * n), n
-    assert sb.lib().streambp_debug_mfma_rate(None, sink.data_ptr(), 4, 1, None) == -1
+        assert torch.all(sink == 8 * 16 * 16 * n), (n, reads)
+    assert sb.lib().streambp_debug_mfma_rate(None, sink.data_ptr(), 4, 1, 0, None) == -1
+    assert sb.lib().streambp_debug_mfma_rate(ones.data_ptr(), sink.data_ptr(), 4, 1, 5, None) == -2
     assert sb.debug_mfma_rate(ones, workgroups=64, iters=100, repeats=1) > 0
+    assert sb.debug_mfma_rate(ones, workgroups=64, iters=100, repeats=1, lds_reads=8) > 0
 
 
 def test_softmax_numerators_from_the_store_epilogue():
